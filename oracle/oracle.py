@@ -1,0 +1,206 @@
+"""Python face of the CPU oracle (ctypes over oracle/libic_oracle.so) + the layer loop.
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg; never by the product package.  It imports nothing
+from the product package either.
+
+Array conventions (numpy, C-contiguous):
+  q   [B,Tq,H_I,d_I]  uint16 (bfloat16 bit patterns) or uint8 (e4m3 bytes)
+  k   [B,Lk,d_I]      same element type as q
+  w   [B,Tq,H_I]      float32
+  q_scale [B,Tq], k_scale [B,Lk] float32 (fp8 only)
+  Q   [B,Tq,H_q,d_qk] uint16 ; KV [B,Lk,row_elems] uint16
+  idx [B,Tq,k_sel]    int32, -1 padded
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+BF16, FP8_E4M3 = 0, 1
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = os.path.join(_HERE, "libic_oracle.so")
+        if not os.path.exists(path):
+            from . import build as _b
+            _b.build(force=True)
+        _LIB = C.CDLL(path)
+        _LIB.ico_widen_bf16.restype = C.c_double
+        _LIB.ico_widen_bf16.argtypes = [C.c_uint16]
+        _LIB.ico_widen_e4m3.restype = C.c_double
+        _LIB.ico_widen_e4m3.argtypes = [C.c_uint8]
+        _LIB.ico_num_threads.restype = C.c_int
+    return _LIB
+
+
+def num_threads():
+    return int(lib().ico_num_threads())
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _rows(rows):
+    if rows is None:
+        return None, 0
+    r = np.ascontiguousarray(np.asarray(rows, dtype=np.int32))
+    return r, int(r.size)
+
+
+def _check_indexer(q, k, w, dtype, q_scale, k_scale):
+    et = np.uint16 if dtype == BF16 else np.uint8
+    assert q.dtype == et and k.dtype == et, (q.dtype, k.dtype)
+    assert w.dtype == np.float32
+    assert q.ndim == 4 and k.ndim == 3 and w.ndim == 3
+    B, Tq, H, d = q.shape
+    assert k.shape[0] == B and k.shape[2] == d and w.shape == (B, Tq, H)
+    for a in (q, k, w):
+        assert a.flags.c_contiguous
+    if dtype == FP8_E4M3:
+        assert q_scale.dtype == np.float32 and q_scale.shape == (B, Tq)
+        assert k_scale.dtype == np.float32 and k_scale.shape == (B, k.shape[1])
+    return B, Tq, k.shape[1], H, d
+
+
+def indexer_scores(q, k, w, q_pos0, dtype=BF16, q_scale=None, k_scale=None, rows=None):
+    """I[b, r, s] in fp64 for the chosen query rows; hidden keys are -inf."""
+    B, Tq, Lk, H, d = _check_indexer(q, k, w, dtype, q_scale, k_scale)
+    r, n = _rows(rows)
+    n_rows = n if r is not None else Tq
+    out = np.empty((B, n_rows, Lk), dtype=np.float64)
+    rc = lib().ico_indexer_scores(C.c_int(dtype), _p(q), _p(k), _p(w), _p(q_scale), _p(k_scale),
+                                  C.c_int(B), C.c_int(Tq), C.c_int(Lk), C.c_int(H), C.c_int(d),
+                                  C.c_long(q_pos0), _p(r), C.c_int(n_rows), _p(out))
+    assert rc == 0, rc
+    return out
+
+
+def topk_row(scores, nv, k_sel):
+    """Top-k of one scored row (first nv entries visible)."""
+    scores = np.ascontiguousarray(scores, dtype=np.float64)
+    idx = np.empty(k_sel, dtype=np.int32)
+    sel = np.empty(k_sel, dtype=np.float64)
+    kth, nxt, ma = C.c_double(), C.c_double(), C.c_double()
+    rc = lib().ico_topk_row(_p(scores), C.c_int(nv), C.c_int(k_sel), _p(idx), _p(sel),
+                            C.byref(kth), C.byref(nxt), C.byref(ma))
+    assert rc == 0, rc
+    return dict(idx=idx, sel=sel, kth=kth.value, next=nxt.value, mean_abs=ma.value)
+
+
+def indexer_topk(q, k, w, q_pos0, k_sel, dtype=BF16, q_scale=None, k_scale=None, rows=None):
+    """Indexer + top-k.  Returns idx [B,n_rows,k_sel] (score-descending, ties lower
+    position first, -1 tail), sel (their fp64 scores), and per row: kth (last selected
+    score), next (best unselected score or -inf), mean_abs (mean |I| over visible keys)."""
+    B, Tq, Lk, H, d = _check_indexer(q, k, w, dtype, q_scale, k_scale)
+    r, n = _rows(rows)
+    n_rows = n if r is not None else Tq
+    idx = np.empty((B, n_rows, k_sel), dtype=np.int32)
+    sel = np.empty((B, n_rows, k_sel), dtype=np.float64)
+    kth = np.empty((B, n_rows), dtype=np.float64)
+    nxt = np.empty((B, n_rows), dtype=np.float64)
+    ma = np.empty((B, n_rows), dtype=np.float64)
+    rc = lib().ico_indexer_topk(C.c_int(dtype), _p(q), _p(k), _p(w), _p(q_scale), _p(k_scale),
+                                C.c_int(B), C.c_int(Tq), C.c_int(Lk), C.c_int(H), C.c_int(d),
+                                C.c_long(q_pos0), C.c_int(k_sel), _p(r), C.c_int(n_rows),
+                                _p(idx), _p(sel), _p(kth), _p(nxt), _p(ma))
+    assert rc == 0, rc
+    return dict(idx=idx, sel=sel, kth=kth, next=nxt, mean_abs=ma)
+
+
+def _check_attn(Q, KV, idx):
+    assert Q.dtype == np.uint16 and KV.dtype == np.uint16 and idx.dtype == np.int32
+    assert Q.ndim == 4 and KV.ndim == 3 and idx.ndim == 3
+    for a in (Q, KV, idx):
+        assert a.flags.c_contiguous
+    B, Tq, Hq, d_qk = Q.shape
+    assert KV.shape[0] == B and idx.shape[0] == B
+    return B, Tq, KV.shape[1], Hq, d_qk, KV.shape[2], idx.shape[2]
+
+
+def sparse_attn(Q, KV, idx, d_v, v_off, sm_scale, rows=None, idx_is_subset=False):
+    """Sparse MQA attention over the rows named by idx.  Returns (O fp64 [B,n,Hq,d_v], lse)."""
+    B, Tq, Lk, Hq, d_qk, row, k_sel = _check_attn(Q, KV, idx)
+    r, n = _rows(rows)
+    n_rows = n if r is not None else Tq
+    assert idx.shape[1] == (n_rows if idx_is_subset else Tq)
+    O = np.empty((B, n_rows, Hq, d_v), dtype=np.float64)
+    lse = np.empty((B, n_rows, Hq), dtype=np.float64)
+    rc = lib().ico_sparse_attn(_p(Q), _p(KV), _p(idx), C.c_int(B), C.c_int(Tq), C.c_int(Lk),
+                               C.c_int(Hq), C.c_int(d_qk), C.c_int(d_v), C.c_int(v_off),
+                               C.c_int(row), C.c_int(k_sel), C.c_double(sm_scale), _p(r),
+                               C.c_int(n_rows), C.c_int(1 if idx_is_subset else 0), _p(O), _p(lse))
+    assert rc == 0, rc
+    return O, lse
+
+
+def dense_causal_attn(Q, KV, d_v, v_off, sm_scale, q_pos0):
+    """Textbook causal softmax attention over every visible key (pin for sparse_attn)."""
+    assert Q.dtype == np.uint16 and KV.dtype == np.uint16
+    B, Tq, Hq, d_qk = Q.shape
+    Lk, row = KV.shape[1], KV.shape[2]
+    O = np.empty((B, Tq, Hq, d_v), dtype=np.float64)
+    rc = lib().ico_dense_causal_attn(_p(Q), _p(KV), C.c_int(B), C.c_int(Tq), C.c_int(Lk),
+                                     C.c_int(Hq), C.c_int(d_qk), C.c_int(d_v), C.c_int(v_off),
+                                     C.c_int(row), C.c_double(sm_scale), C.c_long(q_pos0), _p(O))
+    assert rc == 0, rc
+    return O
+
+
+# ---- pattern strings and the layer loop (Fig. 2, Sec. 3 Overview) -------------
+
+def pattern_from_string(s):
+    """'FSSF..' -> list of bools (True = Full).  The first layer must be F (Sec. 3 Overview)."""
+    mask = []
+    for ch in s:
+        if ch not in "FS":
+            raise ValueError("pattern characters must be F or S: %r" % ch)
+        mask.append(ch == "F")
+    if not mask or not mask[0]:
+        raise ValueError("the first layer must be F")
+    return mask
+
+
+def pattern_uniform(n, r):
+    """Uniform interleave: keep every r-th indexer, FSSSFSSS... for r = 4 (Sec. 3.1)."""
+    if n <= 0 or r <= 0:
+        raise ValueError("n and r must be positive")
+    return [(l % r) == 0 for l in range(n)]
+
+
+def source_layer(mask, l):
+    """f(l) = max{ j < l : c_j = F } for an S layer; l itself for an F layer."""
+    if mask[l]:
+        return l
+    for j in range(l - 1, -1, -1):
+        if mask[j]:
+            return j
+    raise ValueError("S layer with no preceding F layer")
+
+
+def forward_stack(layers, full_mask, k_sel, q_pos0, d_v, v_off, sm_scale, dtype=BF16):
+    """IndexCache inference loop (Fig. 2b) over attention-only layers.
+
+    layers: list of dicts with q,k,w (may be absent on S layers) and Q,KV.
+    F layer: T_cache <- Top-k(Indexer); S layer: T_cache untouched; then sparse attention
+    with the layer's own Q/KV and T_cache.  Returns (list of O, list of the idx each layer used,
+    number of indexer invocations)."""
+    if not full_mask or not full_mask[0]:
+        raise ValueError("the first layer must be F")
+    t_cache = None
+    outs, used, n_indexer = [], [], 0
+    for l, layer in enumerate(layers):
+        if full_mask[l]:
+            t_cache = indexer_topk(layer["q"], layer["k"], layer["w"], q_pos0, k_sel, dtype,
+                                   layer.get("q_scale"), layer.get("k_scale"))["idx"]
+            n_indexer += 1
+        O, _ = sparse_attn(layer["Q"], layer["KV"], t_cache, d_v, v_off, sm_scale)
+        outs.append(O)
+        used.append(t_cache)
+    return outs, used, n_indexer
