@@ -1,0 +1,181 @@
+/*
+ * indexcache.h -- C ABI of the MI355X (gfx950) IndexCache / DSA hot-path library.
+ *
+ * The library computes, on one GPU, the attention-side hot path of DeepSeek Sparse
+ * Attention with IndexCache's cross-layer index reuse:
+ *   (1) the causal lightning-indexer score  I[t,s] = sum_j w[t,j] * ReLU(q[t,j,:] . k[s,:])
+ *       ("multi-head ReLU-gated dot product" over all preceding tokens, paper Sec. 2.1;
+ *       score vector I_t of Sec. 3 Notation),
+ *   (2) the per-query index set T_t = Top-k(I_t) (Sec. 3 Notation),
+ *   (3) sparse core attention over exactly the selected rows (Sec. 2.1, MLA/MQA form),
+ *   (4) the inference loop of Fig. 2(b): Full layers run (1)+(2) and overwrite the cached
+ *       index tensor, Shared layers reuse it (Sec. 3 Overview).
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless the comment says "host".
+ *     Descriptors, masks and pattern strings are host memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued asynchronously on it; no call synchronises the device.
+ *   - The caller owns every buffer, including the workspace; the library never allocates,
+ *     frees or keeps device memory.  Inputs are read-only, outputs are fully overwritten.
+ *   - Arguments are validated on the host before anything is launched; on error nothing has
+ *     been enqueued, a status is returned and ic_last_error() describes it.  Nothing aborts.
+ *   - Causality: key s of a sequence is visible to query row i iff s <= q_pos0 + i and
+ *     s < Lk (inclusive causal mask).  Prefill: Tq = Lk, q_pos0 = 0.  Decode: Tq = 1,
+ *     q_pos0 = Lk - 1 (the new token's key is already in the cache).
+ */
+#ifndef INDEXCACHE_H
+#define INDEXCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ic_status {
+    IC_OK = 0,
+    IC_ERR_NULL = 1,        /* a required pointer is NULL */
+    IC_ERR_SHAPE = 2,       /* a size is non-positive, inconsistent or overflows int32 indexing */
+    IC_ERR_UNSUPPORTED = 3, /* dtype / head count / head dim / k_sel outside what the kernels cover */
+    IC_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned (256 B) or smaller than *_workspace() */
+    IC_ERR_PATTERN = 5,     /* layer pattern invalid: the first layer must be Full (Sec. 3 Overview) */
+    IC_ERR_HIP = 6          /* a HIP runtime call or kernel launch failed */
+} ic_status;
+
+typedef enum ic_dtype {
+    IC_BF16 = 0,     /* bfloat16 q and k */
+    IC_FP8_E4M3 = 1  /* OCP e4m3 q and k with one fp32 scale per token */
+} ic_dtype;
+
+#define IC_MAX_K 2048       /* largest supported k_sel */
+#define IC_MAX_HEADS_I 64   /* largest supported number of indexer heads */
+#define IC_MAX_HEADS_Q 32   /* largest supported number of attention query heads */
+
+/* One indexer + top-k problem over B independent sequences. */
+typedef struct ic_indexer_desc {
+    int32_t B;        /* sequences */
+    int32_t Tq;       /* query rows per sequence */
+    int32_t Lk;       /* keys per sequence */
+    int32_t H_I;      /* indexer heads, 1..IC_MAX_HEADS_I */
+    int32_t d_I;      /* indexer head dim: 64 or 128 */
+    int32_t k_sel;    /* k of Top-k, 1..IC_MAX_K */
+    int64_t q_pos0;   /* absolute position of query row 0 */
+    int32_t dtype;    /* ic_dtype of q and k */
+    uint32_t flags;   /* reserved, must be 0 */
+    const float *q_scale; /* [B,Tq] device, fp8 only (else NULL): q = q8 * q_scale */
+    const float *k_scale; /* [B,Lk] device, fp8 only (else NULL): k = k8 * k_scale */
+} ic_indexer_desc;
+
+/* Bytes of workspace ic_indexer_topk needs for this problem (0 on an invalid descriptor).
+ * The workspace holds a strip of score rows for the query rows in flight (never Tq x Lk for
+ * long sequences); a larger workspace is accepted and lets more rows fly per launch. */
+size_t ic_indexer_topk_workspace(const ic_indexer_desc *desc);
+
+/*
+ * Indexer score + per-query top-k (Sec. 2.1; Sec. 3 Notation: T_t = Top-k(I_t)).
+ *   q   [B,Tq,H_I,d_I]  bf16 (or e4m3 bytes)     k [B,Lk,d_I] same type     w [B,Tq,H_I] fp32
+ *   idx [B,Tq,k_sel] int32 out: the n = min(visible keys, k_sel) best positions of each query
+ *       row in ASCENDING position order, the tail filled with -1.  Equal scores are
+ *       resolved towards the lower position.
+ *   sel_scores [B,Tq,k_sel] fp32 out, nullable: I[t, idx] aligned with idx (tail: -inf).
+ */
+ic_status ic_indexer_topk(const ic_indexer_desc *desc, const void *q, const void *k, const float *w,
+                          int32_t *idx, float *sel_scores,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* One sparse-attention problem (MQA: all H_q heads share the single KV row of a position). */
+typedef struct ic_attn_desc {
+    int32_t B;          /* sequences */
+    int32_t Tq;         /* query rows per sequence */
+    int32_t Lk;         /* KV rows per sequence */
+    int32_t H_q;        /* query heads, 1..IC_MAX_HEADS_Q */
+    int32_t d_qk;       /* logits use KV[row, 0:d_qk]          (supported: 576 or 64) */
+    int32_t d_v;        /* values are KV[row, v_off:v_off+d_v] (supported: 512 or 64) */
+    int32_t v_off;      /* multiple of 8 */
+    int32_t row_elems;  /* elements per KV row, >= max(d_qk, v_off + d_v), multiple of 8 */
+    int32_t k_sel;      /* entries per query row in idx */
+    float sm_scale;     /* logit scale (the paper leaves it to the model; 1/sqrt(d_qk) is usual) */
+} ic_attn_desc;
+
+size_t ic_sparse_attn_workspace(const ic_attn_desc *desc);
+
+/*
+ * Sparse core attention over the selected rows only (Sec. 2.1).
+ *   Q  [B,Tq,H_q,d_qk] bf16     KV [B,Lk,row_elems] bf16     idx [B,Tq,k_sel] int32
+ *   For each (b,t,h): z_m = sm_scale * <Q[b,t,h,:], KV[b,idx_m,0:d_qk]> over the entries with
+ *   0 <= idx_m < Lk (others are skipped), p = softmax(z), O[b,t,h,:] = sum_m p_m KV[b,idx_m,v_off:+d_v].
+ *   O   [B,Tq,H_q,d_v] bf16 out (a row with no valid entry gives zeros)
+ *   lse [B,Tq,H_q] fp32 out, nullable: log sum_m exp(z_m) (-inf for an empty row)
+ */
+ic_status ic_sparse_attn(const ic_attn_desc *desc, const void *Q, const void *KV, const int32_t *idx,
+                         void *O, float *lse, void *workspace, size_t workspace_bytes, void *stream);
+
+/* One attention layer of the stack: its indexer problem and its attention problem. */
+typedef struct ic_layer {
+    ic_indexer_desc ix;
+    const void *q;      /* indexer inputs; may be NULL on Shared layers */
+    const void *k;
+    const float *w;
+    ic_attn_desc at;
+    const void *Q;      /* the layer's own attention inputs, used on Full and Shared layers alike */
+    const void *KV;
+    void *O;            /* [B,Tq,H_q,d_v] bf16 out */
+} ic_layer;
+
+/* Workspace for ic_forward_stack = the largest per-layer need (layers is host memory). */
+size_t ic_forward_stack_workspace(const ic_layer *layers, int32_t n_layers);
+
+/*
+ * IndexCache inference loop (Fig. 2b; all-ones full_mask gives standard DSA, Fig. 2a).
+ *   layers    host array of n_layers descriptors; every layer must agree on B, Tq and k_sel
+ *   full_mask host array, 1 = Full (run the indexer, overwrite idx_cache), 0 = Shared (reuse
+ *             idx_cache as the nearest preceding Full layer left it); full_mask[0] must be 1
+ *   idx_cache [B,Tq,k_sel] int32 device, caller-owned: the paper's T_cache, the only index
+ *             buffer of the pass; on return it holds the last Full layer's indices
+ * Every layer then runs sparse attention on its own Q/KV with idx_cache.  At most two kernel
+ * groups per layer are enqueued on `stream`, with no host synchronisation in between.
+ */
+ic_status ic_forward_stack(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask,
+                           int32_t *idx_cache, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Host-only helpers for the pattern string c = c_1..c_N in {F,S}^N (Sec. 3 Overview). */
+ic_status ic_pattern_from_string(const char *fs, uint8_t *full_mask, int32_t n);
+/* Uniform interleave: F at layers l with l % r == 0, "FSSSFSSS.." for r = 4 (Sec. 3.1). */
+ic_status ic_pattern_uniform(int32_t n, int32_t r, uint8_t *full_mask);
+
+/* Message for the last error on the calling thread ("" if none). Host string, do not free. */
+const char *ic_last_error(void);
+
+/*
+ * Parity aid: the raw indexer scores of query rows [row0, row0+n_rows) of every sequence,
+ * computed by the same scoring kernel the top-k path uses.
+ *   out [B,n_rows,Lk] fp32 device; keys hidden by the causal mask are -inf.
+ */
+ic_status ic_debug_indexer_scores(const ic_indexer_desc *desc, const void *q, const void *k,
+                                  const float *w, int32_t row0, int32_t n_rows, float *out,
+                                  void *stream);
+
+/* Number of ic_indexer_topk problems launched by this process so far (for the
+ * "indexer runs exactly on the Full layers" invariant). */
+uint64_t ic_debug_indexer_launch_count(void);
+
+/*
+ * Per-kernel timing with HIP events recorded on the launch stream (a measuring aid; off by
+ * default).  ic_prof_enable(1) starts recording an event pair around every kernel launch
+ * (bounded pool of 8192 pairs; launches beyond it are not recorded), ic_prof_enable(0) stops.
+ * ic_prof_collect waits for the recorded events (host-blocking) and adds their durations to
+ * per-class totals; ic_prof_get reads the totals of kernel class `which`
+ * (0 = indexer score, 1 = top-k select, 2 = sparse attention, 3 = attention split merge):
+ * number of launches and summed duration in milliseconds; ic_prof_reset zeroes the totals.
+ */
+void ic_prof_enable(int32_t on);
+ic_status ic_prof_collect(void);
+ic_status ic_prof_get(int32_t which, int64_t *launches, double *total_ms);
+void ic_prof_reset(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INDEXCACHE_H */

@@ -1,0 +1,16 @@
+"""MI355X-native IndexCache / DeepSeek-Sparse-Attention hot path.
+
+Thin Python binding (argument marshalling only) over libindexcache.so, the hand-written
+HIP library declared in include/indexcache.h.  Every step of the path runs in that library;
+there is no CPU or PyTorch fallback: if the library is missing, loading fails loudly.
+PyTorch is used for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    IcError, Status, lib, lib_path, last_error,
+    indexer_topk, indexer_topk_workspace, sparse_attn, sparse_attn_workspace,
+    forward_stack, forward_stack_workspace, make_layers,
+    pattern_from_string, pattern_uniform,
+    debug_indexer_scores, debug_indexer_launch_count,
+    prof_enable, prof_collect, prof_get, prof_reset,
+    IndexerDesc, AttnDesc, Layer,
+)

@@ -1,0 +1,268 @@
+"""ctypes binding of include/indexcache.h.  Same names as the C entry points, marshalling only."""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+BF16, FP8_E4M3 = 0, 1
+
+
+class Status:
+    OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_PATTERN, ERR_HIP = range(7)
+
+
+class IcError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("ic_status %d: %s" % (status, msg))
+        self.status = status
+
+
+class IndexerDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Tq", C.c_int32), ("Lk", C.c_int32), ("H_I", C.c_int32),
+                ("d_I", C.c_int32), ("k_sel", C.c_int32), ("q_pos0", C.c_int64),
+                ("dtype", C.c_int32), ("flags", C.c_uint32),
+                ("q_scale", C.c_void_p), ("k_scale", C.c_void_p)]
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Tq", C.c_int32), ("Lk", C.c_int32), ("H_q", C.c_int32),
+                ("d_qk", C.c_int32), ("d_v", C.c_int32), ("v_off", C.c_int32),
+                ("row_elems", C.c_int32), ("k_sel", C.c_int32), ("sm_scale", C.c_float)]
+
+
+class Layer(C.Structure):
+    _fields_ = [("ix", IndexerDesc), ("q", C.c_void_p), ("k", C.c_void_p), ("w", C.c_void_p),
+                ("at", AttnDesc), ("Q", C.c_void_p), ("KV", C.c_void_p), ("O", C.c_void_p)]
+
+
+def lib_path():
+    return os.path.join(_HERE, "libindexcache.so")
+
+
+def lib():
+    """Load libindexcache.so.  No fallback: a missing library is an error."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise IcError(-1, "libindexcache.so is not built (run paper_2603_12201_amd/build.py "
+                              "or __graft_entry__.build()); there is no fallback path")
+        L = C.CDLL(path)
+        vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32
+        L.ic_last_error.restype = C.c_char_p
+        L.ic_indexer_topk_workspace.restype = sz
+        L.ic_indexer_topk_workspace.argtypes = [C.POINTER(IndexerDesc)]
+        L.ic_indexer_topk.restype = C.c_int
+        L.ic_indexer_topk.argtypes = [C.POINTER(IndexerDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ic_sparse_attn_workspace.restype = sz
+        L.ic_sparse_attn_workspace.argtypes = [C.POINTER(AttnDesc)]
+        L.ic_sparse_attn.restype = C.c_int
+        L.ic_sparse_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ic_forward_stack_workspace.restype = sz
+        L.ic_forward_stack_workspace.argtypes = [C.POINTER(Layer), i32]
+        L.ic_forward_stack.restype = C.c_int
+        L.ic_forward_stack.argtypes = [C.POINTER(Layer), i32, C.c_char_p, vp, vp, sz, vp]
+        L.ic_pattern_from_string.restype = C.c_int
+        L.ic_pattern_from_string.argtypes = [C.c_char_p, C.c_char_p, i32]
+        L.ic_pattern_uniform.restype = C.c_int
+        L.ic_pattern_uniform.argtypes = [i32, i32, C.c_char_p]
+        L.ic_debug_indexer_scores.restype = C.c_int
+        L.ic_debug_indexer_scores.argtypes = [C.POINTER(IndexerDesc), vp, vp, vp, i32, i32, vp, vp]
+        L.ic_debug_indexer_launch_count.restype = C.c_uint64
+        L.ic_prof_enable.restype = None
+        L.ic_prof_enable.argtypes = [i32]
+        L.ic_prof_collect.restype = C.c_int
+        L.ic_prof_get.restype = C.c_int
+        L.ic_prof_get.argtypes = [i32, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        L.ic_prof_reset.restype = None
+        _LIB = L
+    return _LIB
+
+
+def last_error():
+    return lib().ic_last_error().decode()
+
+
+def _check(rc):
+    if rc != 0:
+        raise IcError(rc, last_error())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float8_e4m3fn:
+        return FP8_E4M3
+    raise IcError(Status.ERR_UNSUPPORTED, "q/k dtype %s is not bf16 or float8_e4m3fn" % t.dtype)
+
+
+def _need(t, name, dtype=None, ndim=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise IcError(Status.ERR_NULL, "%s must be a CUDA(HIP) tensor" % name)
+    if not t.is_contiguous():
+        raise IcError(Status.ERR_SHAPE, "%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise IcError(Status.ERR_SHAPE, "%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if ndim is not None and t.dim() != ndim:
+        raise IcError(Status.ERR_SHAPE, "%s must have %d dims" % (name, ndim))
+
+
+def indexer_desc(q, k, w, k_sel, q_pos0, q_scale=None, k_scale=None):
+    import torch
+    _need(q, "q", ndim=4)
+    _need(k, "k", q.dtype, 3)
+    _need(w, "w", torch.float32, 3)
+    B, Tq, H, d = q.shape
+    if k.shape[0] != B or k.shape[2] != d or tuple(w.shape) != (B, Tq, H):
+        raise IcError(Status.ERR_SHAPE, "q %s, k %s, w %s disagree" % (tuple(q.shape), tuple(k.shape), tuple(w.shape)))
+    code = _dtype_code(q)
+    if code == FP8_E4M3:
+        _need(q_scale, "q_scale", torch.float32, 2)
+        _need(k_scale, "k_scale", torch.float32, 2)
+    return IndexerDesc(B, Tq, k.shape[1], H, d, k_sel, q_pos0, code, 0,
+                       q_scale.data_ptr() if q_scale is not None else None,
+                       k_scale.data_ptr() if k_scale is not None else None)
+
+
+def attn_desc(Q, KV, idx, d_v, v_off, sm_scale):
+    import torch
+    _need(Q, "Q", torch.bfloat16, 4)
+    _need(KV, "KV", torch.bfloat16, 3)
+    _need(idx, "idx", torch.int32, 3)
+    B, Tq, Hq, d_qk = Q.shape
+    if KV.shape[0] != B or idx.shape[0] != B or idx.shape[1] != Tq:
+        raise IcError(Status.ERR_SHAPE, "Q %s, KV %s, idx %s disagree" % (tuple(Q.shape), tuple(KV.shape), tuple(idx.shape)))
+    return AttnDesc(B, Tq, KV.shape[1], Hq, d_qk, d_v, v_off, KV.shape[2], idx.shape[2], sm_scale)
+
+
+def _workspace(nbytes, like):
+    import torch
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=like.device)
+
+
+def indexer_topk_workspace(desc):
+    return int(lib().ic_indexer_topk_workspace(C.byref(desc)))
+
+
+def indexer_topk(q, k, w, k_sel, q_pos0=0, q_scale=None, k_scale=None, want_scores=False,
+                 workspace=None, stream=None, idx=None):
+    """ic_indexer_topk: returns idx [B,Tq,k_sel] int32 (ascending positions, -1 tail) and,
+    if want_scores, sel_scores [B,Tq,k_sel] fp32."""
+    import torch
+    d = indexer_desc(q, k, w, k_sel, q_pos0, q_scale, k_scale)
+    if workspace is None:
+        need = indexer_topk_workspace(d)
+        if need == 0:
+            raise IcError(Status.ERR_UNSUPPORTED, last_error())
+        workspace = _workspace(need, q)
+    if idx is None:
+        idx = torch.empty((d.B, d.Tq, k_sel), dtype=torch.int32, device=q.device)
+    sel = torch.empty((d.B, d.Tq, k_sel), dtype=torch.float32, device=q.device) if want_scores else None
+    _check(lib().ic_indexer_topk(C.byref(d), _ptr(q), _ptr(k), _ptr(w), _ptr(idx), _ptr(sel),
+                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return (idx, sel) if want_scores else idx
+
+
+def sparse_attn_workspace(desc):
+    return int(lib().ic_sparse_attn_workspace(C.byref(desc)))
+
+
+def sparse_attn(Q, KV, idx, d_v, v_off, sm_scale, want_lse=False, workspace=None, stream=None, out=None):
+    """ic_sparse_attn: returns O [B,Tq,H_q,d_v] bf16 (and lse [B,Tq,H_q] fp32 if want_lse)."""
+    import torch
+    d = attn_desc(Q, KV, idx, d_v, v_off, sm_scale)
+    if workspace is None:
+        workspace = _workspace(sparse_attn_workspace(d), Q)
+    O = out if out is not None else torch.empty((d.B, d.Tq, d.H_q, d_v), dtype=torch.bfloat16, device=Q.device)
+    lse = torch.empty((d.B, d.Tq, d.H_q), dtype=torch.float32, device=Q.device) if want_lse else None
+    _check(lib().ic_sparse_attn(C.byref(d), _ptr(Q), _ptr(KV), _ptr(idx), _ptr(O), _ptr(lse),
+                                _ptr(workspace), workspace.numel(), _stream(stream)))
+    return (O, lse) if want_lse else O
+
+
+def make_layers(layers, k_sel, q_pos0, d_v, v_off, sm_scale, outs):
+    """Build the host array of ic_layer from per-layer tensor dicts (q,k,w may be absent on
+    Shared layers) and output tensors.  The returned object keeps the tensors alive."""
+    arr = (Layer * len(layers))()
+    keep = []
+    for l, (t, O) in enumerate(zip(layers, outs)):
+        Q, KV = t["Q"], t["KV"]
+        B, Tq, Hq, d_qk = Q.shape
+        arr[l].at = AttnDesc(B, Tq, KV.shape[1], Hq, d_qk, d_v, v_off, KV.shape[2], k_sel, sm_scale)
+        arr[l].Q, arr[l].KV, arr[l].O = Q.data_ptr(), KV.data_ptr(), O.data_ptr()
+        if t.get("q") is not None:
+            arr[l].ix = indexer_desc(t["q"], t["k"], t["w"], k_sel, q_pos0, t.get("q_scale"), t.get("k_scale"))
+            arr[l].q, arr[l].k, arr[l].w = t["q"].data_ptr(), t["k"].data_ptr(), t["w"].data_ptr()
+        keep.append((t, O))
+    arr._keep = keep
+    return arr
+
+
+def forward_stack_workspace(layer_arr):
+    return int(lib().ic_forward_stack_workspace(layer_arr, len(layer_arr)))
+
+
+def forward_stack(layer_arr, full_mask, idx_cache, workspace, stream=None):
+    """ic_forward_stack over a host array built by make_layers.  full_mask: bytes / list of 0/1."""
+    mask = bytes(bytearray(int(bool(m)) for m in full_mask))
+    if len(mask) != len(layer_arr):
+        raise IcError(Status.ERR_SHAPE, "full_mask has %d entries for %d layers" % (len(mask), len(layer_arr)))
+    _check(lib().ic_forward_stack(layer_arr, len(layer_arr), mask, _ptr(idx_cache),
+                                  _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def pattern_from_string(fs):
+    buf = C.create_string_buffer(max(len(fs), 1))
+    _check(lib().ic_pattern_from_string(fs.encode(), buf, len(fs)))
+    return [b != 0 for b in buf.raw[:len(fs)]]
+
+
+def pattern_uniform(n, r):
+    buf = C.create_string_buffer(max(n, 1))
+    _check(lib().ic_pattern_uniform(n, r, buf))
+    return [b != 0 for b in buf.raw[:n]]
+
+
+def debug_indexer_scores(q, k, w, q_pos0, row0, n_rows, q_scale=None, k_scale=None, stream=None):
+    """ic_debug_indexer_scores: fp32 [B,n_rows,Lk], hidden keys -inf."""
+    import torch
+    d = indexer_desc(q, k, w, 1, q_pos0, q_scale, k_scale)
+    out = torch.empty((d.B, n_rows, d.Lk), dtype=torch.float32, device=q.device)
+    _check(lib().ic_debug_indexer_scores(C.byref(d), _ptr(q), _ptr(k), _ptr(w), row0, n_rows,
+                                         _ptr(out), _stream(stream)))
+    return out
+
+
+def debug_indexer_launch_count():
+    return int(lib().ic_debug_indexer_launch_count())
+
+
+def prof_enable(on):
+    lib().ic_prof_enable(1 if on else 0)
+
+
+def prof_collect():
+    _check(lib().ic_prof_collect())
+
+
+def prof_get(which):
+    n, ms = C.c_int64(), C.c_double()
+    _check(lib().ic_prof_get(which, C.byref(n), C.byref(ms)))
+    return n.value, ms.value
+
+
+def prof_reset():
+    lib().ic_prof_reset()

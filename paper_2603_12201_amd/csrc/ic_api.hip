@@ -1,0 +1,472 @@
+// C ABI of the library: argument validation, workspace planning, the Full/Shared layer loop
+// (paper Fig. 2b) and optional per-kernel event timing.  All device work is enqueued on the
+// caller's stream; nothing here allocates device memory or synchronises in the hot path.
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "ic_common.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+ic_status fail(ic_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+std::atomic<uint64_t> g_indexer_launches{0};
+
+// ---- per-kernel event timing -------------------------------------------------------------
+constexpr int kProfClasses = 4;
+constexpr size_t kProfPool = 8192;
+struct ProfRec {
+    hipEvent_t e0, e1;
+    int which;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+int64_t g_prof_n[kProfClasses] = {0, 0, 0, 0};
+double g_prof_ms[kProfClasses] = {0, 0, 0, 0};
+
+struct ProfScope {
+    hipStream_t st;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int which;
+    bool live = false;
+    ProfScope(int which_, hipStream_t st_) : st(st_), which(which_)
+    {
+        if (!g_prof_on) return;
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        if (g_prof_recs.size() >= kProfPool) return;
+        if (hipEventCreate(&e0) != hipSuccess) return;
+        if (hipEventCreate(&e1) != hipSuccess) {
+            hipEventDestroy(e0);
+            return;
+        }
+        live = true;
+        hipEventRecord(e0, st);
+    }
+    ~ProfScope()
+    {
+        if (!live) return;
+        hipEventRecord(e1, st);
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof_recs.push_back(ProfRec{e0, e1, which});
+    }
+};
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Default strip budget when the caller asks how much workspace to bring.
+constexpr size_t kStripBudget = (size_t)1 << 30;   // 1 GiB of score rows in flight
+constexpr int kMinStripRows = 16;
+
+ic_status check_indexer(const ic_indexer_desc *d)
+{
+    if (!d) return fail(IC_ERR_NULL, "indexer descriptor is NULL");
+    if (d->B <= 0 || d->Tq <= 0 || d->Lk <= 0 || d->H_I <= 0 || d->d_I <= 0 || d->k_sel <= 0)
+        return fail(IC_ERR_SHAPE, "indexer sizes must be positive (B=%d Tq=%d Lk=%d H_I=%d d_I=%d k_sel=%d)",
+                    d->B, d->Tq, d->Lk, d->H_I, d->d_I, d->k_sel);
+    if (d->k_sel > IC_MAX_K) return fail(IC_ERR_UNSUPPORTED, "k_sel=%d exceeds IC_MAX_K=%d", d->k_sel, IC_MAX_K);
+    if (d->flags != 0) return fail(IC_ERR_UNSUPPORTED, "indexer flags must be 0");
+    if (d->dtype != IC_BF16 && d->dtype != IC_FP8_E4M3) return fail(IC_ERR_UNSUPPORTED, "unknown dtype %d", d->dtype);
+    if (!ic::score_shape_supported(d->dtype, d->H_I, d->d_I))
+        return fail(IC_ERR_UNSUPPORTED, "indexer shape not covered: dtype=%d H_I=%d d_I=%d (bf16, H_I<=64, d_I in {64,128})",
+                    d->dtype, d->H_I, d->d_I);
+    if ((int64_t)d->B * d->Tq > INT32_MAX / 2 || (int64_t)d->B * d->Tq * d->k_sel > ((int64_t)1 << 40))
+        return fail(IC_ERR_SHAPE, "B*Tq too large");
+    if (d->q_pos0 < -(int64_t)d->Tq || d->q_pos0 > ((int64_t)1 << 40))
+        return fail(IC_ERR_SHAPE, "q_pos0 out of range");
+    if (d->dtype == IC_FP8_E4M3 && (!d->q_scale || !d->k_scale))
+        return fail(IC_ERR_NULL, "fp8 indexer needs q_scale and k_scale");
+    return IC_OK;
+}
+
+size_t strip_ld(const ic_indexer_desc *d) { return ((size_t)d->Lk + 63) / 64 * 64; }
+
+// Rows of the strip a workspace of `bytes` can hold.
+int64_t strip_rows(const ic_indexer_desc *d, size_t bytes) { return (int64_t)(bytes / (strip_ld(d) * sizeof(float))); }
+
+ic_status check_attn(const ic_attn_desc *d)
+{
+    if (!d) return fail(IC_ERR_NULL, "attention descriptor is NULL");
+    if (d->B <= 0 || d->Tq <= 0 || d->Lk <= 0 || d->H_q <= 0 || d->d_qk <= 0 || d->d_v <= 0 || d->k_sel <= 0 ||
+        d->row_elems <= 0 || d->v_off < 0)
+        return fail(IC_ERR_SHAPE, "attention sizes must be positive");
+    if (d->H_q > IC_MAX_HEADS_Q) return fail(IC_ERR_UNSUPPORTED, "H_q=%d exceeds %d", d->H_q, IC_MAX_HEADS_Q);
+    if (!ic::attn_shape_supported(d->d_qk, d->d_v))
+        return fail(IC_ERR_UNSUPPORTED, "attention head dims not covered: d_qk=%d d_v=%d ((576,512) or (64,64))", d->d_qk, d->d_v);
+    if (d->v_off % 8 != 0 || d->row_elems % 8 != 0)
+        return fail(IC_ERR_SHAPE, "v_off and row_elems must be multiples of 8");
+    const int staged = d->d_qk == 576 ? 576 : 128;   // features of a row the kernel stages
+    if (d->v_off + d->d_v > staged || d->row_elems < staged)
+        return fail(IC_ERR_UNSUPPORTED, "KV row layout not covered: need v_off+d_v <= %d <= row_elems", staged);
+    if ((int64_t)d->B * d->Tq > INT32_MAX / 2) return fail(IC_ERR_SHAPE, "B*Tq too large");
+    if (!(d->sm_scale > 0.f) || d->sm_scale > 1e6f) return fail(IC_ERR_SHAPE, "sm_scale must be positive and finite");
+    return IC_OK;
+}
+
+// Key-slot splits per query: one workgroup per query when there are enough queries to fill the
+// chip, otherwise split the k_sel slots so that about 256 workgroups exist.
+void attn_splits(const ic_attn_desc *d, int *n_splits, int *split_len)
+{
+    const int64_t nq = (int64_t)d->B * d->Tq;
+    const int tiles = (d->k_sel + 63) / 64;
+    int64_t want = nq >= 256 ? 1 : (256 + nq - 1) / nq;
+    if (want > tiles) want = tiles;
+    const int tiles_per = (int)((tiles + want - 1) / want);
+    *split_len = tiles_per * 64;
+    *n_splits = (tiles + tiles_per - 1) / tiles_per;
+}
+
+size_t attn_ws_bytes(const ic_attn_desc *d)
+{
+    int ns, sl;
+    attn_splits(d, &ns, &sl);
+    if (ns <= 1) return 0;
+    const size_t nq = (size_t)d->B * d->Tq;
+    return align_up(nq * ns * d->H_q * d->d_v * sizeof(float)) + align_up(nq * ns * d->H_q * 2 * sizeof(float));
+}
+
+ic_status run_indexer(const ic_indexer_desc *d, const void *q, const void *k, const float *w, int32_t *idx,
+                      float *sel, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    const int64_t rows_cap = strip_rows(d, ws_bytes);
+    const int Ri = (int)(d->Tq < rows_cap ? d->Tq : rows_cap);
+    int64_t bc64 = rows_cap / Ri;
+    const int Bc = (int)(bc64 < 1 ? 1 : (bc64 > d->B ? d->B : bc64));
+    ic::ScoreArgs sa;
+    memset(&sa, 0, sizeof sa);
+    sa.q = q;
+    sa.k = k;
+    sa.w = w;
+    sa.q_scale = d->q_scale;
+    sa.k_scale = d->k_scale;
+    sa.strip = (float *)ws;
+    sa.ld = (int64_t)strip_ld(d);
+    sa.q_pos0 = d->q_pos0;
+    sa.Tq = d->Tq;
+    sa.Lk = d->Lk;
+    sa.H_I = d->H_I;
+    ic::SelectArgs se;
+    memset(&se, 0, sizeof se);
+    se.strip = (const float *)ws;
+    se.ld = sa.ld;
+    se.q_pos0 = d->q_pos0;
+    se.Tq = d->Tq;
+    se.Lk = d->Lk;
+    se.k_sel = d->k_sel;
+    se.idx = idx;
+    se.sel = sel;
+    for (int b0 = 0; b0 < d->B; b0 += Bc) {
+        const int bc = d->B - b0 < Bc ? d->B - b0 : Bc;
+        for (int i0 = 0; i0 < d->Tq; i0 += Ri) {
+            const int ri = d->Tq - i0 < Ri ? d->Tq - i0 : Ri;
+            sa.b0 = b0;
+            sa.i0 = i0;
+            sa.Ri = ri;
+            int64_t max_vis = d->q_pos0 + i0 + ri;
+            max_vis = max_vis < 0 ? 0 : (max_vis > d->Lk ? d->Lk : max_vis);
+            if (max_vis > d->k_sel || sel) {   // rows with <= k_sel visible keys need no scores
+                ProfScope ps(0, st);
+                hipError_t e = ic::launch_score(sa, d->dtype, d->d_I, bc, st);
+                if (e != hipSuccess) return fail(IC_ERR_HIP, "indexer score launch failed: %s", hipGetErrorString(e));
+            }
+            se.b0 = b0;
+            se.i0 = i0;
+            se.Ri = ri;
+            {
+                ProfScope ps(1, st);
+                hipError_t e = ic::launch_select(se, bc * ri, (int)max_vis, st);
+                if (e != hipSuccess) return fail(IC_ERR_HIP, "top-k select launch failed: %s", hipGetErrorString(e));
+            }
+        }
+    }
+    g_indexer_launches.fetch_add(1);
+    return IC_OK;
+}
+
+ic_status check_ws(void *ws, size_t have, size_t need)
+{
+    if (need == 0) return IC_OK;
+    if (!ws) return fail(IC_ERR_WORKSPACE, "workspace is NULL but %zu bytes are needed", need);
+    if (((uintptr_t)ws) % kAlign != 0) return fail(IC_ERR_WORKSPACE, "workspace must be %zu-byte aligned", kAlign);
+    if (have < need) return fail(IC_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", have, need);
+    return IC_OK;
+}
+
+size_t indexer_min_ws(const ic_indexer_desc *d)
+{
+    // at least kMinStripRows rows (or every row of one sequence when there are fewer)
+    const int64_t rows = d->Tq < kMinStripRows ? d->Tq : kMinStripRows;
+    return align_up((size_t)rows * strip_ld(d) * sizeof(float));
+}
+
+ic_status run_attn(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, void *O, float *lse,
+                   void *ws, hipStream_t st)
+{
+    ic::AttnArgs a;
+    memset(&a, 0, sizeof a);
+    a.Q = Q;
+    a.KV = KV;
+    a.idx = idx;
+    a.O = O;
+    a.lse = lse;
+    a.B = d->B;
+    a.Tq = d->Tq;
+    a.Lk = d->Lk;
+    a.H_q = d->H_q;
+    a.v_off = d->v_off;
+    a.row_elems = d->row_elems;
+    a.k_sel = d->k_sel;
+    attn_splits(d, &a.n_splits, &a.split_len);
+    a.scale_log2e = d->sm_scale * 1.4426950408889634f;
+    if (a.n_splits > 1) {
+        const size_t nq = (size_t)d->B * d->Tq;
+        a.part_o = (float *)ws;
+        a.part_ml = (float *)((char *)ws + align_up(nq * a.n_splits * d->H_q * d->d_v * sizeof(float)));
+    }
+    {
+        ProfScope ps(2, st);
+        hipError_t e = ic::launch_attn(a, d->d_qk, d->d_v, st);
+        if (e != hipSuccess) return fail(IC_ERR_HIP, "sparse attention launch failed: %s", hipGetErrorString(e));
+    }
+    if (a.n_splits > 1) {
+        ProfScope ps(3, st);
+        hipError_t e = ic::launch_attn_merge(a, d->d_v, st);
+        if (e != hipSuccess) return fail(IC_ERR_HIP, "attention merge launch failed: %s", hipGetErrorString(e));
+    }
+    return IC_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+const char *ic_last_error(void) { return g_err; }
+
+size_t ic_indexer_topk_workspace(const ic_indexer_desc *d)
+{
+    if (check_indexer(d) != IC_OK) return 0;
+    const size_t row_bytes = strip_ld(d) * sizeof(float);
+    const size_t all = (size_t)d->B * d->Tq * row_bytes;
+    size_t want = all < kStripBudget ? all : kStripBudget;
+    const size_t min_b = indexer_min_ws(d);
+    if (want < min_b) want = min_b;
+    return align_up(want / row_bytes * row_bytes);
+}
+
+ic_status ic_indexer_topk(const ic_indexer_desc *d, const void *q, const void *k, const float *w, int32_t *idx,
+                          float *sel_scores, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ic_status s = check_indexer(d);
+    if (s != IC_OK) return s;
+    if (!q || !k || !w || !idx) return fail(IC_ERR_NULL, "q, k, w and idx must not be NULL");
+    s = check_ws(workspace, workspace_bytes, indexer_min_ws(d));
+    if (s != IC_OK) return s;
+    return run_indexer(d, q, k, w, idx, sel_scores, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+size_t ic_sparse_attn_workspace(const ic_attn_desc *d)
+{
+    if (check_attn(d) != IC_OK) return 0;
+    return attn_ws_bytes(d);
+}
+
+ic_status ic_sparse_attn(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, void *O,
+                         float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ic_status s = check_attn(d);
+    if (s != IC_OK) return s;
+    if (!Q || !KV || !idx || !O) return fail(IC_ERR_NULL, "Q, KV, idx and O must not be NULL");
+    s = check_ws(workspace, workspace_bytes, attn_ws_bytes(d));
+    if (s != IC_OK) return s;
+    return run_attn(d, Q, KV, idx, O, lse, workspace, (hipStream_t)stream);
+}
+
+static ic_status check_stack(const ic_layer *layers, int32_t n, const uint8_t *full_mask)
+{
+    if (!layers) return fail(IC_ERR_NULL, "layers is NULL");
+    if (n <= 0) return fail(IC_ERR_SHAPE, "n_layers must be positive");
+    if (full_mask) {
+        if (!full_mask[0]) return fail(IC_ERR_PATTERN, "the first layer must be Full: there are no indices to reuse yet");
+    }
+    for (int l = 0; l < n; ++l) {
+        const ic_layer *L = &layers[l];
+        const bool full = !full_mask || full_mask[l];
+        ic_status s = check_attn(&L->at);
+        if (s != IC_OK) return s;
+        if (!L->Q || !L->KV || !L->O) return fail(IC_ERR_NULL, "layer %d: Q, KV and O must not be NULL", l);
+        if (full) {
+            s = check_indexer(&L->ix);
+            if (s != IC_OK) return s;
+            if (!L->q || !L->k || !L->w) return fail(IC_ERR_NULL, "Full layer %d: q, k and w must not be NULL", l);
+            if (L->ix.B != L->at.B || L->ix.Tq != L->at.Tq || L->ix.k_sel != L->at.k_sel)
+                return fail(IC_ERR_SHAPE, "layer %d: indexer and attention disagree on B, Tq or k_sel", l);
+        }
+        if (L->at.B != layers[0].at.B || L->at.Tq != layers[0].at.Tq || L->at.k_sel != layers[0].at.k_sel)
+            return fail(IC_ERR_SHAPE, "layer %d: all layers must share B, Tq and k_sel (one index buffer)", l);
+    }
+    return IC_OK;
+}
+
+size_t ic_forward_stack_workspace(const ic_layer *layers, int32_t n_layers)
+{
+    if (!layers || n_layers <= 0) return 0;
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        size_t a = ic_sparse_attn_workspace(&layers[l].at);
+        size_t b = layers[l].q ? ic_indexer_topk_workspace(&layers[l].ix) : 0;
+        if (a > need) need = a;
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+ic_status ic_forward_stack(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, int32_t *idx_cache,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!full_mask) return fail(IC_ERR_NULL, "full_mask is NULL");
+    if (!idx_cache) return fail(IC_ERR_NULL, "idx_cache is NULL");
+    ic_status s = check_stack(layers, n_layers, full_mask);
+    if (s != IC_OK) return s;
+    size_t need = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        size_t a = attn_ws_bytes(&layers[l].at);
+        size_t b = full_mask[l] ? indexer_min_ws(&layers[l].ix) : 0;
+        if (a > need) need = a;
+        if (b > need) need = b;
+    }
+    s = check_ws(workspace, workspace_bytes, need);
+    if (s != IC_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    for (int l = 0; l < n_layers; ++l) {
+        const ic_layer *L = &layers[l];
+        if (full_mask[l]) {   // Full: fresh indices overwrite the cache; Shared: cache left as it is
+            s = run_indexer(&L->ix, L->q, L->k, L->w, idx_cache, nullptr, workspace, workspace_bytes, st);
+            if (s != IC_OK) return s;
+        }
+        s = run_attn(&L->at, L->Q, L->KV, idx_cache, L->O, nullptr, workspace, st);
+        if (s != IC_OK) return s;
+    }
+    return IC_OK;
+}
+
+ic_status ic_pattern_from_string(const char *fs, uint8_t *full_mask, int32_t n)
+{
+    if (!fs || !full_mask) return fail(IC_ERR_NULL, "pattern string and mask must not be NULL");
+    if (n <= 0) return fail(IC_ERR_SHAPE, "n must be positive");
+    if ((int64_t)strlen(fs) != n) return fail(IC_ERR_SHAPE, "pattern has %zu characters, expected %d", strlen(fs), n);
+    for (int l = 0; l < n; ++l) {
+        if (fs[l] == 'F')
+            full_mask[l] = 1;
+        else if (fs[l] == 'S')
+            full_mask[l] = 0;
+        else
+            return fail(IC_ERR_PATTERN, "pattern character %d is '%c', expected F or S", l, fs[l]);
+    }
+    if (!full_mask[0]) return fail(IC_ERR_PATTERN, "the first layer must be Full");
+    return IC_OK;
+}
+
+ic_status ic_pattern_uniform(int32_t n, int32_t r, uint8_t *full_mask)
+{
+    if (!full_mask) return fail(IC_ERR_NULL, "mask must not be NULL");
+    if (n <= 0 || r <= 0) return fail(IC_ERR_SHAPE, "n and r must be positive");
+    for (int l = 0; l < n; ++l) full_mask[l] = (l % r) == 0;
+    return IC_OK;
+}
+
+ic_status ic_debug_indexer_scores(const ic_indexer_desc *d, const void *q, const void *k, const float *w,
+                                  int32_t row0, int32_t n_rows, float *out, void *stream)
+{
+    ic_status s = check_indexer(d);
+    if (s != IC_OK) return s;
+    if (!q || !k || !w || !out) return fail(IC_ERR_NULL, "q, k, w and out must not be NULL");
+    if (row0 < 0 || n_rows <= 0 || (int64_t)row0 + n_rows > d->Tq)
+        return fail(IC_ERR_SHAPE, "rows [%d, %d) outside [0, Tq=%d)", row0, row0 + n_rows, d->Tq);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = ic::launch_fill(out, (int64_t)d->B * n_rows * d->Lk, -INFINITY, st);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "fill launch failed: %s", hipGetErrorString(e));
+    ic::ScoreArgs sa;
+    memset(&sa, 0, sizeof sa);
+    sa.q = q;
+    sa.k = k;
+    sa.w = w;
+    sa.q_scale = d->q_scale;
+    sa.k_scale = d->k_scale;
+    sa.strip = out;
+    sa.ld = d->Lk;
+    sa.q_pos0 = d->q_pos0;
+    sa.Tq = d->Tq;
+    sa.Lk = d->Lk;
+    sa.H_I = d->H_I;
+    sa.b0 = 0;
+    sa.i0 = row0;
+    sa.Ri = n_rows;
+    ProfScope ps(0, st);
+    e = ic::launch_score(sa, d->dtype, d->d_I, d->B, st);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "indexer score launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
+uint64_t ic_debug_indexer_launch_count(void) { return g_indexer_launches.load(); }
+
+void ic_prof_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = on != 0;
+}
+
+ic_status ic_prof_collect(void)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    ic_status rc = IC_OK;
+    for (ProfRec &r : g_prof_recs) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(r.e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.e0, r.e1);
+        if (e == hipSuccess) {
+            g_prof_n[r.which] += 1;
+            g_prof_ms[r.which] += ms;
+        } else {
+            rc = fail(IC_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
+        }
+        hipEventDestroy(r.e0);
+        hipEventDestroy(r.e1);
+    }
+    g_prof_recs.clear();
+    return rc;
+}
+
+ic_status ic_prof_get(int32_t which, int64_t *launches, double *total_ms)
+{
+    if (which < 0 || which >= kProfClasses) return fail(IC_ERR_SHAPE, "kernel class %d outside [0,%d)", which, kProfClasses);
+    if (!launches || !total_ms) return fail(IC_ERR_NULL, "output pointers must not be NULL");
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    *launches = g_prof_n[which];
+    *total_ms = g_prof_ms[which];
+    return IC_OK;
+}
+
+void ic_prof_reset(void)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (int i = 0; i < kProfClasses; ++i) {
+        g_prof_n[i] = 0;
+        g_prof_ms[i] = 0;
+    }
+}
+
+} // extern "C"

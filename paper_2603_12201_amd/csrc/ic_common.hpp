@@ -1,0 +1,74 @@
+// Shared device/host declarations of the gfx950 IndexCache library (internal).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "indexcache.h"
+
+namespace ic {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+constexpr int kWave = 64;
+
+// ---- kernel argument blocks ---------------------------------------------------------
+
+// Indexer scoring of query rows [i0, i0+Ri) of sequences [b0, b0+Bc) against their keys.
+// Scores land in a strip: row (b-b0)*Ri + (i-i0), element s, row stride ld floats.
+struct ScoreArgs {
+    const void *q;        // [B,Tq,H_I,d_I]
+    const void *k;        // [B,Lk,d_I]
+    const float *w;       // [B,Tq,H_I]
+    const float *q_scale; // fp8 only
+    const float *k_scale; // fp8 only
+    float *strip;
+    int64_t ld;
+    int64_t q_pos0;
+    int32_t Tq, Lk, H_I;
+    int32_t b0, i0, Ri;   // chunk origin and rows per sequence in the strip
+    int32_t n_qblocks;    // ceil(Ri / tokens per workgroup)
+    int32_t KC;           // keys per workgroup along grid.y (multiple of 64)
+};
+
+// Per-row top-k over a strip of scores.
+struct SelectArgs {
+    const float *strip;
+    int64_t ld;
+    int64_t q_pos0;
+    int32_t Tq, Lk, k_sel;
+    int32_t b0, i0, Ri;
+    int32_t cache_elems;  // row elements the workgroup may cache in LDS (0 = none)
+    int32_t *idx;         // [B,Tq,k_sel]
+    float *sel;           // [B,Tq,k_sel] or nullptr
+};
+
+struct AttnArgs {
+    const void *Q;        // [B,Tq,H_q,d_qk] bf16
+    const void *KV;       // [B,Lk,row_elems] bf16
+    const int32_t *idx;   // [B,Tq,k_sel]
+    void *O;              // [B,Tq,H_q,d_v] bf16
+    float *lse;           // [B,Tq,H_q] or nullptr
+    float *part_o;        // split partials: [B*Tq, n_splits, H_q, d_v] fp32 (unnormalised)
+    float *part_ml;       // [B*Tq, n_splits, H_q, 2] fp32 (running max in log2 units, sum)
+    int32_t B, Tq, Lk, H_q, v_off, row_elems, k_sel;
+    int32_t n_splits, split_len; // key slots per split (multiple of 64)
+    float scale_log2e;    // sm_scale * log2(e)
+};
+
+// ---- launchers (defined next to their kernels) ----------------------------------------
+
+hipError_t launch_score(const ScoreArgs &a, int dtype, int d_I, int Bc, hipStream_t st);
+hipError_t launch_fill(float *p, int64_t n, float v, hipStream_t st);
+hipError_t launch_select(const SelectArgs &a, int n_rows, int max_row_len, hipStream_t st);
+int select_cache_limit();
+hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st);
+hipError_t launch_attn_merge(const AttnArgs &a, int d_v, hipStream_t st);
+bool score_shape_supported(int dtype, int H_I, int d_I);
+bool attn_shape_supported(int d_qk, int d_v);
+
+} // namespace ic

@@ -1,0 +1,230 @@
+// Lightning-indexer score kernel for gfx950 (CDNA4).
+//
+//   I[t,s] = sum_j w[t,j] * ReLU( q[t,j,:] . k[s,:] )        (paper Sec. 2.1, Sec. 3 Notation)
+//
+// Mapping.  The contraction runs on v_mfma_f32_32x32x16_bf16 with the indexer HEADS of one
+// query token as the 32 rows of the A operand and 32 KEYS as the columns of the B operand,
+// so one accumulator tile holds dot(q[t,j], k[s]) for 32 heads x 32 keys.  In that result
+// layout a lane owns one key column and 16 of the 32 head rows: the ReLU, the weighting by
+// w[t,j] and the sum over heads are 16 in-lane max/fma pairs plus one exchange between the
+// two half-waves.  The q rows of the tokens a wave owns stay in registers for the whole key
+// loop; key tiles (64 keys) are staged through LDS, double buffered, one barrier per tile,
+// and shared by the four waves of the workgroup (each wave owns TPW tokens).
+//
+// The kernel writes scores of the query rows in flight into a strip (rows x Lk fp32); it
+// never holds more rows than the caller's workspace allows.  Keys hidden by the causal mask
+// are not written.
+#include "ic_common.hpp"
+
+namespace ic {
+
+namespace {
+
+// Global -> register -> LDS staging of one tile of 64 key rows (16-byte chunks, coalesced).
+template <int DI, int LPT>
+__device__ __forceinline__ void tile_gload(u32x4 (&pre)[LPT], const unsigned short *kp, int kt, int Lk, int tid)
+{
+    constexpr int CPR = DI / 8;
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+        const int c = tid + 256 * r;
+        const int row = c / CPR, col = c % CPR;
+        const int s = min(kt + row, Lk - 1);                // clamp: rows past Lk are masked later
+        pre[r] = *(const u32x4 *)(kp + ((int64_t)s * DI + col * 8));
+    }
+}
+
+template <int DI, int LPT, int ROWB>
+__device__ __forceinline__ void tile_lstore(const u32x4 (&pre)[LPT], unsigned char *buf, int tid)
+{
+    constexpr int CPR = DI / 8;
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+        const int c = tid + 256 * r;
+        const int row = c / CPR, col = c % CPR;
+        *(u32x4 *)(buf + row * ROWB + col * 16) = pre[r];
+    }
+}
+
+template <int HT, int DI, int TPW>
+__global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
+{
+    constexpr int KS = DI / 16;                 // MFMA k-steps over the head dim
+    constexpr int BT = 4 * TPW;                 // tokens per workgroup
+    constexpr int ROWB = DI * 2 + 16;           // LDS row stride (bytes), padded against bank conflicts
+    constexpr int TILE = 64;                    // keys per LDS tile
+    constexpr int CPR = DI / 8;                 // 16-byte chunks per key row
+    constexpr int LPT = TILE * CPR / 256;       // 16-byte loads per thread per tile
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][TILE * ROWB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r32 = lane & 31, half = lane >> 5;
+    const int qb = a.n_qblocks - 1 - (int)blockIdx.x;      // longest rows first
+    const int b = a.b0 + (int)blockIdx.z;
+    const int i_end = min(a.i0 + a.Ri, a.Tq);
+    const int t_blk = a.i0 + qb * BT;
+    if (t_blk >= i_end) return;
+    const int t_blk_last = min(t_blk + BT, i_end) - 1;
+
+    int64_t vis64 = a.q_pos0 + (int64_t)t_blk_last + 1;    // keys visible to the block's last token
+    vis64 = vis64 < 0 ? 0 : (vis64 > a.Lk ? a.Lk : vis64);
+    const int kc0 = (int)blockIdx.y * a.KC;
+    const int kend = min(kc0 + a.KC, (int)vis64);
+    if (kc0 >= kend) return;                               // whole workgroup: nothing visible here
+
+    const int t_w0 = t_blk + wave * TPW;                   // this wave's first token
+    int64_t wv64 = a.q_pos0 + (int64_t)min(t_w0 + TPW, i_end);
+    wv64 = wv64 < 0 ? 0 : (wv64 > a.Lk ? a.Lk : wv64);
+    const int wave_vis = (t_w0 < i_end) ? (int)wv64 : 0;   // keys >= wave_vis matter to none of its tokens
+
+    // ---- stationary operands: q rows (A operand) and head weights of the wave's tokens ----
+    bf16x8 qa[TPW][HT][KS];
+    float wr[TPW][HT][16];
+    const unsigned short *qp = (const unsigned short *)a.q;
+#pragma unroll
+    for (int j = 0; j < TPW; ++j) {
+        const int t = t_w0 + j;
+        const bool tv = t < i_end;
+        const int64_t trow = (int64_t)b * a.Tq + (tv ? t : 0);
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) {
+            const int head = ht * 32 + r32;
+            const bool hv = tv && head < a.H_I;
+            const unsigned short *src = qp + ((trow * a.H_I + (hv ? head : 0)) * DI + half * 8);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+                if (hv) raw = *(const u32x4 *)(src + ks * 16);
+                qa[j][ht][ks] = __builtin_bit_cast(bf16x8, raw);
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int hrow = ht * 32 + 8 * (i / 4) + 4 * half + (i % 4);
+                wr[j][ht][i] = (tv && hrow < a.H_I) ? a.w[trow * a.H_I + hrow] : 0.f;
+            }
+        }
+    }
+
+    // ---- key tile pipeline ----
+    const unsigned short *kp = (const unsigned short *)a.k + (int64_t)b * a.Lk * DI;
+    u32x4 pre[LPT];
+    const int ntiles = (kend - kc0 + TILE - 1) / TILE;
+    tile_gload<DI, LPT>(pre, kp, kc0, a.Lk, tid);
+    tile_lstore<DI, LPT, ROWB>(pre, &lds[0][0], tid);
+    __syncthreads();
+
+    for (int it = 0; it < ntiles; ++it) {
+        const int kt = kc0 + it * TILE;
+        const int buf = it & 1;
+        if (it + 1 < ntiles) tile_gload<DI, LPT>(pre, kp, kt + TILE, a.Lk, tid);
+
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int s0 = kt + sub * 32;
+            if (s0 >= wave_vis) continue;                   // wave-uniform
+            bf16x8 kb[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kb[ks] = *(const bf16x8 *)(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 16 + half * 8) * 2]);
+#pragma unroll
+            for (int p = 0; p < TPW / 2; ++p) {
+                float part[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int j = 2 * p + u;
+                    float s_acc = 0.f;
+#pragma unroll
+                    for (int ht = 0; ht < HT; ++ht) {
+                        f32x16 acc;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks)
+                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[j][ht][ks], kb[ks], acc, 0, 0, 0);
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            s_acc = fmaf(fmaxf(acc[i], 0.f), wr[j][ht][i], s_acc);
+                    }
+                    part[u] = s_acc;
+                }
+                // each half-wave holds 16 of the 32 head rows: add the other half's partial sum
+                const float tot0 = part[0] + __shfl_xor(part[0], 32);
+                const float tot1 = part[1] + __shfl_xor(part[1], 32);
+                const float v = half ? tot1 : tot0;         // lanes 0-31: token 2p, lanes 32-63: token 2p+1
+                const int t = t_w0 + 2 * p + half;
+                const int s = s0 + r32;
+                if (t < i_end && s < a.Lk && (int64_t)s <= a.q_pos0 + t) {
+                    const int64_t srow = (int64_t)blockIdx.z * a.Ri + (t - a.i0);
+                    a.strip[srow * a.ld + s] = v;
+                }
+            }
+        }
+
+        if (it + 1 < ntiles) tile_lstore<DI, LPT, ROWB>(pre, &lds[buf ^ 1][0], tid);
+        __syncthreads();
+    }
+}
+
+__global__ void fill_kernel(float *p, int64_t n, float v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+
+template <int HT, int DI, int TPW>
+hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
+{
+    const int n_kc = (int)((max_vis + a.KC - 1) / a.KC);
+    if (n_kc <= 0 || a.n_qblocks <= 0 || Bc <= 0) return hipSuccess;
+    dim3 grid((unsigned)a.n_qblocks, (unsigned)n_kc, (unsigned)Bc);
+    hipLaunchKernelGGL((score_kernel<HT, DI, TPW>), grid, dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+} // namespace
+
+bool score_shape_supported(int dtype, int H_I, int d_I)
+{
+    if (dtype != IC_BF16) return false;
+    if (H_I < 1 || H_I > IC_MAX_HEADS_I) return false;
+    return d_I == 64 || d_I == 128;
+}
+
+// Tokens per workgroup for a head count (the launcher and the host-side grid math agree on it).
+static int tokens_per_block(int H_I) { return H_I <= 32 ? 16 : 8; }
+
+hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipStream_t st)
+{
+    (void)dtype;
+    ScoreArgs a = a_in;
+    const int BT = tokens_per_block(a.H_I);
+    a.n_qblocks = (a.Ri + BT - 1) / BT;
+    const int i_last = min(a.i0 + a.Ri, a.Tq) - 1;
+    int64_t max_vis = a.q_pos0 + i_last + 1;
+    max_vis = max_vis < 0 ? 0 : (max_vis > a.Lk ? a.Lk : max_vis);
+    if (max_vis == 0) return hipSuccess;
+    // keys per workgroup: enough workgroups to fill 256 CUs several times, tiles of 64 keys
+    int64_t kc = (max_vis * a.n_qblocks * Bc / 2048 + 63) / 64 * 64;
+    kc = kc < 512 ? 512 : (kc > 4096 ? 4096 : kc);
+    a.KC = (int)kc;
+    if (a.H_I <= 32) {
+        if (d_I == 128) return launch_t<1, 128, 4>(a, Bc, max_vis, st);
+        if (d_I == 64) return launch_t<1, 64, 4>(a, Bc, max_vis, st);
+    } else {
+        if (d_I == 128) return launch_t<2, 128, 2>(a, Bc, max_vis, st);
+        if (d_I == 64) return launch_t<2, 64, 2>(a, Bc, max_vis, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_fill(float *p, int64_t n, float v, hipStream_t st)
+{
+    if (n <= 0) return hipSuccess;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 65535) blocks = 65535;
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+    return hipGetLastError();
+}
+
+} // namespace ic

@@ -1,0 +1,195 @@
+"""GPU parity: each HIP kernel against the CPU oracle on small seeded cases that still span
+several tiles and ragged tails.  Everything goes through the C ABI (ctypes binding)."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print("[case] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def ic():
+    import paper_2603_12201_amd as m
+    m.lib()
+    assert torch.cuda.is_available()
+    return m
+
+
+def _mk_indexer(seed, B, Tq, Lk, H, d, signed_w=False):
+    g = torch.Generator().manual_seed(seed)
+    q = (torch.randn((B, Tq, H, d), generator=g) / math.sqrt(d)).to(torch.bfloat16)
+    k = torch.randn((B, Lk, d), generator=g).to(torch.bfloat16)
+    w = torch.rand((B, Tq, H), generator=g)
+    if signed_w:
+        w = w * 2 - 1
+    return q, k, w.float()
+
+
+SCORE_CASES = [
+    # B, Tq, Lk, H, d, q_pos0, signed
+    (1, 40, 40, 4, 64, 0, False),        # tiny config shape, ragged tail of a 16-token block
+    (2, 37, 150, 32, 128, 113, False),   # chunked prefill: queries in the middle of the context
+    (1, 130, 130, 32, 128, 0, True),     # signed head weights, several key tiles
+    (2, 1, 300, 32, 128, 299, False),    # decode: one query row per sequence
+    (1, 20, 90, 64, 128, 70, False),     # 64 heads (two head tiles)
+    (1, 24, 24, 7, 64, 0, False),        # head count that is not a multiple of anything
+    (1, 9, 50, 32, 128, 10, False),      # Lk caps the visible range (q_pos0 + i >= Lk)
+]
+
+
+@pytest.mark.parametrize("case", SCORE_CASES)
+def test_indexer_scores(ic, oracle, case):
+    B, Tq, Lk, H, d, p0, signed = case
+    say("scores B=%d Tq=%d Lk=%d H=%d d=%d q_pos0=%d signed=%s" % case)
+    q, k, w = _mk_indexer(100 + Tq + H, B, Tq, Lk, H, d, signed)
+    got = ic.debug_indexer_scores(q.cuda(), k.cuda(), w.cuda(), p0, 0, Tq)
+    torch.cuda.synchronize()
+    want = oracle.indexer_scores(synth.bits(q), synth.bits(k), synth.bits(w), p0)
+    parity.check_scores(got.cpu().numpy(), want)
+
+
+def test_indexer_scores_row_window(ic, oracle):
+    say("scores row window")
+    B, Tq, Lk, H, d, p0 = 1, 100, 100, 32, 128, 0
+    q, k, w = _mk_indexer(7, B, Tq, Lk, H, d)
+    got = ic.debug_indexer_scores(q.cuda(), k.cuda(), w.cuda(), p0, 33, 21)
+    torch.cuda.synchronize()
+    want = oracle.indexer_scores(synth.bits(q), synth.bits(k), synth.bits(w), p0, rows=list(range(33, 54)))
+    parity.check_scores(got.cpu().numpy(), want)
+
+
+TOPK_CASES = [
+    # B, Tq, Lk, H, d, q_pos0, k_sel
+    (1, 200, 200, 4, 64, 0, 64),         # tiny-config shape: zero-score ties at the boundary
+    (2, 50, 400, 32, 128, 350, 128),
+    (1, 70, 70, 32, 128, 0, 128),        # every row shorter than k: all positions selected
+    (2, 1, 1000, 32, 128, 999, 256),     # decode
+    (1, 33, 9000, 32, 128, 8967, 2048),  # long rows: 1024-thread select, LDS-cached row
+    (1, 40, 300, 64, 128, 260, 1),       # k = 1: argmax
+]
+
+
+@pytest.mark.parametrize("case", TOPK_CASES)
+def test_indexer_topk(ic, oracle, case):
+    B, Tq, Lk, H, d, p0, ks = case
+    say("topk B=%d Tq=%d Lk=%d H=%d d=%d q_pos0=%d k=%d" % case)
+    q, k, w = _mk_indexer(200 + Tq + ks, B, Tq, Lk, H, d)
+    idx, sel = ic.indexer_topk(q.cuda(), k.cuda(), w.cuda(), ks, p0, want_scores=True)
+    torch.cuda.synchronize()
+    idx, sel = idx.cpu().numpy(), sel.cpu().numpy()
+    sc = oracle.indexer_scores(synth.bits(q), synth.bits(k), synth.bits(w), p0)
+    kinds = {}
+    for b in range(B):
+        for i in range(Tq):
+            nv = max(0, min(Lk, p0 + i + 1))
+            kind = parity.check_idx_row(idx[b, i], sc[b, i], nv, ks, oracle)
+            kinds[kind] = kinds.get(kind, 0) + 1
+            n = min(nv, ks)
+            want_sel = sc[b, i][idx[b, i, :n]]
+            parity.check_scores(sel[b, i, :n][None], want_sel[None])
+            assert np.all(np.isneginf(sel[b, i, n:]))
+    say("row kinds: %s" % kinds)
+
+
+def test_topk_tie_break_on_equal_scores(ic, oracle):
+    # w = 0 makes every score exactly 0: the k lowest positions must win, on every row
+    say("topk all-equal rows")
+    B, Tq, Lk, H, d, ks = 1, 300, 300, 32, 128, 64
+    q, k, w = _mk_indexer(5, B, Tq, Lk, H, d)
+    w.zero_()
+    idx = ic.indexer_topk(q.cuda(), k.cuda(), w.cuda(), ks, 0).cpu().numpy()
+    for i in range(Tq):
+        n = min(i + 1, ks)
+        assert np.array_equal(idx[0, i, :n], np.arange(n))
+        assert np.all(idx[0, i, n:] == -1)
+
+
+def test_topk_monotone_scores(ic, oracle):
+    # one head, one-hot q, keys increasing along that coordinate: scores increase with position,
+    # so the last k visible positions win (the adversarial order for a streaming filter)
+    say("topk monotone rows")
+    B, Tq, Lk, H, d, ks = 1, 500, 500, 1, 64, 32
+    q = torch.zeros((B, Tq, H, d)); q[..., 3] = 1.0
+    k = torch.zeros((B, Lk, d)); k[0, :, 3] = torch.arange(Lk, dtype=torch.float32) / 4.0
+    w = torch.ones((B, Tq, H))
+    idx = ic.indexer_topk(q.bfloat16().cuda(), k.bfloat16().cuda(), w.cuda(), ks, 0).cpu().numpy()
+    kb = k.bfloat16().float()[0, :, 3].numpy()
+    assert np.all(np.diff(kb) >= 0)
+    sc = oracle.indexer_scores(synth.bits(q.bfloat16()), synth.bits(k.bfloat16()), synth.bits(w), 0)
+    for i in range(Tq):
+        parity.check_idx_row(idx[0, i], sc[0, i], i + 1, ks, oracle)
+
+
+def _mk_attn(seed, B, Tq, Lk, Hq, d_qk, row):
+    g = torch.Generator().manual_seed(seed)
+    Q = torch.randn((B, Tq, Hq, d_qk), generator=g).to(torch.bfloat16)
+    KV = torch.randn((B, Lk, row), generator=g).to(torch.bfloat16)
+    return Q, KV
+
+
+def _rand_idx(seed, B, Tq, Lk, ks, p0, holes=False):
+    rng = np.random.default_rng(seed)
+    idx = np.full((B, Tq, ks), -1, dtype=np.int32)
+    for b in range(B):
+        for i in range(Tq):
+            nv = max(0, min(Lk, p0 + i + 1))
+            n = min(nv, ks)
+            idx[b, i, :n] = np.sort(rng.choice(nv, size=n, replace=False))
+            if holes and n > 3:
+                idx[b, i, rng.choice(n, size=n // 3, replace=False)] = -1
+    return idx
+
+
+ATTN_CASES = [
+    # B, Tq, Lk, Hq, d_qk, d_v, v_off, row, k_sel, q_pos0, holes
+    (1, 300, 300, 4, 64, 64, 64, 128, 64, 0, False),     # tiny-config layout [K | V]
+    (1, 260, 260, 32, 576, 512, 0, 576, 128, 0, False),  # MLA row, one workgroup per query
+    (2, 3, 500, 32, 576, 512, 0, 576, 256, 497, False),  # few queries: split path + merge kernel
+    (1, 20, 400, 20, 576, 512, 0, 576, 200, 380, True),  # ragged heads, ragged k_sel, holes in idx
+    (2, 5, 90, 16, 64, 64, 64, 128, 70, 85, True),
+]
+
+
+@pytest.mark.parametrize("case", ATTN_CASES)
+def test_sparse_attn(ic, oracle, case):
+    B, Tq, Lk, Hq, d_qk, d_v, v_off, row, ks, p0, holes = case
+    say("attn B=%d Tq=%d Lk=%d Hq=%d dqk=%d dv=%d voff=%d row=%d k=%d p0=%d holes=%s" % case)
+    Q, KV = _mk_attn(300 + Tq + ks, B, Tq, Lk, Hq, d_qk, row)
+    idx = _rand_idx(400 + Tq, B, Tq, Lk, ks, p0, holes)
+    scale = 1.0 / math.sqrt(d_qk)
+    O, lse = ic.sparse_attn(Q.cuda(), KV.cuda(), torch.from_numpy(idx).cuda(), d_v, v_off, scale, want_lse=True)
+    torch.cuda.synchronize()
+    want, want_lse = oracle.sparse_attn(synth.bits(Q), synth.bits(KV), idx, d_v, v_off, scale)
+    err = parity.check_attn(O.float().cpu().numpy(), want)
+    say("max abs err %.4g" % err)
+    assert np.allclose(lse.cpu().numpy(), want_lse, rtol=0, atol=2e-2)
+
+
+def test_sparse_attn_empty_rows_and_out_of_range(ic, oracle):
+    say("attn empty rows / out-of-range entries")
+    B, Tq, Lk, Hq, d_qk, d_v, row, ks = 1, 4, 50, 32, 576, 512, 576, 64
+    Q, KV = _mk_attn(9, B, Tq, Lk, Hq, d_qk, row)
+    idx = np.full((B, Tq, ks), -1, dtype=np.int32)
+    idx[0, 1, :5] = [3, 7, 9, 11, 49]
+    idx[0, 2, 10] = 20
+    idx[0, 3, :3] = [1, 1000, 2]           # 1000 >= Lk must be skipped, not read
+    scale = 1.0 / 24.0
+    O, lse = ic.sparse_attn(Q.cuda(), KV.cuda(), torch.from_numpy(idx).cuda(), d_v, 0, scale, want_lse=True)
+    torch.cuda.synchronize()
+    idx_o = idx.copy(); idx_o[idx_o >= Lk] = -1
+    want, want_lse = oracle.sparse_attn(synth.bits(Q), synth.bits(KV), idx_o, d_v, 0, scale)
+    parity.check_attn(O.float().cpu().numpy(), want)
+    assert np.all(O[0, 0].float().cpu().numpy() == 0)
+    assert np.all(np.isneginf(lse[0, 0].cpu().numpy()))
+    assert np.allclose(lse[0, 1:].cpu().numpy(), want_lse[0, 1:], atol=2e-2)
