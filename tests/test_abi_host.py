@@ -1,0 +1,155 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and turns bad arguments into status codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "indexcache.h")
+
+
+@pytest.fixture(scope="module")
+def ic():
+    import paper_2603_12201_amd as m
+    if not os.path.exists(m.lib_path()):
+        from paper_2603_12201_amd import build
+        build.build()
+    m.lib()
+    return m
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ic_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(ic):
+    names = _declared()
+    assert {"ic_indexer_topk", "ic_sparse_attn", "ic_forward_stack"} <= set(names)
+    L = ic.lib()
+    for n in names:
+        assert hasattr(L, n), "libindexcache.so does not export %s" % n
+
+
+def test_struct_sizes_match_header_layout(ic):
+    # field order/size as declared: 6*int32 + int64 + int32 + uint32 + 2 pointers
+    assert C.sizeof(ic.IndexerDesc) == 56
+    assert C.sizeof(ic.AttnDesc) == 40
+    assert C.sizeof(ic.Layer) == 56 + 24 + 40 + 24
+
+
+def test_pattern_helpers(ic):
+    assert ic.pattern_uniform(8, 4) == [True, False, False, False, True, False, False, False]
+    assert ic.pattern_uniform(3, 1) == [True, True, True]
+    assert ic.pattern_from_string("FSSF") == [True, False, False, True]
+    for bad, st in [("SFF", ic.Status.ERR_PATTERN), ("FXS", ic.Status.ERR_PATTERN)]:
+        with pytest.raises(ic.IcError) as e:
+            ic.pattern_from_string(bad)
+        assert e.value.status == st
+    with pytest.raises(ic.IcError) as e:
+        ic.pattern_uniform(4, 0)
+    assert e.value.status == ic.Status.ERR_SHAPE
+    L = ic.lib()
+    buf = C.create_string_buffer(4)
+    assert L.ic_pattern_from_string(b"FS", buf, 3) == ic.Status.ERR_SHAPE      # length mismatch
+    assert L.ic_pattern_from_string(None, buf, 3) == ic.Status.ERR_NULL
+    assert b"pattern" in L.ic_last_error() or b"NULL" in L.ic_last_error()
+
+
+def test_paper_patterns_through_the_library(ic):
+    for line in open(os.path.join(ROOT, "tests", "golden", "searched_patterns.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        _, _, s = line.split()
+        mask = ic.pattern_from_string(s)
+        assert [c == "F" for c in s] == mask
+
+
+def _ixd(ic, **kw):
+    d = dict(B=1, Tq=128, Lk=128, H_I=32, d_I=128, k_sel=64, q_pos0=0, dtype=0, flags=0,
+             q_scale=None, k_scale=None)
+    d.update(kw)
+    return ic.IndexerDesc(**d)
+
+
+def _atd(ic, **kw):
+    d = dict(B=1, Tq=128, Lk=128, H_q=32, d_qk=576, d_v=512, v_off=0, row_elems=576, k_sel=64, sm_scale=0.04)
+    d.update(kw)
+    return ic.AttnDesc(**d)
+
+
+def test_indexer_argument_errors(ic):
+    L = ic.lib()
+    S = ic.Status
+    one = C.c_void_p(4096)   # never dereferenced: validation fails first
+    good = _ixd(ic)
+    ws = L.ic_indexer_topk_workspace(C.byref(good))
+    assert ws >= 16 * 128 * 4 and ws % 256 == 0
+    assert L.ic_indexer_topk(None, one, one, one, one, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_indexer_topk(C.byref(good), None, one, one, one, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_indexer_topk(C.byref(good), one, one, one, None, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_indexer_topk(C.byref(good), one, one, one, one, None, None, ws, None) == S.ERR_WORKSPACE
+    assert L.ic_indexer_topk(C.byref(good), one, one, one, one, None, C.c_void_p(4096 + 8), ws, None) == S.ERR_WORKSPACE
+    assert L.ic_indexer_topk(C.byref(good), one, one, one, one, None, one, 1024, None) == S.ERR_WORKSPACE
+    for kw, st in [(dict(k_sel=4096), S.ERR_UNSUPPORTED), (dict(k_sel=0), S.ERR_SHAPE), (dict(B=0), S.ERR_SHAPE),
+                   (dict(Lk=-3), S.ERR_SHAPE), (dict(d_I=96), S.ERR_UNSUPPORTED), (dict(H_I=65), S.ERR_UNSUPPORTED),
+                   (dict(dtype=7), S.ERR_UNSUPPORTED), (dict(flags=1), S.ERR_UNSUPPORTED)]:
+        bad = _ixd(ic, **kw)
+        assert L.ic_indexer_topk_workspace(C.byref(bad)) == 0
+        assert L.ic_indexer_topk(C.byref(bad), one, one, one, one, None, one, ws, None) == st, kw
+        assert len(L.ic_last_error()) > 0
+
+
+def test_attention_argument_errors(ic):
+    L = ic.lib()
+    S = ic.Status
+    one = C.c_void_p(4096)
+    good = _atd(ic, k_sel=256)
+    assert L.ic_sparse_attn_workspace(C.byref(good)) > 0          # 128 queries < 256: split path
+    assert L.ic_sparse_attn_workspace(C.byref(_atd(ic, Tq=4096, Lk=4096))) == 0
+    assert L.ic_sparse_attn(C.byref(good), None, one, one, one, None, one, 1 << 30, None) == S.ERR_NULL
+    assert L.ic_sparse_attn(C.byref(good), one, one, one, one, None, None, 0, None) == S.ERR_WORKSPACE
+    for kw, st in [(dict(H_q=33), S.ERR_UNSUPPORTED), (dict(d_qk=128), S.ERR_UNSUPPORTED),
+                   (dict(v_off=4), S.ERR_SHAPE), (dict(v_off=128), S.ERR_UNSUPPORTED),
+                   (dict(row_elems=512), S.ERR_UNSUPPORTED), (dict(sm_scale=0.0), S.ERR_SHAPE),
+                   (dict(k_sel=0), S.ERR_SHAPE)]:
+        bad = _atd(ic, **kw)
+        assert L.ic_sparse_attn(C.byref(bad), one, one, one, one, None, one, 1 << 30, None) == st, kw
+
+
+def test_forward_stack_argument_errors(ic):
+    L = ic.lib()
+    S = ic.Status
+    one = 4096
+    arr = (ic.Layer * 2)()
+    for l in range(2):
+        arr[l].ix = _ixd(ic, Tq=4096, Lk=4096)
+        arr[l].at = _atd(ic, Tq=4096, Lk=4096)
+        arr[l].q = arr[l].k = arr[l].w = arr[l].Q = arr[l].KV = arr[l].O = one
+    ws = L.ic_forward_stack_workspace(arr, 2)
+    assert ws > 0
+    p = C.c_void_p(one)
+    # the first layer must be Full (there is nothing to reuse yet)
+    assert L.ic_forward_stack(arr, 2, bytes([0, 1]), p, p, ws, None) == S.ERR_PATTERN
+    assert L.ic_forward_stack(arr, 2, None, p, p, ws, None) == S.ERR_NULL
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), None, p, ws, None) == S.ERR_NULL
+    assert L.ic_forward_stack(arr, 0, bytes([1]), p, p, ws, None) == S.ERR_SHAPE
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, 16, None) == S.ERR_WORKSPACE
+    arr[1].at.k_sel = 32                                             # one index buffer: k_sel must agree
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, ws, None) == S.ERR_SHAPE
+    arr[1].at.k_sel = 64
+    arr[1].q = None                                                  # a Shared layer may omit q,k,w ...
+    arr[0].q = None                                                  # ... a Full layer may not
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, ws, None) == S.ERR_NULL
+    # workspace need does not grow with the number of Shared layers (one index buffer, one strip)
+    assert L.ic_forward_stack_workspace(arr, 1) <= ws
+
+
+def test_prof_api_without_gpu(ic):
+    ic.prof_reset()
+    assert ic.prof_get(0) == (0, 0.0)
+    with pytest.raises(ic.IcError):
+        ic.prof_get(9)
