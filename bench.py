@@ -1,0 +1,294 @@
+#!/usr/bin/env python3
+"""Benchmark of the IndexCache / DSA attention-side hot path on one MI355X.
+
+A step is one pass of the whole path (indexer score + top-k on Full layers, sparse MQA
+attention on every layer) through ic_forward_stack over the 48-layer, L = 32768 prefill stack
+with the 1-in-4 Full pattern (FSSS...).  The all-Full arm (standard DSA) and one batched decode
+step (batch 32, context 65536, 4 layers FSSS / FFFF) are timed beside it and reported in
+"arms".  Inputs are synthetic, seeded and resident in HBM before the timed region.
+
+Prints ONE JSON line (see the keys below); progress goes to stderr.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+KERNELS = ["indexer_score", "topk_select", "sparse_attn", "attn_merge"]
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def ensure_built():
+    import paper_2603_12201_amd as ic
+    if not os.path.exists(ic.lib_path()):
+        from paper_2603_12201_amd import build
+        log("libindexcache.so missing: building")
+        build.build()
+    ic.lib()
+    return ic
+
+
+def time_steps(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def prof_snapshot(ic):
+    ic.prof_collect()
+    return {name: ic.prof_get(i) for i, name in enumerate(KERNELS)}
+
+
+class Stack:
+    """Device-resident layer tensors + the host layer array for ic_forward_stack."""
+
+    def __init__(self, ic, synth, cfg, n_layers, share_q_every):
+        import torch
+        self.cfg, self.ic = cfg, ic
+        B, Tq = cfg["B"], cfg["Tq"]
+        t0 = time.perf_counter()
+        self.layers = []
+        for l in range(n_layers):
+            d = synth.indexer_layer(cfg, l, device="cuda")
+            if l < share_q_every:
+                d.update(synth.attn_layer(cfg, l, device="cuda"))
+            else:   # cycle the big attention inputs (they do not influence the indices)
+                src = self.layers[l % share_q_every]
+                d["Q"], d["KV"] = src["Q"], src["KV"]
+            self.layers.append(d)
+            if l % 8 == 7:
+                torch.cuda.synchronize()
+                log("generated %d/%d layers (%.1f s)" % (l + 1, n_layers, time.perf_counter() - t0))
+        self.O = torch.empty((B, Tq, cfg["H_q"], cfg["d_v"]), dtype=torch.bfloat16, device="cuda")
+        self.arr = ic.make_layers(self.layers, cfg["k_sel"], cfg["q_pos0"], cfg["d_v"], cfg["v_off"],
+                                  synth.sm_scale(cfg), [self.O] * n_layers)
+        self.ws = torch.empty(max(ic.forward_stack_workspace(self.arr), 256), dtype=torch.uint8, device="cuda")
+        self.idx_cache = torch.empty((B, Tq, cfg["k_sel"]), dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+
+    def step(self, mask):
+        self.ic.forward_stack(self.arr, mask, self.idx_cache, self.ws)
+
+
+def algorithmic(cfg):
+    """Algorithmic work of ONE layer's kernels (per-unit figures)."""
+    B, Tq, Lk, p0 = cfg["B"], cfg["Tq"], cfg["Lk"], cfg["q_pos0"]
+    pairs = sum(max(0, min(Lk, p0 + i + 1)) for i in range(Tq)) * B if Tq <= 4096 else \
+        B * (Tq * (Tq + 1) // 2 if p0 == 0 and Tq == Lk else Tq * Lk)
+    return {
+        "indexer_flop": 2.0 * cfg["H_I"] * cfg["d_I"] * pairs,                 # 2*H_I*d_I per causal pair
+        "indexer_key_bytes": float(B) * Lk * cfg["d_I"] * 2,                   # decode: the key cache once
+        "select_bytes": 4.0 * pairs + 4.0 * B * Tq * cfg["k_sel"],             # one read of the scores + idx
+        "attn_bytes": float(B) * Tq * (min(cfg["k_sel"], Lk) * cfg["row_elems"] * 2
+                                       + cfg["H_q"] * cfg["d_qk"] * 2 + cfg["H_q"] * cfg["d_v"] * 2),
+        "attn_flop": 2.0 * B * Tq * cfg["H_q"] * min(cfg["k_sel"], Lk) * (cfg["d_qk"] + cfg["d_v"]),
+    }
+
+
+def cpu_baseline(synth, cfg, layer_gpu, n_full, n_layers, budget_s=15.0):
+    """The oracle, as it stands, on a strided sample of query rows of one layer; extrapolated to
+    the whole 1-in-4 stack by the row count (a strided sample is unbiased for the causal work)."""
+    from oracle import oracle as orc
+    import numpy as np
+    Tq = cfg["Tq"]
+    lb = synth.bits_layer(layer_gpu)
+
+    def run(rows):
+        t0 = time.perf_counter()
+        r = orc.indexer_topk(lb["q"], lb["k"], lb["w"], cfg["q_pos0"], cfg["k_sel"], rows=rows)
+        t1 = time.perf_counter()
+        orc.sparse_attn(lb["Q"], lb["KV"], r["idx"], cfg["d_v"], cfg["v_off"], synth.sm_scale(cfg),
+                        rows=rows, idx_is_subset=True)
+        t2 = time.perf_counter()
+        return t1 - t0, t2 - t1
+
+    def strided(n):
+        return sorted(set(int(x) for x in np.linspace(0, Tq - 1, n)))
+
+    rows = strided(32)
+    ti, ta = run(rows)
+    per_row = (ti + ta) / len(rows)
+    n = int(max(32, min(Tq, budget_s / max(per_row, 1e-6))))
+    rows = strided(n)
+    ti, ta = run(rows)
+    layer_idx_s = ti / len(rows) * Tq
+    layer_att_s = ta / len(rows) * Tq
+    total_s = n_full * layer_idx_s + n_layers * layer_att_s
+    return {
+        "value": cfg["B"] * Tq / total_s, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+        "sample": "%d strided query rows of one layer (indexer+top-k %.2f s, attention %.2f s), "
+                  "extrapolated by row count to %d Full + %d attention layers"
+                  % (len(rows), ti, ta, n_full, n_layers),
+        "extrapolated": True,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--layers", type=int, default=48, help="layers of the prefill stack (48 = the metric's workload)")
+    ap.add_argument("--distinct-attn-inputs", type=int, default=4,
+                    help="distinct per-layer Q/KV buffers to generate; later layers cycle through them")
+    ap.add_argument("--decode-steps", type=int, default=20)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    ic = ensure_built()
+    import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    # ---------------- prefill: 48-layer stack, L = 32768 ----------------
+    cfg = synth.config("c3", n_layers=args.layers)
+    n_layers = args.layers
+    mask_14 = ic.pattern_uniform(n_layers, 4)
+    mask_all = [True] * n_layers
+    stack = Stack(ic, synth, cfg, n_layers, max(1, min(args.distinct_attn_inputs, n_layers)))
+    alg = algorithmic(cfg)
+    tokens = cfg["B"] * cfg["Tq"]
+
+    log("prefill 1-in-4 arm")
+    ic.prof_reset()
+    for _ in range(args.warmup):
+        stack.step(mask_14)
+    torch.cuda.synchronize()
+    ic.prof_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stack.step(mask_14)
+    torch.cuda.synchronize()
+    ms_14 = (time.perf_counter() - t0) * 1e3 / args.steps
+    ic.prof_enable(False)
+    prof_14 = prof_snapshot(ic)
+
+    log("prefill all-Full arm")
+    ms_all = time_steps(lambda: stack.step(mask_all), max(1, args.steps - 1), 1)
+
+    def per_launch(prof, name):
+        n, ms = prof[name]
+        return (ms / n) if n else None
+
+    # per-layer kernel time (one layer = all its launches of that class)
+    n_full = sum(mask_14)
+    t_score = prof_14["indexer_score"][1] / (args.steps * n_full)
+    t_select = prof_14["topk_select"][1] / (args.steps * n_full)
+    t_attn = prof_14["sparse_attn"][1] / (args.steps * n_layers)
+    kernels = {
+        "indexer_score": {"bound": "mfma", "ms_per_layer": t_score,
+                          "achieved": alg["indexer_flop"] / (t_score * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                          "unit": "TFLOP/s", "launches_per_layer": prof_14["indexer_score"][0] / (args.steps * n_full)},
+        "topk_select": {"bound": "hbm", "ms_per_layer": t_select,
+                        "achieved": alg["select_bytes"] / (t_select * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "launches_per_layer": prof_14["topk_select"][0] / (args.steps * n_full)},
+        "sparse_attn": {"bound": "hbm", "ms_per_layer": t_attn,
+                        "achieved": alg["attn_bytes"] / (t_attn * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "launches_per_layer": prof_14["sparse_attn"][0] / (args.steps * n_layers),
+                        "mfma_tflops": alg["attn_flop"] / (t_attn * 1e-3) / 1e12},
+    }
+    for k in kernels.values():
+        k["frac"] = k["achieved"] / k["peak"]
+    # dominant kernel of the timed step = largest share of the step's time
+    share = {"indexer_score": t_score * n_full, "topk_select": t_select * n_full, "sparse_attn": t_attn * n_layers}
+    dom = max(share, key=share.get)
+    roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
+                "peak": kernels[dom]["peak"], "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
+                "traffic": None, "avg_launch_ms": per_launch(prof_14, dom),
+                "share_of_step": share[dom] / sum(share.values())}
+
+    arms = {
+        "prefill_1in4": {"ms_per_step": ms_14, "tokens_per_s": tokens / (ms_14 * 1e-3), "full_layers": n_full},
+        "prefill_all_full": {"ms_per_step": ms_all, "tokens_per_s": tokens / (ms_all * 1e-3), "full_layers": n_layers},
+        "prefill_speedup_1in4_vs_all_full": ms_all / ms_14,
+    }
+
+    cpu = None
+    if not args.no_cpu:
+        log("cpu baseline (oracle, bounded sample)")
+        cpu = cpu_baseline(synth, cfg, stack.layers[0], n_full, n_layers)
+
+    del stack
+    torch.cuda.empty_cache()
+
+    # ---------------- decode: batch 32, context 65536, 4 layers ----------------
+    if not args.no_decode:
+        dcfg = synth.config("c2")
+        log("decode inputs")
+        dstack = Stack(ic, synth, dcfg, dcfg["n_layers"], dcfg["n_layers"])
+        dalg = algorithmic(dcfg)
+        m_fsss = ic.pattern_from_string("FSSS")
+        m_ffff = [True] * 4
+        ms_d14 = time_steps(lambda: dstack.step(m_fsss), args.decode_steps, 3)
+        ms_dall = time_steps(lambda: dstack.step(m_ffff), args.decode_steps, 3)
+        ic.prof_reset()
+        ic.prof_enable(True)
+        for _ in range(5):
+            dstack.step(m_ffff)
+        torch.cuda.synchronize()
+        ic.prof_enable(False)
+        dp = prof_snapshot(ic)
+        d_idx = (dp["indexer_score"][1] + dp["topk_select"][1]) / (5 * 4)
+        d_att = (dp["sparse_attn"][1] + dp["attn_merge"][1]) / (5 * 4)
+        arms.update({
+            "decode_1in4": {"ms_per_step": ms_d14, "tokens_per_s": dcfg["B"] / (ms_d14 * 1e-3), "pattern": "FSSS"},
+            "decode_all_full": {"ms_per_step": ms_dall, "tokens_per_s": dcfg["B"] / (ms_dall * 1e-3), "pattern": "FFFF"},
+            "decode_speedup_1in4_vs_all_full": ms_dall / ms_d14,
+            "decode_kernels": {
+                "indexer_plus_topk": {"bound": "hbm", "ms_per_layer": d_idx,
+                                      "achieved": dalg["indexer_key_bytes"] / (d_idx * 1e-3) / 1e9,
+                                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                      "frac": dalg["indexer_key_bytes"] / (d_idx * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                "sparse_attn_plus_merge": {"bound": "hbm", "ms_per_layer": d_att,
+                                           "achieved": dalg["attn_bytes"] / (d_att * 1e-3) / 1e9,
+                                           "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                           "frac": dalg["attn_bytes"] / (d_att * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            },
+        })
+        del dstack
+
+    out = {
+        "metric": "prefill & decode tokens/s, 48-layer DSA stack L=32K, 1-in-4 Full vs all-Full",
+        "value": tokens / (ms_14 * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_14,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[3]: 48-layer attention-only DSA stack prefill, 1 sequence, L=32768, "
+                               "H_I=32 d_I=128 k=2048, MQA 32 heads, KV row 576 bf16, 1-in-4 Full (value); "
+                               "all-Full and decode (configs[2]) in arms",
+                   "layers": n_layers, "pattern": "FSSS x%d" % (n_layers // 4), "L": cfg["Tq"], "k_sel": cfg["k_sel"],
+                   "distinct_attn_inputs": min(args.distinct_attn_inputs, n_layers)},
+        "roofline": roofline,
+        "kernels": kernels,
+        "arms": arms,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

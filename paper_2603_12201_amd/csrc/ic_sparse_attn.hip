@@ -290,9 +290,9 @@ hipError_t launch_t(const AttnArgs &a, hipStream_t st)
     constexpr int ROWB = ROW_F * 2 + 16;
     const size_t lds = (size_t)2 * kTile * ROWB + 3 * kTile * sizeof(int32_t) + 2 * 2 * 16 * 2 * sizeof(float);
     static_assert((size_t)2 * (D_V / 16) * 4 * 64 * 4 <= (size_t)2 * kTile * ROWB, "partner O must fit in the tile buffers");
-    hipError_t e = hipFuncSetAttribute((const void *)attn_kernel<D_QK, D_V, ROW_F>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    static hipError_t attr = hipFuncSetAttribute((const void *)attn_kernel<D_QK, D_V, ROW_F>,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (attr != hipSuccess) return attr;
     dim3 grid((unsigned)((int64_t)a.B * a.Tq), (unsigned)a.n_splits);
     hipLaunchKernelGGL((attn_kernel<D_QK, D_V, ROW_F>), grid, dim3(256), lds, st, a);
     return hipGetLastError();

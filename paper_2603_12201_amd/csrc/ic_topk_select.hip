@@ -189,16 +189,19 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     if (max_row_len <= a.k_sel) cache = 0;     // short rows never reach the radix path
     a.cache_elems = cache;
     const size_t lds = select_lds_bytes(cache);
-    hipError_t e;
-    if (max_row_len <= 8192) {
-        e = hipFuncSetAttribute((const void *)select_kernel<256>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+    // opt in once per process to the largest LDS footprint either variant can ask for
+    static hipError_t attr256 = hipFuncSetAttribute((const void *)select_kernel<256>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                    (int)select_lds_bytes(8192));
+    static hipError_t attr1024 = hipFuncSetAttribute((const void *)select_kernel<1024>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                     (int)select_lds_bytes(select_cache_limit()));
+    if (attr256 != hipSuccess) return attr256;
+    if (attr1024 != hipSuccess) return attr1024;
+    if (max_row_len <= 8192)
         hipLaunchKernelGGL((select_kernel<256>), dim3((unsigned)n_rows), dim3(256), lds, st, a);
-    } else {
-        e = hipFuncSetAttribute((const void *)select_kernel<1024>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
+    else
         hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);
-    }
     return hipGetLastError();
 }
 
