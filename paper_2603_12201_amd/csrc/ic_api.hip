@@ -118,12 +118,12 @@ ic_status check_attn(const ic_attn_desc *d)
 }
 
 // Key-slot splits per query: one workgroup per query when there are enough queries to fill the
-// chip, otherwise split the k_sel slots so that about 256 workgroups exist.
+// chip (two workgroups per CU), otherwise split the k_sel slots so that about 512 workgroups exist.
 void attn_splits(const ic_attn_desc *d, int *n_splits, int *split_len)
 {
     const int64_t nq = (int64_t)d->B * d->Tq;
     const int tiles = (d->k_sel + 63) / 64;
-    int64_t want = nq >= 256 ? 1 : (256 + nq - 1) / nq;
+    int64_t want = nq >= 512 ? 1 : (512 + nq - 1) / nq;
     if (want > tiles) want = tiles;
     const int tiles_per = (int)((tiles + want - 1) / want);
     *split_len = tiles_per * 64;

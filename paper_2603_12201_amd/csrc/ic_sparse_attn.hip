@@ -1,46 +1,77 @@
 // Sparse MQA core attention over the selected KV rows (paper Sec. 2.1: the main attention is
 // computed only over the top-k subset; MLA form, one shared KV row per position).
 //
-// One workgroup (4 waves) per query token and key-slot split.  Tiles of 64 selected rows are
-// gathered with 16-byte coalesced loads (each row is contiguous) into a double-buffered LDS
-// tile, row-major.  Every wave is an independent online-softmax worker on 16 of the 32 heads
-// and 32 of the 64 tile rows:
+// One workgroup (4 waves) per query token and key-slot split; two workgroups fit a CU (75 KB of
+// LDS, <= 256 VGPRs each) so that one computes while the other waits for its gather.  Tiles of
+// 32 selected rows are gathered with 16-byte coalesced loads (each row is contiguous) into a
+// double-buffered LDS tile, row-major.  A wave owns 16 of the 32 heads and half of the value
+// columns, and runs its own online softmax over every row of the tile:
 //   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = tile rows (16-byte LDS reads), B = Q (registers)
 //   P   = exp2(S^T * scale*log2e - m)   in the result layout: a lane owns one head, 8 keys
 //   O  += P V     same MFMA; P is already an A operand (its contraction slots are whatever keys
 //                 the lane holds), and V comes out of the SAME row-major tile through the LDS
 //                 transpose read ds_read_b64_tr_b16, which hands a lane one value column of four
 //                 consecutive tile rows.  No transposed copy of V is ever made.
-// The two waves that share a head group merge their (m, l, O) once at the end through LDS; with
-// several splits per query the unnormalised partials go to the workspace and a small kernel
-// merges them.
+// The two waves of a head group compute the same S^T (cheap next to the gather) and therefore
+// the same softmax statistics, so no exchange between waves is ever needed.  With several
+// splits per query the unnormalised partials go to the workspace and a small kernel merges them.
 #include "ic_common.hpp"
 
 namespace ic {
 
 namespace {
 
-constexpr int kTile = 64;
+constexpr int kTile = 32;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+template <int ROW_F, int LPT>
+__device__ __forceinline__ void attn_gload(u32x4 (&pre)[LPT], const unsigned short *kv_seq, const int32_t *ti,
+                                           int row_elems, int tid)
+{
+    constexpr int CPR = ROW_F / 8;
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+        const int u = tid + 256 * r;
+        if (u < kTile * CPR) {
+            const int row = u / CPR, col = u % CPR;
+            const int32_t v = ti[row];
+            pre[r] = *(const u32x4 *)(kv_seq + ((int64_t)(v < 0 ? 0 : v) * row_elems + col * 8));
+        }
+    }
+}
+
+template <int ROW_F, int LPT, int ROWB>
+__device__ __forceinline__ void attn_lstore(const u32x4 (&pre)[LPT], unsigned char *tile, int tid)
+{
+    constexpr int CPR = ROW_F / 8;
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) {
+        const int u = tid + 256 * r;
+        if (u < kTile * CPR) {
+            const int row = u / CPR, col = u % CPR;
+            *(u32x4 *)(tile + row * ROWB + col * 16) = pre[r];
+        }
+    }
+}
+
 template <int D_QK, int D_V, int ROW_F>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
+__global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 {
     constexpr int ROWB = ROW_F * 2 + 16;                  // LDS row stride in bytes
     constexpr int CPR = ROW_F / 8;                        // 16-byte chunks staged per row
     constexpr int LPT = (kTile * CPR + 255) / 256;        // chunk loads per thread per tile
     constexpr int KSTEPS = D_QK / 32;
-    constexpr int NB = D_V / 16;
+    constexpr int DVW = D_V / 2;                          // value columns per wave
+    constexpr int NB = DVW / 16;
     constexpr int TILEB = kTile * ROWB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char *tile0 = smem;                          // [2][kTile][ROWB]
     int32_t *tidx = (int32_t *)(smem + 2 * TILEB);        // [3][kTile] validated row ids of a tile
-    float *stats = (float *)(tidx + 3 * kTile);           // [2 kh][2 mh][16][2]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
-    const int mh = wave & 1, kh = wave >> 1;
+    const int mh = wave & 1, vh = wave >> 1;
     const int64_t qrow = blockIdx.x;                      // flattened (b, t)
     const int b = (int)(qrow / a.Tq);
     const int sp = blockIdx.y;
@@ -51,7 +82,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
     const int32_t *idx_row = a.idx + qrow * a.k_sel;
     const unsigned short *kv_seq = (const unsigned short *)a.KV + (int64_t)b * a.Lk * a.row_elems;
 
-    auto fetch_idx = [&](int it) -> int32_t {             // threads 0..63: validated row id of a slot
+    auto fetch_idx = [&](int it) -> int32_t {             // threads 0..31: validated row id of a slot
         const int slot = slot0 + it * kTile + tid;
         int32_t v = -1;
         if (it < ntiles && slot < slot1) v = idx_row[slot];
@@ -73,39 +104,16 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
         }
     }
 
-    u32x4 pre[LPT];
-    auto gload = [&](int it) {                            // gather tile `it` into registers
-        const int32_t *ti = tidx + (it % 3) * kTile;
-#pragma unroll
-        for (int r = 0; r < LPT; ++r) {
-            const int u = tid + 256 * r;
-            if (u < kTile * CPR) {
-                const int row = u / CPR, col = u % CPR;
-                const int32_t v = ti[row];
-                pre[r] = *(const u32x4 *)(kv_seq + ((int64_t)(v < 0 ? 0 : v) * a.row_elems + col * 8));
-            }
-        }
-    };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int r = 0; r < LPT; ++r) {
-            const int u = tid + 256 * r;
-            if (u < kTile * CPR) {
-                const int row = u / CPR, col = u % CPR;
-                *(u32x4 *)(tile0 + buf * TILEB + row * ROWB + col * 16) = pre[r];
-            }
-        }
-    };
-
     // ---- prologue ----
     if (tid < kTile) {
         tidx[0 * kTile + tid] = fetch_idx(0);
         tidx[1 * kTile + tid] = fetch_idx(1);
     }
     __syncthreads();
+    u32x4 pre[LPT];
     if (ntiles > 0) {
-        gload(0);
-        lstore(0);
+        attn_gload<ROW_F, LPT>(pre, kv_seq, tidx, a.row_elems, tid);
+        attn_lstore<ROW_F, LPT, ROWB>(pre, tile0, tid);
     }
     __syncthreads();
 
@@ -120,32 +128,31 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
         const int buf = it & 1;
         int32_t nxt_idx = -1;
         if (tid < kTile) nxt_idx = fetch_idx(it + 2);
-        if (it + 1 < ntiles) gload(it + 1);
+        if (it + 1 < ntiles) attn_gload<ROW_F, LPT>(pre, kv_seq, tidx + ((it + 1) % 3) * kTile, a.row_elems, tid);
 
         if (wave_ok) {
             const unsigned char *tb = tile0 + buf * TILEB;
-            // S^T for the wave's 32 rows (two 16-row blocks) x 16 heads
+            // S^T for the tile's 32 rows (two 16-row blocks) x this wave's 16 heads
             f32x4 sacc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int ks = 0; ks < KSTEPS; ++ks) {
 #pragma unroll
                 for (int blk = 0; blk < 2; ++blk) {
-                    const bf16x8 ka = *(const bf16x8 *)(tb + (32 * kh + 16 * blk + l16) * ROWB + (32 * ks + 8 * g) * 2);
+                    const bf16x8 ka = *(const bf16x8 *)(tb + (16 * blk + l16) * ROWB + (32 * ks + 8 * g) * 2);
                     sacc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[ks], sacc[blk], 0, 0, 0);
                 }
             }
-            // validity of the lane's 8 key slots: rows 32kh + 16blk + 4g + i
+            // validity of the lane's 8 key slots: rows 16blk + 4g + i
             const int32_t *ti = tidx + (it % 3) * kTile;
             float z[8];
             bool ok[8];
             float mx = -INFINITY;
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
-                const i32x4 rv = *(const i32x4 *)(ti + 32 * kh + 16 * blk + 4 * g);
-                const int32_t rvv[4] = {rv[0], rv[1], rv[2], rv[3]};
+                const i32x4 rv = *(const i32x4 *)(ti + 16 * blk + 4 * g);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    ok[4 * blk + i] = rvv[i] >= 0;
+                    ok[4 * blk + i] = rv[i] >= 0;
                     z[4 * blk + i] = sacc[blk][i] * a.scale_log2e;
                     if (ok[4 * blk + i]) mx = fmaxf(mx, z[4 * blk + i]);
                 }
@@ -177,7 +184,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
 #pragma unroll
             for (int j = 0; j < 8; ++j) pa[j] = (__bf16)pv[j];
             // O += P V : V columns of 4 consecutive tile rows through the LDS transpose read
-            const unsigned char *vb0 = tb + (32 * kh + 4 * g + (l16 >> 2)) * ROWB + (a.v_off + 4 * (l16 & 3)) * 2;
+            const unsigned char *vb0 = tb + (4 * g + (l16 >> 2)) * ROWB + (a.v_off + DVW * vh + 4 * (l16 & 3)) * 2;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -190,106 +197,80 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a)
             }
         }
 
-        if (it + 1 < ntiles) lstore(buf ^ 1);
+        if (it + 1 < ntiles) attn_lstore<ROW_F, LPT, ROWB>(pre, tile0 + (buf ^ 1) * TILEB, tid);
         if (tid < kTile) tidx[((it + 2) % 3) * kTile + tid] = nxt_idx;
         __syncthreads();
     }
+    if (!wave_ok) return;
 
-    // ---- merge the two key-halves of each head group ----
+    // ---- epilogue: this wave's heads x its value columns ----
     float l_tot = l_run + __shfl_xor(l_run, 16);
-    l_tot += __shfl_xor(l_tot, 32);
-    float *xo = (float *)smem;                            // [2 mh][NB*4][64] partner O (tiles are dead now)
-    if (g == 0) {
-        stats[((kh * 2 + mh) * 16 + l16) * 2 + 0] = m_run;
-        stats[((kh * 2 + mh) * 16 + l16) * 2 + 1] = l_tot;
-    }
-    if (kh == 1) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) xo[(mh * NB * 4 + nb * 4 + i) * 64 + lane] = oacc[nb][i];
-    }
-    __syncthreads();
-    if (kh != 0 || !wave_ok) return;
-
+    l_tot += __shfl_xor(l_tot, 32);                       // every lane: full sum of head l16
     const bool split = a.n_splits > 1;
-    // per-lane head l16: log-sum-exp (or the split's m, l)
-    {
-        const float m0 = m_run, l0 = l_tot;
-        const float m1 = stats[((1 * 2 + mh) * 16 + l16) * 2 + 0];
-        const float l1 = stats[((1 * 2 + mh) * 16 + l16) * 2 + 1];
-        const float m = fmaxf(m0, m1);
-        const float a0 = (m0 == -INFINITY) ? 0.f : fast_exp2(m0 - m);
-        const float a1 = (m1 == -INFINITY) ? 0.f : fast_exp2(m1 - m);
-        const float l = l0 * a0 + l1 * a1;
-        if (g == 0 && head_ok) {
-            if (split) {
-                float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + head) * 2;
-                ml[0] = m;
-                ml[1] = l;
-            } else if (a.lse) {
-                a.lse[qrow * a.H_q + head] = (l > 0.f) ? (m + __builtin_log2f(l)) * 0.6931471805599453f : -INFINITY;
-            }
+    if (vh == 0 && g == 0 && head_ok) {
+        if (split) {
+            float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + head) * 2;
+            ml[0] = m_run;
+            ml[1] = l_tot;
+        } else if (a.lse) {
+            a.lse[qrow * a.H_q + head] =
+                (l_tot > 0.f) ? (m_run + __builtin_log2f(l_tot)) * 0.6931471805599453f : -INFINITY;
         }
     }
-    // O rows of this lane: heads 16mh + 4g + i
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int hr = 4 * g + i;
+        const int hr = 4 * g + i;                         // O row of this lane
         const int hq = 16 * mh + hr;
-        const float m0 = stats[((0 * 2 + mh) * 16 + hr) * 2 + 0], l0 = stats[((0 * 2 + mh) * 16 + hr) * 2 + 1];
-        const float m1 = stats[((1 * 2 + mh) * 16 + hr) * 2 + 0], l1 = stats[((1 * 2 + mh) * 16 + hr) * 2 + 1];
-        const float m = fmaxf(m0, m1);
-        const float a0 = (m0 == -INFINITY) ? 0.f : fast_exp2(m0 - m);
-        const float a1 = (m1 == -INFINITY) ? 0.f : fast_exp2(m1 - m);
-        const float l = l0 * a0 + l1 * a1;
+        const float l = __shfl(l_tot, hr);                // the sum lives in the lanes with l16 == hr
         if (hq >= a.H_q) continue;
         if (split) {
-            float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V;
+            float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + DVW * vh;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                po[16 * nb + l16] = oacc[nb][i] * a0 + xo[(mh * NB * 4 + nb * 4 + i) * 64 + lane] * a1;
+            for (int nb = 0; nb < NB; ++nb) po[16 * nb + l16] = oacc[nb][i];
         } else {
             const float inv = (l > 0.f) ? 1.f / l : 0.f;
-            __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V;
+            __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + DVW * vh;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                po[16 * nb + l16] = (__bf16)((oacc[nb][i] * a0 + xo[(mh * NB * 4 + nb * 4 + i) * 64 + lane] * a1) * inv);
+            for (int nb = 0; nb < NB; ++nb) po[16 * nb + l16] = (__bf16)(oacc[nb][i] * inv);
         }
     }
 }
 
-// Combine the per-split partials of one query: O = sum_s O_s 2^(m_s-m) / sum_s l_s 2^(m_s-m).
+// Combine the per-split partials of one (query, head): O = sum_s O_s 2^(m_s-m) / sum_s l_s 2^(m_s-m).
+// One workgroup per (query, head); a thread owns 4 consecutive value columns.
 template <int D_V>
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
+__global__ __launch_bounds__(D_V / 4) void attn_merge_kernel(AttnArgs a)
 {
     const int64_t qrow = blockIdx.x;
-    const int n = a.H_q * D_V;
-    for (int e = threadIdx.x; e < n; e += 256) {
-        const int h = e / D_V, v = e % D_V;
-        float m = -INFINITY;
-        for (int s = 0; s < a.n_splits; ++s)
-            m = fmaxf(m, a.part_ml[((qrow * a.n_splits + s) * a.H_q + h) * 2 + 0]);
-        float l = 0.f, o = 0.f;
-        for (int s = 0; s < a.n_splits; ++s) {
-            const float ms = a.part_ml[((qrow * a.n_splits + s) * a.H_q + h) * 2 + 0];
-            const float ls = a.part_ml[((qrow * a.n_splits + s) * a.H_q + h) * 2 + 1];
-            const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - m);
-            l += ls * sc;
-            o += a.part_o[((qrow * a.n_splits + s) * a.H_q + h) * D_V + v] * sc;
-        }
-        ((__bf16 *)a.O)[(qrow * a.H_q + h) * D_V + v] = (__bf16)((l > 0.f) ? o / l : 0.f);
-        if (v == 0 && a.lse)
-            a.lse[qrow * a.H_q + h] = (l > 0.f) ? (m + __builtin_log2f(l)) * 0.6931471805599453f : -INFINITY;
+    const int h = blockIdx.y;
+    const int v = threadIdx.x * 4;
+    const float *ml = a.part_ml + ((qrow * a.n_splits) * a.H_q + h) * 2;
+    const int64_t ml_stride = (int64_t)a.H_q * 2;
+    float m = -INFINITY;
+    for (int s = 0; s < a.n_splits; ++s) m = fmaxf(m, ml[s * ml_stride]);
+    float l = 0.f;
+    f32x4 o = {0.f, 0.f, 0.f, 0.f};
+    const float *po = a.part_o + ((qrow * a.n_splits) * a.H_q + h) * D_V + v;
+    for (int s = 0; s < a.n_splits; ++s) {
+        const float ms = ml[s * ml_stride], ls = ml[s * ml_stride + 1];
+        const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - m);
+        l += ls * sc;
+        const f32x4 x = *(const f32x4 *)(po + (int64_t)s * a.H_q * D_V);
+        o += x * sc;
     }
+    const float inv = (l > 0.f) ? 1.f / l : 0.f;
+    __bf16 *out = (__bf16 *)a.O + (qrow * a.H_q + h) * D_V + v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out[j] = (__bf16)(o[j] * inv);
+    if (threadIdx.x == 0 && a.lse)
+        a.lse[qrow * a.H_q + h] = (l > 0.f) ? (m + __builtin_log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
 template <int D_QK, int D_V, int ROW_F>
 hipError_t launch_t(const AttnArgs &a, hipStream_t st)
 {
     constexpr int ROWB = ROW_F * 2 + 16;
-    const size_t lds = (size_t)2 * kTile * ROWB + 3 * kTile * sizeof(int32_t) + 2 * 2 * 16 * 2 * sizeof(float);
-    static_assert((size_t)2 * (D_V / 16) * 4 * 64 * 4 <= (size_t)2 * kTile * ROWB, "partner O must fit in the tile buffers");
+    const size_t lds = (size_t)2 * kTile * ROWB + 3 * kTile * sizeof(int32_t);
     static hipError_t attr = hipFuncSetAttribute((const void *)attn_kernel<D_QK, D_V, ROW_F>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return attr;
@@ -316,11 +297,11 @@ hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st)
 hipError_t launch_attn_merge(const AttnArgs &a, int d_v, hipStream_t st)
 {
     if ((int64_t)a.B * a.Tq <= 0) return hipSuccess;
-    dim3 grid((unsigned)((int64_t)a.B * a.Tq));
+    dim3 grid((unsigned)((int64_t)a.B * a.Tq), (unsigned)a.H_q);
     if (d_v == 512)
-        hipLaunchKernelGGL((attn_merge_kernel<512>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attn_merge_kernel<512>), grid, dim3(128), 0, st, a);
     else if (d_v == 64)
-        hipLaunchKernelGGL((attn_merge_kernel<64>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attn_merge_kernel<64>), grid, dim3(16), 0, st, a);
     else
         return hipErrorInvalidValue;
     return hipGetLastError();
