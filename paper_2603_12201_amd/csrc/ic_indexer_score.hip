@@ -11,6 +11,12 @@
 // loop; key tiles (64 keys) are staged through LDS, double buffered, one barrier per tile,
 // and shared by the four waves of the workgroup (each wave owns TPW tokens).
 //
+// Occupancy.  A wave cannot overlap its own MFMAs with its own VALU epilogue (both issue through
+// the same port), and the epilogue costs about as many cycles as the MFMAs.  Two workgroups per
+// CU (two waves per SIMD, <= 256 registers each) let one wave's epilogue run under the other's
+// MFMAs; that caps a wave at 3 tokens (96 q + 48 w registers), which still reuses every B
+// operand read from LDS three times (LDS return bandwidth, ~64 B/clk/CU, is the next limit).
+//
 // The kernel writes scores of the query rows in flight into a strip (rows x Lk fp32); it
 // never holds more rows than the caller's workspace allows.  Keys hidden by the causal mask
 // are not written.
@@ -21,40 +27,48 @@ namespace ic {
 namespace {
 
 // Global -> register -> LDS staging of one tile of 64 key rows (16-byte chunks, coalesced).
-template <int DI, int LPT>
+template <int DI, int LPT, int NT>
 __device__ __forceinline__ void tile_gload(u32x4 (&pre)[LPT], const unsigned short *kp, int kt, int Lk, int tid)
 {
     constexpr int CPR = DI / 8;
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
-        const int c = tid + 256 * r;
+        const int c = tid + NT * r;
         const int row = c / CPR, col = c % CPR;
         const int s = min(kt + row, Lk - 1);                // clamp: rows past Lk are masked later
         pre[r] = *(const u32x4 *)(kp + ((int64_t)s * DI + col * 8));
     }
 }
 
-template <int DI, int LPT, int ROWB>
+template <int DI, int LPT, int ROWB, int NT>
 __device__ __forceinline__ void tile_lstore(const u32x4 (&pre)[LPT], unsigned char *buf, int tid)
 {
     constexpr int CPR = DI / 8;
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
-        const int c = tid + 256 * r;
+        const int c = tid + NT * r;
         const int row = c / CPR, col = c % CPR;
         *(u32x4 *)(buf + row * ROWB + col * 16) = pre[r];
     }
 }
 
-template <int HT, int DI, int TPW>
-__global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
+// ReLU on the bit pattern: a non-positive float (including -0) is a non-positive integer.
+__device__ __forceinline__ float relu(float x)
 {
+    const int xi = __float_as_int(x);
+    return __int_as_float(xi > 0 ? xi : 0);
+}
+
+template <int HT, int DI, int TPW, int NW>
+__global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_kernel(ScoreArgs a)
+{
+    constexpr int NT = 64 * NW;                 // threads per workgroup
     constexpr int KS = DI / 16;                 // MFMA k-steps over the head dim
-    constexpr int BT = 4 * TPW;                 // tokens per workgroup
+    constexpr int BT = NW * TPW;                // tokens per workgroup
     constexpr int ROWB = DI * 2 + 16;           // LDS row stride (bytes), padded against bank conflicts
     constexpr int TILE = 64;                    // keys per LDS tile
     constexpr int CPR = DI / 8;                 // 16-byte chunks per key row
-    constexpr int LPT = TILE * CPR / 256;       // 16-byte loads per thread per tile
+    constexpr int LPT = TILE * CPR / NT;        // 16-byte loads per thread per tile
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][TILE * ROWB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -105,33 +119,89 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
         }
     }
 
-    // ---- key tile pipeline ----
+    // ---- key tile pipeline: global -> registers -> LDS, double buffered, one barrier per tile ----
     const unsigned short *kp = (const unsigned short *)a.k + (int64_t)b * a.Lk * DI;
     u32x4 pre[LPT];
     const int ntiles = (kend - kc0 + TILE - 1) / TILE;
-    tile_gload<DI, LPT>(pre, kp, kc0, a.Lk, tid);
-    tile_lstore<DI, LPT, ROWB>(pre, &lds[0][0], tid);
+    tile_gload<DI, LPT, NT>(pre, kp, kc0, a.Lk, tid);
+    tile_lstore<DI, LPT, ROWB, NT>(pre, &lds[0][0], tid);
     __syncthreads();
+
+    // Combine the two half-wave partial sums of a token pair (or of one token with itself) and
+    // store 32 scores per row.  permlane32_swap(x, y) returns {[x.lo, y.lo], [x.hi, y.hi]}: their
+    // sum is token A's total in lanes 0-31 and token B's in lanes 32-63.
+    auto emit = [&](float pa, float pb, bool pair, int j, int s0, bool interior) {
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(pa), __float_as_uint(pb), false, false);
+        const float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+        const int t = t_w0 + j + half;
+        const int s = s0 + r32;
+        const bool lane_on = pair || half == 0;
+        if (lane_on && (interior || (t < i_end && s < a.Lk && (int64_t)s <= a.q_pos0 + t))) {
+            const int64_t srow = (int64_t)blockIdx.z * a.Ri + (t - a.i0);
+            a.strip[srow * a.ld + s] = v;
+        }
+    };
 
     for (int it = 0; it < ntiles; ++it) {
         const int kt = kc0 + it * TILE;
         const int buf = it & 1;
-        if (it + 1 < ntiles) tile_gload<DI, LPT>(pre, kp, kt + TILE, a.Lk, tid);
+        if (it + 1 < ntiles) tile_gload<DI, LPT, NT>(pre, kp, kt + TILE, a.Lk, tid);
 
+        // Interior tile: all 64 keys are visible to every token of this wave and every token is a
+        // real row, so nothing needs masking and the whole tile is one straight-line block.
+        const bool interior = (t_w0 + TPW <= i_end) && (kt + TILE <= a.Lk) &&
+                              ((int64_t)(kt + TILE - 1) <= a.q_pos0 + t_w0);
+        if (interior) {
+            // Software pipeline over the units (key subtile, token, head tile): the MFMA chain of unit
+            // c+1 is issued before the ReLU/weight/sum epilogue of unit c, so the matrix pipe works
+            // under this wave's own VALU epilogue as well as under the other wave's.
+            bf16x8 kb[KS];                                  // B operands of the subtile being multiplied
+            auto load_kb = [&](int sub) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int s0 = kt + sub * 32;
-            if (s0 >= wave_vis) continue;                   // wave-uniform
-            bf16x8 kb[KS];
+                for (int ks = 0; ks < KS; ++ks)
+                    kb[ks] = *(const bf16x8 *)(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 16 + half * 8) * 2]);
+            };
+            constexpr int NCH = 2 * TPW * HT;
+            f32x16 acc[2];
+            float part[TPW];
+            auto chain = [&](int c) -> f32x16 {
+                const int x = c / HT, ht = c % HT, j = x % TPW;
+                if (c % (TPW * HT) == 0) load_kb(x / TPW);  // first unit of a subtile
+                f32x16 r;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                kb[ks] = *(const bf16x8 *)(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 16 + half * 8) * 2]);
+                for (int i = 0; i < 16; ++i) r[i] = 0.f;
 #pragma unroll
-            for (int p = 0; p < TPW / 2; ++p) {
-                float part[2];
+                for (int ks = 0; ks < KS; ++ks)
+                    r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[j][ht][ks], kb[ks], r, 0, 0, 0);
+                return r;
+            };
+            acc[0] = chain(0);
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int j = 2 * p + u;
+            for (int c = 0; c < NCH; ++c) {
+                if (c + 1 < NCH) acc[(c + 1) & 1] = chain(c + 1);
+                const int x = c / HT, ht = c % HT, sub = x / TPW, j = x % TPW;
+                float s_acc = (ht == 0) ? 0.f : part[j];
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    s_acc = fmaf(relu(acc[c & 1][i]), wr[j][ht][i], s_acc);
+                part[j] = s_acc;
+                if (ht == HT - 1) {
+                    if (j & 1) emit(part[j - 1], part[j], true, j - 1, kt + sub * 32, true);
+                    else if (j == TPW - 1) emit(part[j], part[j], false, j, kt + sub * 32, true);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int s0 = kt + sub * 32;
+                if (s0 >= wave_vis) continue;               // wave-uniform: hidden from all its tokens
+                bf16x8 kb[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    kb[ks] = *(const bf16x8 *)(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 16 + half * 8) * 2]);
+                float part[TPW];
+#pragma unroll
+                for (int j = 0; j < TPW; ++j) {
                     float s_acc = 0.f;
 #pragma unroll
                     for (int ht = 0; ht < HT; ++ht) {
@@ -143,24 +213,19 @@ __global__ __launch_bounds__(256) void score_kernel(ScoreArgs a)
                             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[j][ht][ks], kb[ks], acc, 0, 0, 0);
 #pragma unroll
                         for (int i = 0; i < 16; ++i)
-                            s_acc = fmaf(fmaxf(acc[i], 0.f), wr[j][ht][i], s_acc);
+                            s_acc = fmaf(relu(acc[i]), wr[j][ht][i], s_acc);
                     }
-                    part[u] = s_acc;
+                    part[j] = s_acc;
                 }
-                // each half-wave holds 16 of the 32 head rows: add the other half's partial sum
-                const float tot0 = part[0] + __shfl_xor(part[0], 32);
-                const float tot1 = part[1] + __shfl_xor(part[1], 32);
-                const float v = half ? tot1 : tot0;         // lanes 0-31: token 2p, lanes 32-63: token 2p+1
-                const int t = t_w0 + 2 * p + half;
-                const int s = s0 + r32;
-                if (t < i_end && s < a.Lk && (int64_t)s <= a.q_pos0 + t) {
-                    const int64_t srow = (int64_t)blockIdx.z * a.Ri + (t - a.i0);
-                    a.strip[srow * a.ld + s] = v;
+#pragma unroll
+                for (int j = 0; j < TPW; j += 2) {
+                    const bool pair = j + 1 < TPW;
+                    emit(part[j], pair ? part[j + 1] : part[j], pair, j, s0, false);
                 }
             }
         }
 
-        if (it + 1 < ntiles) tile_lstore<DI, LPT, ROWB>(pre, &lds[buf ^ 1][0], tid);
+        if (it + 1 < ntiles) tile_lstore<DI, LPT, ROWB, NT>(pre, &lds[buf ^ 1][0], tid);
         __syncthreads();
     }
 }
@@ -172,13 +237,13 @@ __global__ void fill_kernel(float *p, int64_t n, float v)
     for (; i < n; i += stride) p[i] = v;
 }
 
-template <int HT, int DI, int TPW>
+template <int HT, int DI, int TPW, int NW>
 hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
 {
     const int n_kc = (int)((max_vis + a.KC - 1) / a.KC);
     if (n_kc <= 0 || a.n_qblocks <= 0 || Bc <= 0) return hipSuccess;
     dim3 grid((unsigned)a.n_qblocks, (unsigned)n_kc, (unsigned)Bc);
-    hipLaunchKernelGGL((score_kernel<HT, DI, TPW>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW>), grid, dim3(64 * NW), 0, st, a);
     return hipGetLastError();
 }
 
@@ -192,7 +257,7 @@ bool score_shape_supported(int dtype, int H_I, int d_I)
 }
 
 // Tokens per workgroup for a head count (the launcher and the host-side grid math agree on it).
-static int tokens_per_block(int H_I) { return H_I <= 32 ? 16 : 8; }
+static int tokens_per_block(int H_I) { return H_I <= 32 ? 12 : 8; }
 
 hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipStream_t st)
 {
@@ -209,11 +274,11 @@ hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipSt
     kc = kc < 512 ? 512 : (kc > 4096 ? 4096 : kc);
     a.KC = (int)kc;
     if (a.H_I <= 32) {
-        if (d_I == 128) return launch_t<1, 128, 4>(a, Bc, max_vis, st);
-        if (d_I == 64) return launch_t<1, 64, 4>(a, Bc, max_vis, st);
+        if (d_I == 128) return launch_t<1, 128, 3, 4>(a, Bc, max_vis, st);
+        if (d_I == 64) return launch_t<1, 64, 3, 4>(a, Bc, max_vis, st);
     } else {
-        if (d_I == 128) return launch_t<2, 128, 2>(a, Bc, max_vis, st);
-        if (d_I == 64) return launch_t<2, 64, 2>(a, Bc, max_vis, st);
+        if (d_I == 128) return launch_t<2, 128, 2, 4>(a, Bc, max_vis, st);
+        if (d_I == 64) return launch_t<2, 64, 2, 4>(a, Bc, max_vis, st);
     }
     return hipErrorInvalidValue;
 }
