@@ -1,11 +1,16 @@
 // Per-query top-k over a strip of indexer scores (T_t = Top-k(I_t), paper Sec. 3 Notation).
 //
-// One workgroup per query row.  Scores become order-preserving 32-bit keys; an MSB-first
-// radix select (four 8-bit digits, LDS histograms) finds the exact key of the k-th largest
-// score and how many entries equal to it belong to the result; one ordered pass then emits
-// every position whose key is larger, plus the first (lowest-position) entries that tie with
-// it, in ascending position order.  Rows of up to `cache_elems` scores are read from HBM once
-// and kept in LDS for all passes.
+// One workgroup per query row.  Scores become order-preserving 32-bit keys.  An MSB-first
+// radix select finds the exact key of the k-th largest score and how many entries equal to it
+// belong to the result; one ordered pass then emits every position whose key is larger, plus
+// the first (lowest-position) entries that tie with it, in ascending position order.
+//
+//   pass 1   12-bit digit (sign, exponent, 3 mantissa bits) over the whole row, fused with the
+//            single read of the row from HBM; rows of up to `cache_elems` keys stay in LDS
+//   pass 2,3 12 + 8 bits; only entries that match the prefix found so far touch the histogram,
+//            so these are read-mostly sweeps over the cached row
+//   emit     wave scan of per-thread counts (greater/equal packed in one word) + a scan of the
+//            wave totals; a thread owns 4 consecutive positions in every sweep
 #include "ic_common.hpp"
 
 namespace ic {
@@ -25,17 +30,60 @@ __device__ __forceinline__ float key_score(uint32_t key)
     return __uint_as_float(u);
 }
 
-constexpr int kCopies = 8; // histogram copies per digit (lanes spread over them)
+constexpr int kBins1 = 4096;   // histogram bins: digits of 12, 12 and 8 key bits
+
+// Workgroup-wide descending scan over `nbins` counters: finds the digit d with
+// count(bins > d) < need <= count(bins >= d) and writes {d, need - count(bins > d)} to bc.
+// Every thread owns BPT consecutive bins, highest bins first.
+template <int NT, int BPT>
+__device__ __forceinline__ void find_digit(const uint32_t *cnt, uint32_t need, uint32_t *wsum, uint32_t *bc,
+                                           int tid, int lane, int wave)
+{
+    constexpr int NW = NT / 64;
+    const int top = NT * BPT - 1 - BPT * tid;          // highest bin of this thread
+    uint32_t c[BPT];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < BPT; ++j) {
+        c[j] = cnt[top - j];
+        mine += c[j];
+    }
+    uint32_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0;
+#pragma unroll
+    for (int wv = 0; wv < NW; ++wv)
+        if (wv < wave) before += wsum[wv];
+    incl += before;
+    const uint32_t excl = incl - mine;
+    if (excl < need && need <= incl) {                 // exactly one thread
+        uint32_t run = excl;
+#pragma unroll
+        for (int j = 0; j < BPT; ++j) {
+            if (run < need && need <= run + c[j]) {
+                bc[0] = (uint32_t)(top - j);
+                bc[1] = need - run;
+            }
+            run += c[j];
+        }
+    }
+    __syncthreads();
+}
 
 template <int NT>
 __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
 {
     constexpr int NW = NT / 64;
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
-    uint32_t *hist = smem;                     // [256][kCopies]
-    uint32_t *cnt = hist + 256 * kCopies;      // [256]
-    uint32_t *wtot = cnt + 256;                // [2][NW] packed per-wave totals (double buffered)
-    uint32_t *bc = wtot + 2 * NW;              // [2] broadcast: chosen digit, remaining need
+    uint32_t *hist1 = smem;                    // [kBins1]
+    uint32_t *wsum = hist1 + kBins1;           // [2][NW] (scan partials / emit totals, double buffered)
+    uint32_t *bc = wsum + 2 * NW;              // [4] broadcast: digit, remaining need
     uint32_t *cache = bc + 4;                  // [cache_elems] keys of the row
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -59,68 +107,78 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     }
 
     const bool cached = nv <= a.cache_elems;   // workgroup-uniform
-    if (cached) {
-        for (int p = tid; p < nv; p += NT) cache[p] = score_key(row[p]);
-        __syncthreads();
-    }
     auto get_key = [&](int p) -> uint32_t { return cached ? cache[p] : score_key(row[p]); };
+    // four consecutive keys starting at p (p % 4 == 0); entries at or beyond nv are unspecified
+    auto get_key4 = [&](int p) -> u32x4 {
+        u32x4 k4 = u32x4{0u, 0u, 0u, 0u};
+        if (p < nv) {
+            if (cached) {
+                k4 = *(const u32x4 *)(cache + p);
+            } else {
+                const f32x4 v = *(const f32x4 *)(row + p);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) k4[e] = score_key(v[e]);
+            }
+        }
+        return k4;
+    };
 
-    // ---- radix select: exact key of the k-th largest score ----
-    uint32_t prefix = 0, prefix_mask = 0;
-    uint32_t need = (uint32_t)a.k_sel;         // entries still to take among keys matching prefix
-#pragma unroll 1
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        for (int e = tid; e < 256 * kCopies; e += NT) hist[e] = 0;
-        __syncthreads();
-        for (int p = tid; p < nv; p += NT) {
-            const uint32_t key = get_key(p);
-            if ((key & prefix_mask) == prefix)
-                atomicAdd(&hist[((key >> shift) & 255u) * kCopies + (lane & (kCopies - 1))], 1u);
-        }
-        __syncthreads();
-        if (tid < 256) {
-            uint32_t s = 0;
+    // ---- pass 1: 12-bit digit, fused with the read of the row ----
+    for (int e = tid; e < kBins1; e += NT) hist1[e] = 0;
+    __syncthreads();
+    {
+        // 16-byte loads, kLoadBatch of them in flight per thread: the strip lives in HBM and one
+        // workgroup per CU has to cover the whole memory latency by itself.  Rows start 256-byte
+        // aligned and are padded to a multiple of 64 floats, so the last vector may run past nv
+        // (never past the row); those lanes are masked.
+        constexpr int kLoadBatch = 4;
+        for (int base = 0; base < nv; base += NT * 4 * kLoadBatch) {
+            f32x4 v[kLoadBatch];
 #pragma unroll
-            for (int c = 0; c < kCopies; ++c) s += hist[tid * kCopies + c];
-            cnt[tid] = s;
-        }
-        __syncthreads();
-        if (wave == 0) {
-            // lane L owns digits 255-4L .. 252-4L (descending); find where the running count reaches need
-            uint32_t c4[4];
-            uint32_t mine = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                c4[j] = cnt[255 - 4 * lane - j];
-                mine += c4[j];
+            for (int u = 0; u < kLoadBatch; ++u) {
+                const int p = base + (u * NT + tid) * 4;
+                v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (p < nv) v[u] = *(const f32x4 *)(row + p);
             }
-            uint32_t incl = mine;
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t up = __shfl_up(incl, off);
-                if (lane >= off) incl += up;
-            }
-            const uint32_t excl = incl - mine;
-            if (excl < need && need <= incl) {           // exactly one lane
-                uint32_t run = excl;
-                int digit = 255 - 4 * lane;
-                uint32_t left = need;
+            for (int u = 0; u < kLoadBatch; ++u) {
+                const int p = base + (u * NT + tid) * 4;
+                if (p < nv) {
+                    u32x4 k4;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (run < need && need <= run + c4[j]) {
-                        digit = 255 - 4 * lane - j;
-                        left = need - run;
+                    for (int e = 0; e < 4; ++e) {
+                        k4[e] = score_key(v[u][e]);
+                        if (p + e < nv) atomicAdd(&hist1[k4[e] >> 20], 1u);
                     }
-                    run += c4[j];
+                    if (cached) *(u32x4 *)(cache + p) = k4;   // cache is 16-byte aligned, p % 4 == 0
                 }
-                bc[0] = (uint32_t)digit;
-                bc[1] = left;
             }
         }
+    }
+    __syncthreads();
+    find_digit<NT, kBins1 / NT>(hist1, (uint32_t)a.k_sel, wsum, bc, tid, lane, wave);
+    uint32_t prefix = bc[0] << 20, prefix_mask = 0xFFF00000u;
+    uint32_t need = bc[1];
+    __syncthreads();
+
+    // ---- passes 2 and 3: bits [19:8] and [7:0] of the entries that match the prefix so far ----
+#pragma unroll 1
+    for (int pass = 0; pass < 2; ++pass) {
+        const int shift = pass == 0 ? 8 : 0;
+        const uint32_t dmask = pass == 0 ? 4095u : 255u;
+        for (int e = tid; e < kBins1; e += NT) hist1[e] = 0;
         __syncthreads();
+        for (int p0 = 0; p0 < nv; p0 += 4 * NT) {
+            const int p = p0 + 4 * tid;
+            const u32x4 k4 = get_key4(p);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (p + e < nv && (k4[e] & prefix_mask) == prefix) atomicAdd(&hist1[(k4[e] >> shift) & dmask], 1u);
+        }
+        __syncthreads();
+        find_digit<NT, kBins1 / NT>(hist1, need, wsum, bc, tid, lane, wave);
         prefix |= bc[0] << shift;
-        prefix_mask |= 255u << shift;
+        prefix_mask |= dmask << shift;
         need = bc[1];
         __syncthreads();
     }
@@ -128,53 +186,64 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     const uint32_t need_eq = need;             // how many entries equal to tau are selected
 
     // ---- ordered emit: slot = #greater before + min(#equal before, need_eq) ----
-    uint32_t run_g = 0, run_e = 0;
-    const int nchunks = (nv + NT - 1) / NT;
+    // A thread owns 4 consecutive positions; counts of greater / equal entries travel packed in
+    // one word (equal << 16 | greater) through a wave scan and a 16-entry scan of the wave totals.
+    uint32_t run = 0;                                  // packed counts of all previous chunks
+    const int nchunks = (nv + 4 * NT - 1) / (4 * NT);
 #pragma unroll 1
     for (int c = 0; c < nchunks; ++c) {
-        const int p = c * NT + tid;
-        uint32_t key = 0;
-        bool g = false, e = false;
-        if (p < nv) {
-            key = get_key(p);
-            g = key > tau;
-            e = key == tau;
-        }
-        const unsigned long long mg = __ballot(g), me = __ballot(e);
-        const unsigned long long below = (1ull << lane) - 1ull;
-        const uint32_t g_in = (uint32_t)__popcll(mg & below), e_in = (uint32_t)__popcll(me & below);
-        uint32_t *wt = wtot + (c & 1) * NW;
-        if (lane == 0) wt[wave] = ((uint32_t)__popcll(me) << 16) | (uint32_t)__popcll(mg);
-        __syncthreads();
-        uint32_t g_before = run_g, e_before = run_e, g_all = 0, e_all = 0;
+        const int p = c * 4 * NT + 4 * tid;
+        const u32x4 k4 = get_key4(p);
+        uint32_t gm = 0, em = 0;
 #pragma unroll
-        for (int wv = 0; wv < NW; ++wv) {
-            const uint32_t t = wt[wv];
-            const uint32_t tg = t & 0xFFFFu, te = t >> 16;
-            if (wv < wave) {
-                g_before += tg;
-                e_before += te;
-            }
-            g_all += tg;
-            e_all += te;
-        }
-        g_before += g_in;
-        e_before += e_in;
-        if (g || (e && e_before < need_eq)) {
-            const uint32_t slot = g_before + (e_before < need_eq ? e_before : need_eq);
-            if (slot < (uint32_t)a.k_sel) {            // always true for a consistent select
-                oidx[slot] = p;
-                if (osel) osel[slot] = key_score(key);
+        for (int e = 0; e < 4; ++e) {
+            if (p + e < nv) {
+                gm |= (k4[e] > tau ? 1u : 0u) << e;
+                em |= (k4[e] == tau ? 1u : 0u) << e;
             }
         }
-        run_g += g_all;
-        run_e += e_all;
+        const uint32_t mine = ((uint32_t)__popc(em) << 16) | (uint32_t)__popc(gm);
+        uint32_t incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        uint32_t *wt = wsum + (c & 1) * NW;
+        if (lane == 63) wt[wave] = incl;
+        __syncthreads();
+        uint32_t ws = lane < NW ? wt[lane] : 0u;       // scan of the wave totals (NW <= 16)
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            const uint32_t up = __shfl_up(ws, off);
+            if (lane >= off) ws += up;
+        }
+        const uint32_t waves_before = wave == 0 ? 0u : __shfl(ws, wave - 1);
+        const uint32_t chunk_total = __shfl(ws, NW - 1);
+        uint32_t before = run + waves_before + incl - mine;
+        uint32_t g_before = before & 0xFFFFu, e_before = before >> 16;
+        if ((gm | em) != 0u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool g = (gm >> e) & 1u, q = (em >> e) & 1u;
+                if (g || (q && e_before < need_eq)) {
+                    const uint32_t slot = g_before + (e_before < need_eq ? e_before : need_eq);
+                    if (slot < (uint32_t)a.k_sel) {    // always true for a consistent select
+                        oidx[slot] = p + e;
+                        if (osel) osel[slot] = key_score(k4[e]);
+                    }
+                }
+                g_before += g ? 1u : 0u;
+                e_before += q ? 1u : 0u;
+            }
+        }
+        run += chunk_total;
     }
 }
 
 size_t select_lds_bytes(int cache_elems)
 {
-    return (size_t)(256 * kCopies + 256 + 2 * 16 + 4 + cache_elems) * sizeof(uint32_t);
+    return (size_t)(kBins1 + 2 * 16 + 4 + cache_elems) * sizeof(uint32_t);
 }
 
 } // namespace
