@@ -59,12 +59,17 @@ __device__ __forceinline__ float relu(float x)
     return __int_as_float(xi > 0 ? xi : 0);
 }
 
-template <int HT, int DI, int TPW, int NW>
-__global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_kernel(ScoreArgs a)
+// STREAM = true is the few-query-rows form (decode): the workgroup owns ONE token, every wave
+// keeps its q rows, and the waves take turns on the key subtiles (wave w multiplies subtile
+// w & 1 of the tiles with parity w >> 1) so that all four SIMDs share the little matrix work
+// while the kernel streams the key cache.
+template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM>
+__global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
 {
+    static_assert(!STREAM || (TPW == 1 && NW == 4), "the streaming form is one token, four waves");
     constexpr int NT = 64 * NW;                 // threads per workgroup
     constexpr int KS = DI / 16;                 // MFMA k-steps over the head dim
-    constexpr int BT = NW * TPW;                // tokens per workgroup
+    constexpr int BT = STREAM ? 1 : NW * TPW;   // tokens per workgroup
     constexpr int ROWB = DI * 2 + 16;           // LDS row stride (bytes), padded against bank conflicts
     constexpr int TILE = 64;                    // keys per LDS tile
     constexpr int CPR = DI / 8;                 // 16-byte chunks per key row
@@ -86,7 +91,7 @@ __global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_k
     const int kend = min(kc0 + a.KC, (int)vis64);
     if (kc0 >= kend) return;                               // whole workgroup: nothing visible here
 
-    const int t_w0 = t_blk + wave * TPW;                   // this wave's first token
+    const int t_w0 = STREAM ? t_blk : t_blk + wave * TPW;  // this wave's first token
     int64_t wv64 = a.q_pos0 + (int64_t)min(t_w0 + TPW, i_end);
     wv64 = wv64 < 0 ? 0 : (wv64 > a.Lk ? a.Lk : wv64);
     const int wave_vis = (t_w0 < i_end) ? (int)wv64 : 0;   // keys >= wave_vis matter to none of its tokens
@@ -121,10 +126,15 @@ __global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_k
 
     // ---- key tile pipeline: global -> registers -> LDS, double buffered, one barrier per tile ----
     const unsigned short *kp = (const unsigned short *)a.k + (int64_t)b * a.Lk * DI;
-    u32x4 pre[LPT];
+    // PD register sets keep PD tiles in flight from HBM/L2 (set t % PD holds tile t); a tile is
+    // copied to LDS one iteration before it is multiplied.
+    u32x4 pre[PD][LPT];
     const int ntiles = (kend - kc0 + TILE - 1) / TILE;
-    tile_gload<DI, LPT, NT>(pre, kp, kc0, a.Lk, tid);
-    tile_lstore<DI, LPT, ROWB, NT>(pre, &lds[0][0], tid);
+    tile_gload<DI, LPT, NT>(pre[0], kp, kc0, a.Lk, tid);
+#pragma unroll
+    for (int d = 1; d < PD; ++d)
+        if (d < ntiles) tile_gload<DI, LPT, NT>(pre[d], kp, kc0 + d * TILE, a.Lk, tid);
+    tile_lstore<DI, LPT, ROWB, NT>(pre[0], &lds[0][0], tid);
     __syncthreads();
 
     // Combine the two half-wave partial sums of a token pair (or of one token with itself) and
@@ -142,16 +152,20 @@ __global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_k
         }
     };
 
-    for (int it = 0; it < ntiles; ++it) {
+    for (int it0 = 0; it0 < ntiles; it0 += PD) {
+#pragma unroll
+      for (int ph = 0; ph < PD; ++ph) {
+        const int it = it0 + ph;
+        if (it >= ntiles) break;                            // workgroup-uniform
         const int kt = kc0 + it * TILE;
         const int buf = it & 1;
-        if (it + 1 < ntiles) tile_gload<DI, LPT, NT>(pre, kp, kt + TILE, a.Lk, tid);
+        if (it + PD < ntiles) tile_gload<DI, LPT, NT>(pre[ph], kp, kt + PD * TILE, a.Lk, tid);
 
         // Interior tile: all 64 keys are visible to every token of this wave and every token is a
         // real row, so nothing needs masking and the whole tile is one straight-line block.
         const bool interior = (t_w0 + TPW <= i_end) && (kt + TILE <= a.Lk) &&
                               ((int64_t)(kt + TILE - 1) <= a.q_pos0 + t_w0);
-        if (interior) {
+        if (interior && !STREAM) {
             // Software pipeline over the units (key subtile, token, head tile): the MFMA chain of unit
             // c+1 is issued before the ReLU/weight/sum epilogue of unit c, so the matrix pipe works
             // under this wave's own VALU epilogue as well as under the other wave's.
@@ -195,6 +209,7 @@ __global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_k
             for (int sub = 0; sub < 2; ++sub) {
                 const int s0 = kt + sub * 32;
                 if (s0 >= wave_vis) continue;               // wave-uniform: hidden from all its tokens
+                if (STREAM && (sub != (wave & 1) || (it & 1) != (wave >> 1))) continue;   // another wave's turn
                 bf16x8 kb[KS];
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
@@ -225,8 +240,9 @@ __global__ __launch_bounds__(64 * NW, (HT == 1 && NW == 4) ? 2 : 1) void score_k
             }
         }
 
-        if (it + 1 < ntiles) tile_lstore<DI, LPT, ROWB, NT>(pre, &lds[buf ^ 1][0], tid);
+        if (it + 1 < ntiles) tile_lstore<DI, LPT, ROWB, NT>(pre[(ph + 1) % PD], &lds[buf ^ 1][0], tid);
         __syncthreads();
+      }
     }
 }
 
@@ -237,13 +253,13 @@ __global__ void fill_kernel(float *p, int64_t n, float v)
     for (; i < n; i += stride) p[i] = v;
 }
 
-template <int HT, int DI, int TPW, int NW>
+template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM>
 hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
 {
     const int n_kc = (int)((max_vis + a.KC - 1) / a.KC);
     if (n_kc <= 0 || a.n_qblocks <= 0 || Bc <= 0) return hipSuccess;
     dim3 grid((unsigned)a.n_qblocks, (unsigned)n_kc, (unsigned)Bc);
-    hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW>), grid, dim3(64 * NW), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW, PD, MINB, STREAM>), grid, dim3(64 * NW), 0, st, a);
     return hipGetLastError();
 }
 
@@ -256,29 +272,32 @@ bool score_shape_supported(int dtype, int H_I, int d_I)
     return d_I == 64 || d_I == 128;
 }
 
-// Tokens per workgroup for a head count (the launcher and the host-side grid math agree on it).
-static int tokens_per_block(int H_I) { return H_I <= 32 ? 12 : 8; }
-
 hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipStream_t st)
 {
     (void)dtype;
     ScoreArgs a = a_in;
-    const int BT = tokens_per_block(a.H_I);
+    // Few query rows per sequence (decode, short chunks): one token per workgroup, three workgroups
+    // per CU and three key tiles in flight per workgroup, because the kernel then only streams keys.
+    // Otherwise 3 tokens per wave (2 for 64 heads) and the matrix pipe is the limit.
+    const bool few_rows = a.Ri <= 4;
+    const int BT = few_rows ? 1 : (a.H_I <= 32 ? 12 : 8);
     a.n_qblocks = (a.Ri + BT - 1) / BT;
     const int i_last = min(a.i0 + a.Ri, a.Tq) - 1;
     int64_t max_vis = a.q_pos0 + i_last + 1;
     max_vis = max_vis < 0 ? 0 : (max_vis > a.Lk ? a.Lk : max_vis);
     if (max_vis == 0) return hipSuccess;
-    // keys per workgroup: enough workgroups to fill 256 CUs several times, tiles of 64 keys
-    int64_t kc = (max_vis * a.n_qblocks * Bc / 2048 + 63) / 64 * 64;
+    // keys per workgroup (tiles of 64 keys): prefill wants enough workgroups to fill 256 CUs
+    // several times; the streaming variant wants exactly one resident round (3 per CU).
+    const int64_t want_wgs = few_rows ? 768 : 2048;
+    int64_t kc = (max_vis * a.n_qblocks * Bc / want_wgs + 63) / 64 * 64;
     kc = kc < 512 ? 512 : (kc > 4096 ? 4096 : kc);
     a.KC = (int)kc;
     if (a.H_I <= 32) {
-        if (d_I == 128) return launch_t<1, 128, 3, 4>(a, Bc, max_vis, st);
-        if (d_I == 64) return launch_t<1, 64, 3, 4>(a, Bc, max_vis, st);
+        if (d_I == 128) return few_rows ? launch_t<1, 128, 1, 4, 3, 3, true>(a, Bc, max_vis, st) : launch_t<1, 128, 3, 4, 1, 2, false>(a, Bc, max_vis, st);
+        if (d_I == 64) return few_rows ? launch_t<1, 64, 1, 4, 3, 3, true>(a, Bc, max_vis, st) : launch_t<1, 64, 3, 4, 1, 2, false>(a, Bc, max_vis, st);
     } else {
-        if (d_I == 128) return launch_t<2, 128, 2, 4>(a, Bc, max_vis, st);
-        if (d_I == 64) return launch_t<2, 64, 2, 4>(a, Bc, max_vis, st);
+        if (d_I == 128) return few_rows ? launch_t<2, 128, 1, 4, 3, 2, true>(a, Bc, max_vis, st) : launch_t<2, 128, 2, 4, 1, 1, false>(a, Bc, max_vis, st);
+        if (d_I == 64) return few_rows ? launch_t<2, 64, 1, 4, 3, 2, true>(a, Bc, max_vis, st) : launch_t<2, 64, 2, 4, 1, 1, false>(a, Bc, max_vis, st);
     }
     return hipErrorInvalidValue;
 }
