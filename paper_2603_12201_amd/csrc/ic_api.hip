@@ -82,7 +82,7 @@ ic_status check_indexer(const ic_indexer_desc *d)
     if (d->flags != 0) return fail(IC_ERR_UNSUPPORTED, "indexer flags must be 0");
     if (d->dtype != IC_BF16 && d->dtype != IC_FP8_E4M3) return fail(IC_ERR_UNSUPPORTED, "unknown dtype %d", d->dtype);
     if (!ic::score_shape_supported(d->dtype, d->H_I, d->d_I))
-        return fail(IC_ERR_UNSUPPORTED, "indexer shape not covered: dtype=%d H_I=%d d_I=%d (bf16, H_I<=64, d_I in {64,128})",
+        return fail(IC_ERR_UNSUPPORTED, "indexer shape not covered: dtype=%d H_I=%d d_I=%d (H_I<=64; bf16: d_I in {64,128}; fp8: d_I = 128)",
                     d->dtype, d->H_I, d->d_I);
     if ((int64_t)d->B * d->Tq > INT32_MAX / 2 || (int64_t)d->B * d->Tq * d->k_sel > ((int64_t)1 << 40))
         return fail(IC_ERR_SHAPE, "B*Tq too large");

@@ -26,24 +26,57 @@ namespace ic {
 
 namespace {
 
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+// The two operand formats.  bf16: v_mfma_f32_32x32x16_bf16, 16 contraction elements per step,
+// a lane holds 8 of them (16 bytes).  fp8 (OCP e4m3): v_mfma_f32_32x32x64_f8f6f4, 64 elements per
+// step, a lane holds 32 of them (32 bytes) -- twice the matrix rate per instruction cycle.
+template <bool FP8> struct Fmt;
+template <> struct Fmt<false> {
+    typedef bf16x8 Op;
+    static constexpr int kStep = 16, kElemBytes = 2;
+    static __device__ __forceinline__ Op load(const unsigned char *p) { return *(const Op *)p; }
+    static __device__ __forceinline__ Op zero() { return __builtin_bit_cast(Op, u32x4{0u, 0u, 0u, 0u}); }
+    static __device__ __forceinline__ f32x16 mma(Op x, Op y, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, c, 0, 0, 0);
+    }
+};
+template <> struct Fmt<true> {
+    typedef i32x8 Op;
+    static constexpr int kStep = 64, kElemBytes = 1;
+    static __device__ __forceinline__ Op load(const unsigned char *p)
+    {
+        const u32x4 lo = *(const u32x4 *)p, hi = *(const u32x4 *)(p + 16);
+        return Op{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+    }
+    static __device__ __forceinline__ Op zero() { return Op{0, 0, 0, 0, 0, 0, 0, 0}; }
+    static __device__ __forceinline__ f32x16 mma(Op x, Op y, f32x16 c)
+    {
+        // formats 0/0 = e4m3 x e4m3; constant zero scale operands select the unscaled instruction
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(x, y, c, 0, 0, 0, 0, 0, 0);
+    }
+};
+
 // Global -> register -> LDS staging of one tile of 64 key rows (16-byte chunks, coalesced).
-template <int DI, int LPT, int NT>
-__device__ __forceinline__ void tile_gload(u32x4 (&pre)[LPT], const unsigned short *kp, int kt, int Lk, int tid)
+// RB = bytes per key row.
+template <int RB, int LPT, int NT>
+__device__ __forceinline__ void tile_gload(u32x4 (&pre)[LPT], const unsigned char *kp, int kt, int Lk, int tid)
 {
-    constexpr int CPR = DI / 8;
+    constexpr int CPR = RB / 16;
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
         const int c = tid + NT * r;
         const int row = c / CPR, col = c % CPR;
         const int s = min(kt + row, Lk - 1);                // clamp: rows past Lk are masked later
-        pre[r] = *(const u32x4 *)(kp + ((int64_t)s * DI + col * 8));
+        pre[r] = *(const u32x4 *)(kp + ((int64_t)s * RB + col * 16));
     }
 }
 
-template <int DI, int LPT, int ROWB, int NT>
+template <int RB, int LPT, int ROWB, int NT>
 __device__ __forceinline__ void tile_lstore(const u32x4 (&pre)[LPT], unsigned char *buf, int tid)
 {
-    constexpr int CPR = DI / 8;
+    constexpr int CPR = RB / 16;
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
         const int c = tid + NT * r;
@@ -63,17 +96,22 @@ __device__ __forceinline__ float relu(float x)
 // keeps its q rows, and the waves take turns on the key subtiles (wave w multiplies subtile
 // w & 1 of the tiles with parity w >> 1) so that all four SIMDs share the little matrix work
 // while the kernel streams the key cache.
-template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM>
+template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM, bool FP8>
 __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
 {
     static_assert(!STREAM || (TPW == 1 && NW == 4), "the streaming form is one token, four waves");
+    typedef Fmt<FP8> F;
+    typedef typename F::Op Op;
     constexpr int NT = 64 * NW;                 // threads per workgroup
-    constexpr int KS = DI / 16;                 // MFMA k-steps over the head dim
+    constexpr int KS = DI / F::kStep;           // MFMA k-steps over the head dim
+    constexpr int OPB = F::kStep / 2 * F::kElemBytes;   // operand bytes per lane per k-step
     constexpr int BT = STREAM ? 1 : NW * TPW;   // tokens per workgroup
-    constexpr int ROWB = DI * 2 + 16;           // LDS row stride (bytes), padded against bank conflicts
+    constexpr int RB = DI * F::kElemBytes;      // bytes per key row
+    constexpr int ROWB = RB + 16;               // LDS row stride (bytes), padded against bank conflicts
     constexpr int TILE = 64;                    // keys per LDS tile
-    constexpr int CPR = DI / 8;                 // 16-byte chunks per key row
-    constexpr int LPT = TILE * CPR / NT;        // 16-byte loads per thread per tile
+    constexpr int CPR = RB / 16;                // 16-byte chunks per key row
+    constexpr int LPT = (TILE * CPR + NT - 1) / NT;     // 16-byte loads per thread per tile
+    static_assert(TILE * CPR % NT == 0, "tile chunks must divide evenly over the threads");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][TILE * ROWB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -97,24 +135,25 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     const int wave_vis = (t_w0 < i_end) ? (int)wv64 : 0;   // keys >= wave_vis matter to none of its tokens
 
     // ---- stationary operands: q rows (A operand) and head weights of the wave's tokens ----
-    bf16x8 qa[TPW][HT][KS];
+    Op qa[TPW][HT][KS];
     float wr[TPW][HT][16];
-    const unsigned short *qp = (const unsigned short *)a.q;
+    float sqr[TPW];                                        // fp8: per-token scale of q
+    const unsigned char *qp = (const unsigned char *)a.q;
 #pragma unroll
     for (int j = 0; j < TPW; ++j) {
         const int t = t_w0 + j;
         const bool tv = t < i_end;
         const int64_t trow = (int64_t)b * a.Tq + (tv ? t : 0);
+        sqr[j] = (FP8 && tv) ? a.q_scale[trow] : 1.f;
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht) {
             const int head = ht * 32 + r32;
             const bool hv = tv && head < a.H_I;
-            const unsigned short *src = qp + ((trow * a.H_I + (hv ? head : 0)) * DI + half * 8);
+            const unsigned char *src = qp + ((trow * a.H_I + (hv ? head : 0)) * DI) * F::kElemBytes + half * OPB;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-                if (hv) raw = *(const u32x4 *)(src + ks * 16);
-                qa[j][ht][ks] = __builtin_bit_cast(bf16x8, raw);
+                qa[j][ht][ks] = F::zero();
+                if (hv) qa[j][ht][ks] = F::load(src + ks * 2 * OPB);
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -125,16 +164,17 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     }
 
     // ---- key tile pipeline: global -> registers -> LDS, double buffered, one barrier per tile ----
-    const unsigned short *kp = (const unsigned short *)a.k + (int64_t)b * a.Lk * DI;
+    const unsigned char *kp = (const unsigned char *)a.k + (int64_t)b * a.Lk * RB;
+    const float *ksc = FP8 ? a.k_scale + (int64_t)b * a.Lk : nullptr;
     // PD register sets keep PD tiles in flight from HBM/L2 (set t % PD holds tile t); a tile is
     // copied to LDS one iteration before it is multiplied.
     u32x4 pre[PD][LPT];
     const int ntiles = (kend - kc0 + TILE - 1) / TILE;
-    tile_gload<DI, LPT, NT>(pre[0], kp, kc0, a.Lk, tid);
+    tile_gload<RB, LPT, NT>(pre[0], kp, kc0, a.Lk, tid);
 #pragma unroll
     for (int d = 1; d < PD; ++d)
-        if (d < ntiles) tile_gload<DI, LPT, NT>(pre[d], kp, kc0 + d * TILE, a.Lk, tid);
-    tile_lstore<DI, LPT, ROWB, NT>(pre[0], &lds[0][0], tid);
+        if (d < ntiles) tile_gload<RB, LPT, NT>(pre[d], kp, kc0 + d * TILE, a.Lk, tid);
+    tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[0][0], tid);
     __syncthreads();
 
     // Combine the two half-wave partial sums of a token pair (or of one token with itself) and
@@ -142,10 +182,15 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     // sum is token A's total in lanes 0-31 and token B's in lanes 32-63.
     auto emit = [&](float pa, float pb, bool pair, int j, int s0, bool interior) {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(pa), __float_as_uint(pb), false, false);
-        const float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+        float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
         const int t = t_w0 + j + half;
         const int s = s0 + r32;
         const bool lane_on = pair || half == 0;
+        if (FP8) {
+            // positive per-token scales commute with the ReLU gate: I = sq[t] sk[s] sum_j w_j ReLU(q8_j . k8)
+            const float sq = (pair && half) ? sqr[(j + 1) % TPW] : sqr[j];
+            v *= sq * ksc[min(s, a.Lk - 1)];
+        }
         if (lane_on && (interior || (t < i_end && s < a.Lk && (int64_t)s <= a.q_pos0 + t))) {
             const int64_t srow = (int64_t)blockIdx.z * a.Ri + (t - a.i0);
             a.strip[srow * a.ld + s] = v;
@@ -159,7 +204,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         if (it >= ntiles) break;                            // workgroup-uniform
         const int kt = kc0 + it * TILE;
         const int buf = it & 1;
-        if (it + PD < ntiles) tile_gload<DI, LPT, NT>(pre[ph], kp, kt + PD * TILE, a.Lk, tid);
+        if (it + PD < ntiles) tile_gload<RB, LPT, NT>(pre[ph], kp, kt + PD * TILE, a.Lk, tid);
 
         // Interior tile: all 64 keys are visible to every token of this wave and every token is a
         // real row, so nothing needs masking and the whole tile is one straight-line block.
@@ -169,11 +214,11 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
             // Software pipeline over the units (key subtile, token, head tile): the MFMA chain of unit
             // c+1 is issued before the ReLU/weight/sum epilogue of unit c, so the matrix pipe works
             // under this wave's own VALU epilogue as well as under the other wave's.
-            bf16x8 kb[KS];                                  // B operands of the subtile being multiplied
+            Op kb[KS];                                      // B operands of the subtile being multiplied
             auto load_kb = [&](int sub) {
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    kb[ks] = *(const bf16x8 *)(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 16 + half * 8) * 2]);
+                    kb[ks] = F::load(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 2 + half) * OPB]);
             };
             constexpr int NCH = 2 * TPW * HT;
             f32x16 acc[2];
@@ -186,7 +231,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
                 for (int i = 0; i < 16; ++i) r[i] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    r = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[j][ht][ks], kb[ks], r, 0, 0, 0);
+                    r = F::mma(qa[j][ht][ks], kb[ks], r);
                 return r;
             };
             acc[0] = chain(0);
@@ -210,10 +255,10 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
                 const int s0 = kt + sub * 32;
                 if (s0 >= wave_vis) continue;               // wave-uniform: hidden from all its tokens
                 if (STREAM && (sub != (wave & 1) || (it & 1) != (wave >> 1))) continue;   // another wave's turn
-                bf16x8 kb[KS];
+                Op kb[KS];
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    kb[ks] = *(const bf16x8 *)(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 16 + half * 8) * 2]);
+                    kb[ks] = F::load(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 2 + half) * OPB]);
                 float part[TPW];
 #pragma unroll
                 for (int j = 0; j < TPW; ++j) {
@@ -225,7 +270,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
                         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks)
-                            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[j][ht][ks], kb[ks], acc, 0, 0, 0);
+                            acc = F::mma(qa[j][ht][ks], kb[ks], acc);
 #pragma unroll
                         for (int i = 0; i < 16; ++i)
                             s_acc = fmaf(relu(acc[i]), wr[j][ht][i], s_acc);
@@ -240,7 +285,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
             }
         }
 
-        if (it + 1 < ntiles) tile_lstore<DI, LPT, ROWB, NT>(pre[(ph + 1) % PD], &lds[buf ^ 1][0], tid);
+        if (it + 1 < ntiles) tile_lstore<RB, LPT, ROWB, NT>(pre[(ph + 1) % PD], &lds[buf ^ 1][0], tid);
         __syncthreads();
       }
     }
@@ -253,13 +298,13 @@ __global__ void fill_kernel(float *p, int64_t n, float v)
     for (; i < n; i += stride) p[i] = v;
 }
 
-template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM>
+template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM, bool FP8>
 hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
 {
     const int n_kc = (int)((max_vis + a.KC - 1) / a.KC);
     if (n_kc <= 0 || a.n_qblocks <= 0 || Bc <= 0) return hipSuccess;
     dim3 grid((unsigned)a.n_qblocks, (unsigned)n_kc, (unsigned)Bc);
-    hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW, PD, MINB, STREAM>), grid, dim3(64 * NW), 0, st, a);
+    hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW, PD, MINB, STREAM, FP8>), grid, dim3(64 * NW), 0, st, a);
     return hipGetLastError();
 }
 
@@ -267,20 +312,20 @@ hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
 
 bool score_shape_supported(int dtype, int H_I, int d_I)
 {
-    if (dtype != IC_BF16) return false;
     if (H_I < 1 || H_I > IC_MAX_HEADS_I) return false;
+    if (dtype == IC_FP8_E4M3) return d_I == 128;
+    if (dtype != IC_BF16) return false;
     return d_I == 64 || d_I == 128;
 }
 
 hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipStream_t st)
 {
-    (void)dtype;
     ScoreArgs a = a_in;
     // Few query rows per sequence (decode, short chunks): one token per workgroup, three workgroups
     // per CU and three key tiles in flight per workgroup, because the kernel then only streams keys.
     // Otherwise 3 tokens per wave (2 for 64 heads) and the matrix pipe is the limit.
     const bool few_rows = a.Ri <= 4;
-    const int BT = few_rows ? 1 : (a.H_I <= 32 ? 12 : 8);
+    const int BT = few_rows ? 1 : (a.H_I <= 32 ? 12 : 8);   // 4 waves x tokens per wave of the chosen form
     a.n_qblocks = (a.Ri + BT - 1) / BT;
     const int i_last = min(a.i0 + a.Ri, a.Tq) - 1;
     int64_t max_vis = a.q_pos0 + i_last + 1;
@@ -292,12 +337,21 @@ hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipSt
     int64_t kc = (max_vis * a.n_qblocks * Bc / want_wgs + 63) / 64 * 64;
     kc = kc < 512 ? 512 : (kc > 4096 ? 4096 : kc);
     a.KC = (int)kc;
-    if (a.H_I <= 32) {
-        if (d_I == 128) return few_rows ? launch_t<1, 128, 1, 4, 3, 3, true>(a, Bc, max_vis, st) : launch_t<1, 128, 3, 4, 1, 2, false>(a, Bc, max_vis, st);
-        if (d_I == 64) return few_rows ? launch_t<1, 64, 1, 4, 3, 3, true>(a, Bc, max_vis, st) : launch_t<1, 64, 3, 4, 1, 2, false>(a, Bc, max_vis, st);
+    const bool fp8 = dtype == IC_FP8_E4M3;
+    if (!fp8) {
+        if (a.H_I <= 32) {
+            if (d_I == 128) return few_rows ? launch_t<1, 128, 1, 4, 3, 3, true, false>(a, Bc, max_vis, st) : launch_t<1, 128, 3, 4, 1, 2, false, false>(a, Bc, max_vis, st);
+            if (d_I == 64) return few_rows ? launch_t<1, 64, 1, 4, 3, 3, true, false>(a, Bc, max_vis, st) : launch_t<1, 64, 3, 4, 1, 2, false, false>(a, Bc, max_vis, st);
+        } else {
+            if (d_I == 128) return few_rows ? launch_t<2, 128, 1, 4, 3, 2, true, false>(a, Bc, max_vis, st) : launch_t<2, 128, 2, 4, 1, 1, false, false>(a, Bc, max_vis, st);
+            if (d_I == 64) return few_rows ? launch_t<2, 64, 1, 4, 3, 2, true, false>(a, Bc, max_vis, st) : launch_t<2, 64, 2, 4, 1, 1, false, false>(a, Bc, max_vis, st);
+        }
     } else {
-        if (d_I == 128) return few_rows ? launch_t<2, 128, 1, 4, 3, 2, true>(a, Bc, max_vis, st) : launch_t<2, 128, 2, 4, 1, 1, false>(a, Bc, max_vis, st);
-        if (d_I == 64) return few_rows ? launch_t<2, 64, 1, 4, 3, 2, true>(a, Bc, max_vis, st) : launch_t<2, 64, 2, 4, 1, 1, false>(a, Bc, max_vis, st);
+        if (a.H_I <= 32) {
+            if (d_I == 128) return few_rows ? launch_t<1, 128, 1, 4, 3, 3, true, true>(a, Bc, max_vis, st) : launch_t<1, 128, 3, 4, 1, 2, false, true>(a, Bc, max_vis, st);
+        } else {
+            if (d_I == 128) return few_rows ? launch_t<2, 128, 1, 4, 3, 2, true, true>(a, Bc, max_vis, st) : launch_t<2, 128, 2, 4, 1, 2, false, true>(a, Bc, max_vis, st);
+        }
     }
     return hipErrorInvalidValue;
 }

@@ -126,8 +126,12 @@ def _sample_rows(Tq, k_sel, n, seed):
 
 
 def _check_indexer_rows(ic, oracle, cfg, layer_gpu, idx_gpu, sel_gpu, rows, b=0):
-    lb = {k: synth.bits(v[b:b + 1]) for k, v in layer_gpu.items() if k in ("q", "k", "w")}
-    sc = oracle.indexer_scores(lb["q"], lb["k"], lb["w"], cfg["q_pos0"], rows=rows)
+    lb = {k: synth.bits(v[b:b + 1]) for k, v in layer_gpu.items() if k in ("q", "k", "w", "q_scale", "k_scale")}
+    if cfg["dtype"] == "fp8":
+        sc = oracle.indexer_scores(lb["q"], lb["k"], lb["w"], cfg["q_pos0"], dtype=oracle.FP8_E4M3,
+                                   q_scale=lb["q_scale"], k_scale=lb["k_scale"], rows=rows)
+    else:
+        sc = oracle.indexer_scores(lb["q"], lb["k"], lb["w"], cfg["q_pos0"], rows=rows)
     g = idx_gpu[b].cpu().numpy()
     kinds = {}
     for j, t in enumerate(rows):
@@ -196,5 +200,24 @@ def test_prefill_32k_layer_sampled(ic, oracle):
     idx_rows = np.ascontiguousarray(idx_cache[:, rows].cpu().numpy())
     want, _ = oracle.sparse_attn(Qb, KVb, idx_rows, cfg["d_v"], cfg["v_off"], synth.sm_scale(cfg), rows=rows,
                                  idx_is_subset=True)
+    err = parity.check_attn(outs[0][:, rows].float().cpu().numpy(), want)
+    say("attention err %.4g" % err)
+
+
+def test_fp8_long_context_layer_sampled(ic, oracle):
+    """configs[4], one Full layer at full size (L=131072, 64 fp8 heads): sampled rows of idx and O."""
+    cfg = synth.config("c4")
+    say("c4 one fp8 layer at L=131072")
+    lay = synth.stack_layers(cfg, device="cuda", n_layers=1)[0]
+    torch.cuda.synchronize()
+    outs, idx_cache, n_idx = _run_stack(ic, cfg, [lay], [True])
+    assert n_idx == 1
+    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 12, 5)
+    kinds = _check_indexer_rows(ic, oracle, cfg, lay, idx_cache, None, rows)
+    say("rows %s kinds %s" % (rows, kinds))
+    Qb, KVb = synth.bits(lay["Q"][:, rows]), synth.bits(lay["KV"])
+    idx_rows = np.ascontiguousarray(idx_cache[:, rows].cpu().numpy())
+    # Q rows were gathered: address them as rows 0..n-1 of a compact Q
+    want, _ = oracle.sparse_attn(Qb, KVb, idx_rows, cfg["d_v"], cfg["v_off"], synth.sm_scale(cfg))
     err = parity.check_attn(outs[0][:, rows].float().cpu().numpy(), want)
     say("attention err %.4g" % err)

@@ -59,6 +59,70 @@ def test_indexer_scores(ic, oracle, case):
     parity.check_scores(got.cpu().numpy(), want)
 
 
+FP8_CASES = [
+    # B, Tq, Lk, H, q_pos0
+    (1, 70, 70, 64, 0),        # configs[4] head count: two head tiles
+    (2, 30, 200, 32, 170),
+    (2, 1, 300, 64, 299),      # decode form
+    (1, 40, 40, 20, 0),        # ragged head count
+]
+
+
+def _mk_fp8(seed, B, Tq, Lk, H, d=128):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn((B, Tq, H * d), generator=g) / math.sqrt(d)
+    k = torch.randn((B, Lk, d), generator=g)
+    w = torch.rand((B, Tq, H), generator=g)
+    q8, qs = synth.quantize_e4m3(q)
+    k8, ks = synth.quantize_e4m3(k)
+    return q8.reshape(B, Tq, H, d).contiguous(), k8.contiguous(), w.float(), qs.contiguous(), ks.contiguous()
+
+
+@pytest.mark.parametrize("case", FP8_CASES)
+def test_indexer_scores_fp8(ic, oracle, case):
+    B, Tq, Lk, H, p0 = case
+    say("fp8 scores B=%d Tq=%d Lk=%d H=%d q_pos0=%d" % case)
+    q8, k8, w, qs, ks = _mk_fp8(500 + Tq + H, B, Tq, Lk, H)
+    got = ic.debug_indexer_scores(q8.cuda(), k8.cuda(), w.cuda(), p0, 0, Tq, q_scale=qs.cuda(), k_scale=ks.cuda())
+    torch.cuda.synchronize()
+    want = oracle.indexer_scores(synth.bits(q8), synth.bits(k8), synth.bits(w), p0, dtype=oracle.FP8_E4M3,
+                                 q_scale=synth.bits(qs), k_scale=synth.bits(ks))
+    parity.check_scores(got.cpu().numpy(), want)
+
+
+def test_indexer_topk_fp8(ic, oracle):
+    B, Tq, Lk, H, p0, ksel = 1, 48, 600, 64, 552, 128
+    say("fp8 topk")
+    q8, k8, w, qs, ks = _mk_fp8(77, B, Tq, Lk, H)
+    idx = ic.indexer_topk(q8.cuda(), k8.cuda(), w.cuda(), ksel, p0, q_scale=qs.cuda(), k_scale=ks.cuda())
+    torch.cuda.synchronize()
+    sc = oracle.indexer_scores(synth.bits(q8), synth.bits(k8), synth.bits(w), p0, dtype=oracle.FP8_E4M3,
+                               q_scale=synth.bits(qs), k_scale=synth.bits(ks))
+    g = idx.cpu().numpy()
+    for i in range(Tq):
+        parity.check_idx_row(g[0, i], sc[0, i], min(Lk, p0 + i + 1), ksel, oracle)
+
+
+def test_fp8_exact_on_power_of_two_inputs(ic, oracle):
+    # every e4m3 value and product is exact in fp32; with power-of-two inputs and scales the sums
+    # are exact too, so GPU and oracle must agree to the last bit
+    say("fp8 exact")
+    B, Tq, Lk, H, d = 1, 33, 33, 32, 128
+    g = torch.Generator().manual_seed(3)
+    q = torch.randint(-2, 3, (B, Tq, H, d), generator=g).float()
+    k = torch.randint(-2, 3, (B, Lk, d), generator=g).float()
+    w = torch.randint(0, 4, (B, Tq, H), generator=g).float() * 0.25
+    qs = torch.full((B, Tq), 0.5)
+    ks = torch.full((B, Lk), 2.0)
+    q8, k8 = q.to(torch.float8_e4m3fn), k.to(torch.float8_e4m3fn)
+    got = ic.debug_indexer_scores(q8.cuda(), k8.cuda(), w.cuda(), 0, 0, Tq, q_scale=qs.cuda(), k_scale=ks.cuda())
+    want = oracle.indexer_scores(synth.bits(q8), synth.bits(k8), synth.bits(w), 0, dtype=oracle.FP8_E4M3,
+                                 q_scale=synth.bits(qs), k_scale=synth.bits(ks))
+    got = got.cpu().numpy().astype(np.float64)
+    vis = np.isfinite(want)
+    assert np.array_equal(got[vis], want[vis])
+
+
 def test_indexer_scores_row_window(ic, oracle):
     say("scores row window")
     B, Tq, Lk, H, d, p0 = 1, 100, 100, 32, 128, 0
