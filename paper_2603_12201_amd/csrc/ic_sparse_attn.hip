@@ -25,34 +25,30 @@ constexpr int kTile = 32;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Tile staging.  A thread owns tile row tid / 8 and the 16-byte chunks (tid % 8) + 8 r of that
+// row: eight neighbouring lanes read one full 128-byte line, and no index needs a division.
 template <int ROW_F, int LPT>
 __device__ __forceinline__ void attn_gload(u32x4 (&pre)[LPT], const unsigned short *kv_seq, const int32_t *ti,
                                            int row_elems, int tid)
 {
     constexpr int CPR = ROW_F / 8;
+    const int row = tid >> 3, c0 = tid & 7;
+    const int32_t v = ti[row];
+    const unsigned short *src = kv_seq + (int64_t)(v < 0 ? 0 : v) * row_elems + c0 * 8;
 #pragma unroll
-    for (int r = 0; r < LPT; ++r) {
-        const int u = tid + 256 * r;
-        if (u < kTile * CPR) {
-            const int row = u / CPR, col = u % CPR;
-            const int32_t v = ti[row];
-            pre[r] = *(const u32x4 *)(kv_seq + ((int64_t)(v < 0 ? 0 : v) * row_elems + col * 8));
-        }
-    }
+    for (int r = 0; r < LPT; ++r)
+        if (c0 + 8 * r < CPR) pre[r] = *(const u32x4 *)(src + 64 * r);
 }
 
 template <int ROW_F, int LPT, int ROWB>
 __device__ __forceinline__ void attn_lstore(const u32x4 (&pre)[LPT], unsigned char *tile, int tid)
 {
     constexpr int CPR = ROW_F / 8;
+    const int row = tid >> 3, c0 = tid & 7;
+    unsigned char *dst = tile + row * ROWB + c0 * 16;
 #pragma unroll
-    for (int r = 0; r < LPT; ++r) {
-        const int u = tid + 256 * r;
-        if (u < kTile * CPR) {
-            const int row = u / CPR, col = u % CPR;
-            *(u32x4 *)(tile + row * ROWB + col * 16) = pre[r];
-        }
-    }
+    for (int r = 0; r < LPT; ++r)
+        if (c0 + 8 * r < CPR) *(u32x4 *)(dst + 128 * r) = pre[r];
 }
 
 template <int D_QK, int D_V, int ROW_F>
@@ -60,7 +56,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 {
     constexpr int ROWB = ROW_F * 2 + 16;                  // LDS row stride in bytes
     constexpr int CPR = ROW_F / 8;                        // 16-byte chunks staged per row
-    constexpr int LPT = (kTile * CPR + 255) / 256;        // chunk loads per thread per tile
+    constexpr int LPT = (CPR + 7) / 8;                    // chunk loads per thread per tile (one row per 8 lanes)
+    static_assert(kTile * 8 == 256, "256 threads cover the tile rows, 8 lanes per row");
     constexpr int KSTEPS = D_QK / 32;
     constexpr int DVW = D_V / 2;                          // value columns per wave
     constexpr int NB = DVW / 16;
