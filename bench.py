@@ -19,6 +19,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the kernels at the configs[3] per-layer shape, from rocprofv3 FETCH_SIZE +
+# WRITE_SIZE scaled by a plain-copy reference (profiles/attn_score_select_prefill32k_hbm_traffic.txt).
+MEASURED_TRAFFIC_BYTES = {"sparse_attn": 19.96e9 + 1.07e9, "indexer_score": 0.427e9 + 0.543e9,
+                          "topk_select": 0.672e9 + 0.067e9}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 KERNELS = ["indexer_score", "topk_select", "sparse_attn", "attn_merge"]
@@ -150,6 +154,9 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of 1 GiB (reference dispatches for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -163,6 +170,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------- prefill: 48-layer stack, L = 32768 ----------------
     cfg = synth.config("c3", n_layers=args.layers)
@@ -218,7 +233,9 @@ def main():
     dom = max(share, key=share.get)
     roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
                 "peak": kernels[dom]["peak"], "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
-                "traffic": None, "avg_launch_ms": per_launch(prof_14, dom),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if cfg["Tq"] == 32768 else None,
+                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled; see profiles/)",
+                "avg_launch_ms": per_launch(prof_14, dom),
                 "share_of_step": share[dom] / sum(share.values())}
 
     arms = {
