@@ -16,7 +16,6 @@
 // the same softmax statistics, so no exchange between waves is ever needed.  With several
 // splits per query the unnormalised partials go to the workspace and a small kernel merges them.
 #include "ic_common.hpp"
-#include <stdlib.h>
 #include <type_traits>
 
 namespace ic {
@@ -236,31 +235,30 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 }
 
 // ---- row-slab form (576/512 MLA rows) --------------------------------------------------
-// One workgroup (4 waves, one per SIMD, the whole register file) per query and key-slot split;
-// tiles of 64 selected rows.  Wave w owns rows 16w..16w+15 of a tile and gathers them straight
-// into registers in the A-operand layout of v_mfma_f32_16x16x32_bf16 (lane = row l%16, eight
-// features 32 ks + 8 (l/16)): the key side of S^T = K Q^T never passes through LDS, and Q for all
-// 32 heads stays in registers.  Only the value columns go to LDS (written from the same registers,
-// read back once through the transpose read), and the 64x32 probabilities.
-//   producer role (rows of the wave):  S^T, p = 2^(z - m_w) against the wave's own reference
-//       maximum m_w = max(running maximum of all waves up to the previous tile, this tile's own)
+// One workgroup (4 waves, one per SIMD, the whole register file) per query, for launches with
+// enough queries to fill the chip; tiles of 64 selected rows, two tiles resident in LDS.  Wave w owns rows 16w..16w+15 of a tile
+// in the producer role and value columns 32w + 128nb + (0..31) in the consumer role:
+//   gather    eight lanes fetch one 128-byte line of a row (the access shape the vector memory
+//             path serves fastest), 18 loads per lane and tile, refilled in place one tile ahead
+//   stage     the wave stores its own 16 rows to the LDS tile (after the barrier of the previous
+//             tile, so nobody still reads that buffer) and reads them back in the A-operand
+//             layout of v_mfma_f32_16x16x32_bf16: every key byte is written and read once
+//   produce   S^T = K Q^T for 16 rows x 32 heads (Q stays in registers), p = 2^(z - m_w) against
+//             a lazily updated reference maximum, P and m_w to LDS
 //   one barrier per tile
-//   consumer role (value columns 32w + 128nb + 0..31, all heads):  M = max over the four m_w, the
-//       probabilities of wave j are rescaled by 2^(m_j - M) when some m_j differs, O += P V on
-//       v_mfma_f32_32x32x16_bf16 whose contraction steps are exactly the four waves' row groups.
+//   consume   M = max over the four m_w; probabilities of wave j are rescaled by 2^(m_j - M) when
+//             some m_j differs; O += P V on v_mfma_f32_32x32x16_bf16, whose four contraction
+//             steps are exactly the four waves' row groups; V comes out of the same row-major
+//             tile through the LDS transpose read, once per element.
 // Row sums stay with the producers in their own reference and are combined once at the end.
 constexpr int kSlabTile = 64;
 constexpr float kLazyLog2 = 8.f;
 
-// Byte offset of value column byte `b` of tile row `row` in the LDS value tile (row stride
-// D_V*2, no padding).  The 32-byte unit is xored with the row's low two bits and the 16-byte half
-// with bit 2 of the row, so that the four rows of a transpose read and the eight rows of a
-// 16-byte store pass fall into distinct banks.
-template <int VROWB>
-__device__ __forceinline__ int vswz(int row, int b)
-{
-    return row * VROWB + ((((b >> 5) ^ (row & 3)) << 5) | ((((b >> 4) & 1) ^ ((row >> 2) & 1)) << 4) | (b & 15));
-}
+// Swizzle of the 16-byte slot inside each 128-byte window of a tile row (row stride 1152 bytes,
+// a multiple of 128, no padding): eight consecutive rows land in eight different slots (the
+// A-operand reads and the stores), four consecutive rows in four different 32-byte pairs (the
+// transpose reads).
+__device__ __forceinline__ int slot_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
 
 // Reductions over the four 16-lane groups of a wave with the row-swap instructions (plain VALU
 // latency, no trip through the LDS crossbar).  permlane16_swap(x, x) yields {[r0,r0,r2,r2],
@@ -281,32 +279,43 @@ __device__ __forceinline__ float xsum16_32(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-template <int D_QK, int D_V, int V0S>                     // V0S: first 32-feature chunk of a row that holds value columns
+// Validity of the 16 rows of a wave from the two ballots over the gather lanes (lane 8r' + piece
+// holds row r' of the first / second eight rows): bit r of the result is row r.
+__device__ __forceinline__ unsigned rows_mask(unsigned long long ba, unsigned long long bb)
+{
+    // byte r of a ballot is 0x00 or 0xFF; keep bit 0 of each byte and gather the eight bits in the
+    // top byte of a product whose partial sums never collide
+    const unsigned long long ones = 0x0101010101010101ull, pack = 0x0102040810204080ull;
+    const unsigned lo = (unsigned)(((ba & ones) * pack) >> 56);
+    const unsigned hi = (unsigned)(((bb & ones) * pack) >> 56);
+    return lo | (hi << 8);
+}
+
+template <int D_QK, int D_V>                              // value columns = the first D_V features of a row
 __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
 {
-    constexpr int KS = D_QK / 32;                         // contraction steps of S^T
-    constexpr int VS = D_V / 32;                          // slab chunks that hold value columns
-    constexpr int VROWB = D_V * 2;
-    constexpr int VBUFB = kSlabTile * VROWB;
+    constexpr int KS = D_QK / 32;                         // contraction steps of S^T = 16-byte chunks per gather lane
+    constexpr int ROWB = D_QK * 2;                        // LDS row stride
+    static_assert(ROWB % 128 == 0 && D_V % 128 == 0 && KS % 2 == 0, "row = whole 128-byte windows");
+    constexpr int TBUFB = kSlabTile * ROWB;
     constexpr int PSTR = kSlabTile * 2 + 16;              // bytes per head row of the P tile
     constexpr int PBUFB = 32 * PSTR;
     constexpr int NBW = D_V / 4 / 32;                     // 32-column blocks per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *vbuf = smem;                           // [2][64][VROWB]
-    unsigned char *pbuf = smem + 2 * VBUFB;               // [2][32][PSTR]
-    float *mbuf = (float *)(pbuf + 2 * PBUFB);            // [2][4][32] reference maxima of the waves
-    float *lbuf = mbuf + 2 * 4 * 32;                      // [4][32] final row sums
+    unsigned char *tbuf = smem;                           // [2][64][ROWB]
+    unsigned char *pbuf = smem + 2 * TBUFB;               // [2][32][PSTR]
+    float *lbuf = (float *)(pbuf + 2 * PBUFB);            // [4][32] final row sums
     float *abuf = lbuf + 4 * 32;                          // [4][32] per-wave rescale factors
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
     const int l32 = lane & 31, hh = lane >> 5;
+    const int gr = lane >> 3, gp = lane & 7;              // gather role: row (and row + 8), 16-byte piece
     const int64_t qrow = blockIdx.x;
     const int b = (int)(qrow / a.Tq);
-    const int sp = blockIdx.y;
-    const int slot0 = sp * a.split_len;
-    const int slot1 = min(slot0 + a.split_len, a.k_sel);
-    const int ntiles = (slot1 - slot0 + kSlabTile - 1) / kSlabTile;
+    constexpr int slot0 = 0;                              // this form always covers a query's whole selection
+    const int slot1 = a.k_sel;
+    const int ntiles = (slot1 + kSlabTile - 1) / kSlabTile;
 
     const int32_t *idx_row = a.idx + qrow * a.k_sel;
     const unsigned short *kv_seq = (const unsigned short *)a.KV + (int64_t)b * a.Lk * a.row_elems;
@@ -314,16 +323,17 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     // Loads inside the tile loop are unconditional (clamped addresses, result discarded when out
     // of range): the wait counters are positional, and a load that may or may not have been
     // issued would force every later wait down to "everything has landed".
-    auto fetch_idx = [&](int it) -> int32_t {             // validated id of the lane's row in tile it
-        const int slot = slot0 + it * kSlabTile + 16 * wave + l16;
-        const int32_t v = idx_row[min(slot, a.k_sel - 1)];
-        return (slot < slot1 && v >= 0 && v < a.Lk) ? v : -1;
+    struct Ids { int32_t lo, hi; };                       // validated ids of tile rows 16w+gr and 16w+gr+8
+    auto fetch_ids = [&](int it) -> Ids {
+        const int s_lo = slot0 + it * kSlabTile + 16 * wave + gr, s_hi = s_lo + 8;
+        const int32_t v_lo = idx_row[min(s_lo, a.k_sel - 1)], v_hi = idx_row[min(s_hi, a.k_sel - 1)];
+        Ids r;
+        r.lo = (s_lo < slot1 && v_lo >= 0 && v_lo < a.Lk) ? v_lo : -1;
+        r.hi = (s_hi < slot1 && v_hi >= 0 && v_hi < a.Lk) ? v_hi : -1;
+        return r;
     };
-    auto gload = [&](u32x4 (&s)[KS], int32_t v) {
-        const unsigned short *src = kv_seq + (int64_t)(v < 0 ? 0 : v) * a.row_elems + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) s[ks] = *(const u32x4 *)(src + 32 * ks);
-    };
+    auto row_ptr = [&](int32_t v) { return kv_seq + (int64_t)(v < 0 ? 0 : v) * a.row_elems + 8 * gp; };
+    auto ids_mask = [&](const Ids &d) { return rows_mask(__ballot(d.lo >= 0), __ballot(d.hi >= 0)); };
 
     // Q as the B operand: lane (head 16 hb + l16, features 8 g..) for both head blocks
     bf16x8 qreg[2][KS];
@@ -336,6 +346,9 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         for (int ks = 0; ks < KS; ++ks) {
             u32x4 raw = u32x4{0u, 0u, 0u, 0u};
             if (ok) raw = *(const u32x4 *)(qp + 32 * ks);
+            // pin Q to the accumulation half of the register file (MFMA reads B operands from
+            // there directly): the vector half is needed for the gather and the LDS operands
+            asm volatile("" : "+a"(raw));
             qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
         }
     }
@@ -345,48 +358,73 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[nb][i] = 0.f;
-    float m_all[2] = {-INFINITY, -INFINITY};              // running maximum over all waves, heads 16hb+l16
+    float m_all[2] = {-INFINITY, -INFINITY};              // common reference of all waves, heads 16hb+l16
     float m_ref[2] = {-INFINITY, -INFINITY};              // this wave's current reference
-    float m_c = -INFINITY;                                // running maximum over all waves, head l32
+    float m_c = -INFINITY;                                // common reference, head l32
     float l_own[2] = {0.f, 0.f};                          // this lane's share of the wave's row sums (ref m_ref)
 
-    // The slab is one register array that is refilled chunk by chunk: as soon as chunk ks of the
-    // current tile has fed its two MFMAs and its LDS store, the same registers receive chunk ks of
-    // the next tile, so every load has a whole tile period to land and only one slab is live.
-    u32x4 cur[KS];
-    int32_t idx_cur = fetch_idx(0);
-    int32_t idx_nxt = fetch_idx(1);
-    if (ntiles > 0) gload(cur, idx_cur);
+    // LDS addresses of the lane in its three roles (byte offsets inside one tile buffer)
+    const int st_off = (16 * wave + gr) * ROWB + ((gp ^ slot_swz(gr)) << 4);          // + 8 rows for odd chunks
+    const int ka_row = (16 * wave + l16) * ROWB;
+    const int ka_e = ka_row + ((g ^ slot_swz(l16)) << 4);                             // even contraction steps
+    const int ka_o = ka_row + (((4 + g) ^ slot_swz(l16)) << 4);                       // odd ones
+    const int tr_row = 8 * hh + (l16 >> 2);
+    const int tr_slot = 4 * (wave & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
+    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ slot_swz(tr_row)) << 4) + 8 * (l16 & 1);
+    const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ slot_swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
 
-    auto step = [&](int it, auto prefetch) {
-        const int buf = it & 1;
-        const int32_t idx_n2 = fetch_idx(it + 2);
-        const unsigned short *nsrc = kv_seq + (int64_t)(idx_nxt < 0 ? 0 : idx_nxt) * a.row_elems + 8 * g;
-        // chunk c of the value part holds bytes 64 c + 16 g of the row; the swizzle only touches
-        // the low two bits of the 32-byte unit index, so even and odd chunks each sit at a
-        // constant stride from one lane-dependent base
-        unsigned char *we, *wo;
-        {
-            unsigned char *vb = vbuf + buf * VBUFB;
-            const int row = 16 * wave + l16;
-            we = vb + vswz<VROWB>(row, 16 * g);
-            wo = vb + vswz<VROWB>(row, 64 + 16 * g);
-        }
-        // S^T for the wave's 16 rows x 32 heads (one accumulation chain per head block)
-        f32x4 s2[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    // The gather registers are refilled chunk by chunk: as soon as chunk ks of tile t+1 has been
+    // stored to LDS, the same registers receive chunk ks of tile t+2.
+    u32x4 cur[KS];
+    auto gload = [&](const Ids &d) {
+        const unsigned short *pl = row_ptr(d.lo), *ph = row_ptr(d.hi);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
+    };
+    unsigned vm_cur, vm_n1;
+    Ids ids_n2;
+    {
+        const Ids d0 = fetch_ids(0), d1 = fetch_ids(1);
+        ids_n2 = fetch_ids(2);
+        gload(d0);
+        vm_cur = ids_mask(d0);
+        vm_n1 = ids_mask(d1);
+        const unsigned short *pl = row_ptr(d1.lo), *ph = row_ptr(d1.hi);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 ka = __builtin_bit_cast(bf16x8, cur[ks]);
-            s2[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[0][ks], s2[0], 0, 0, 0);
-            s2[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[1][ks], s2[1], 0, 0, 0);
-            if (ks >= V0S && ks < V0S + VS) {
-                const int c = ks - V0S;
-                *(u32x4 *)(((c & 1) ? wo : we) + 128 * (c >> 1)) = cur[ks];
-            }
-            if constexpr (decltype(prefetch)::value) cur[ks] = *(const u32x4 *)(nsrc + 32 * ks);
+            *(u32x4 *)(tbuf + st_off + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
+            cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
         }
-        // rows of the lane: 4 g + i; their validity from the row ids held by lanes 0..15
-        const unsigned vmask = (unsigned)(__ballot(idx_cur >= 0) & 0xFFFFull);
+    }
+
+    // One tile.  stage_next: tile it+1 exists (store it);  load_next2: tile it+2 exists (refill
+    // the gather registers).  The LDS pipeline is the busiest unit of this kernel (it spends about
+    // as long on a 4-byte access as on a 16-byte one), so everything that crosses it is packed
+    // into as few, as wide instructions as possible.
+    auto step = [&](int it, auto stage_next, auto load_next2) {
+        const int buf = it & 1;
+        const Ids ids_n3 = fetch_ids(it + 3);
+        const unsigned char *tb = tbuf + buf * TBUFB;
+
+        // S^T for the wave's 16 rows x 32 heads: two accumulation chains per head block
+        f32x4 s4[2][2];
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int par = 0; par < 2; ++par) s4[hb][par] = f32x4{0.f, 0.f, 0.f, 0.f};
+        constexpr int KRING = 6;                          // A-operand reads in flight ahead of the MFMAs
+        bf16x8 ka[KRING];
+        auto ka_read = [&](int ks) { return *(const bf16x8 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1)); };
+#pragma unroll
+        for (int r = 0; r < KRING; ++r) ka[r] = ka_read(r);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            s4[0][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks % KRING], qreg[0][ks], s4[0][ks & 1], 0, 0, 0);
+            s4[1][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks % KRING], qreg[1][ks], s4[1][ks & 1], 0, 0, 0);
+            if (ks + KRING < KS) ka[ks % KRING] = ka_read(ks + KRING);
+        }
+        // rows of the lane: 4 g + i.  A head row of the P tile is 128 bytes of probabilities
+        // followed by the four waves' reference maxima in its 16 bytes of padding.
         unsigned char *pb = pbuf + buf * PBUFB;
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb) {
@@ -394,8 +432,8 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             float mx = -INFINITY;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const bool ok = (vmask >> (4 * g + i)) & 1u;
-                z[i] = ok ? s2[hb][i] * a.scale_log2e : -INFINITY;
+                const bool ok = (vm_cur >> (4 * g + i)) & 1u;
+                z[i] = ok ? (s4[hb][0][i] + s4[hb][1][i]) * a.scale_log2e : -INFINITY;
                 mx = fmaxf(mx, z[i]);
             }
             mx = xmax16_32(mx);
@@ -414,45 +452,39 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             }
             l_own[hb] = l_own[hb] * resc + psum;
             m_ref[hb] = m_new;
-            *(s16x4 *)(pb + (16 * hb + l16) * PSTR + (16 * wave + 4 * g) * 2) = pk;
-            if (g == 0) mbuf[(buf * 4 + wave) * 32 + 16 * hb + l16] = m_new;
+            unsigned char *prow = pb + (16 * hb + l16) * PSTR;
+            *(s16x4 *)(prow + (16 * wave + 4 * g) * 2) = pk;
+            if (g == 0) *(float *)(prow + kSlabTile * 2 + 4 * wave) = m_new;
         }
         __syncthreads();
 
-        // transpose reads: the wave's value columns are 32 w + 128 nb + (0..31), so that nb only
-        // moves address bits above the swizzled ones; rows 16 j + 8 hh + (l16>>2) and + 4
-        const unsigned char *vb = vbuf + buf * VBUFB;
-        const int trow = 8 * hh + (l16 >> 2);
-        const int tcb = (32 * wave + 16 * (g & 1) + 4 * (l16 & 3)) * 2;
-        const unsigned char *vr0 = vb + vswz<VROWB>(trow, tcb);
-        const unsigned char *vr1 = vb + vswz<VROWB>(trow + 4, tcb);
+        // operands of the consumer role, all requested at once right behind the barrier: the four
+        // reference maxima and the probabilities of head l32, and every value operand of the tile
         typedef __attribute__((ext_vector_type(8))) short s16x8;
         typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        const f32x4 mjc = *(const f32x4 *)(pb + l32 * PSTR + kSlabTile * 2);
         bf16x8 pa[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) pa[j] = *(const bf16x8 *)(pb + l32 * PSTR + (16 * j + 8 * hh) * 2);
-        // the value operands of row group j+1 are requested before the MFMAs of group j issue
-        s16x4 vq[2][NBW][2];
-        auto vload = [&](int j) {
+        s16x4 vq[4][NBW][2];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int nb = 0; nb < NBW; ++nb) {
-                vq[j & 1][nb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr0 + 16 * j * VROWB + 256 * nb));
-                vq[j & 1][nb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(vr1 + 16 * j * VROWB + 256 * nb));
+                vq[j][nb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
+                vq[j][nb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
             }
-        };
-        vload(0);
+        __builtin_amdgcn_sched_barrier(0);
 
-        // maxima of the four row groups: for the producer heads 16hb + l16 (next tile's reference)
-        // and for the head l32 whose probabilities the lane feeds to the MFMA as the A operand
-#pragma unroll
-        for (int hb = 0; hb < 2; ++hb) {
-            const float *mp = mbuf + buf * 128 + 16 * hb + l16;
-            m_all[hb] = fmaxf(fmaxf(mp[0], mp[32]), fmaxf(mp[64], mp[96]));
-        }
-        float mjc[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) mjc[j] = mbuf[buf * 128 + 32 * j + l32];
+        // new common reference of head l32 (= 16 (g&1) + l16); the producer role needs it for heads
+        // l16 and 16 + l16, one of which lives in the neighbouring 16-lane group
         const float m_new_c = fmaxf(fmaxf(mjc[0], mjc[1]), fmaxf(mjc[2], mjc[3]));
+        {
+            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m_new_c), __float_as_uint(m_new_c), false, false);
+            // sw[0] = groups [0,0,2,2], sw[1] = groups [1,1,3,3]: heads l16 and 16 + l16
+            m_all[0] = __uint_as_float(sw[0]);
+            m_all[1] = __uint_as_float(sw[1]);
+        }
         const float alpha = (m_new_c == -INFINITY) ? 1.f : fast_exp2(m_c - m_new_c);
         m_c = m_new_c;
         float fj[4];
@@ -469,78 +501,99 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             f32x4 ar[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) ar[q] = *(const f32x4 *)(ab + 8 * q + 4 * hh);
+            // The accumulators live in accumulation registers; move each value out and back right
+            // here (opaque to the compiler), otherwise it copies all 64 of them to vector registers
+            // ahead of the branch in every tile.  The MFMAs that wrote them retired a tile ago and
+            // the next MFMA that reads them is far behind the trailing no-ops.
 #pragma unroll
             for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[nb][i] *= ar[i >> 2][i & 3];
+                for (int i = 0; i < 16; ++i) {
+                    float t;
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(oacc[nb][i]));
+                    t *= ar[i >> 2][i & 3];
+                    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(oacc[nb][i]) : "v"(t));
+                }
+            asm volatile("s_nop 7\n\ts_nop 7");
         }
-        const bool scale_p = __ballot(any_f) != 0ull;
-        if (scale_p) {
+        if (__ballot(any_f) != 0ull) {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pa[j][e] = (__bf16)((float)pa[j][e] * fj[j]);
         }
+        const unsigned vm_n2 = ids_mask(ids_n2);
+
+        // O += P V, with the staging of tile it+1 (every wave is past the previous tile's reads of
+        // the other buffer) and the gather of tile it+2 issued in the shadow of the MFMAs
+        unsigned char *tn = tbuf + (buf ^ 1) * TBUFB + st_off;
+        const unsigned short *pl = row_ptr(ids_n2.lo), *ph = row_ptr(ids_n2.hi);
+        auto stage = [&](int ks) {
+            if constexpr (decltype(stage_next)::value) {
+                if (ks < KS) {
+                    *(u32x4 *)(tn + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
+                    if constexpr (decltype(load_next2)::value) cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
+                }
+            }
+        };
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (j + 1 < 4) vload(j + 1);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int nb = 0; nb < NBW; ++nb) {
-                const s16x4 v0 = vq[j & 1][nb][0], v1 = vq[j & 1][nb][1];
+                const s16x4 v0 = vq[j][nb][0], v1 = vq[j][nb][1];
                 const s16x8 vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
                 oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[j], __builtin_bit_cast(bf16x8, vv), oacc[nb], 0, 0, 0);
+                stage(4 * j + nb);
             }
-            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 4 * NBW; ks < KS; ++ks) stage(ks);
+        if constexpr (decltype(stage_next)::value) {
+            // keep the order: one MFMA, then one LDS store and (when there is one) one gather load
+#pragma unroll
+            for (int k = 0; k < 4 * NBW; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                if constexpr (decltype(load_next2)::value) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
         }
-        idx_cur = idx_nxt;
-        idx_nxt = idx_n2;
+        vm_cur = vm_n1;
+        vm_n1 = vm_n2;
+        ids_n2 = ids_n3;
     };
 
     {
         int it = 0;
 #pragma unroll 1
-        for (; it + 1 < ntiles; ++it) step(it, std::true_type{});
-        if (it < ntiles) step(it, std::false_type{});
+        for (; it + 2 < ntiles; ++it) step(it, std::true_type{}, std::true_type{});
+        if (it + 1 < ntiles) {
+            step(it, std::true_type{}, std::false_type{});
+            ++it;
+        }
+        if (it < ntiles) step(it, std::false_type{}, std::false_type{});
     }
 
     // ---- epilogue: combine the producers' row sums, normalise, store ----
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb) {
         const float l = xsum16_32(l_own[hb]);
-        // bring the wave's sum to the common maximum before publishing it
+        // bring the wave's sum to the common reference before publishing it
         const float f = (m_all[hb] == -INFINITY) ? 0.f : fast_exp2(m_ref[hb] - m_all[hb]);
         if (g == 0) lbuf[wave * 32 + 16 * hb + l16] = l * f;
     }
     __syncthreads();
     const float l_head = lbuf[l32] + lbuf[32 + l32] + lbuf[64 + l32] + lbuf[96 + l32];   // head l32
     const float m_head = m_c;
-    const bool split = a.n_splits > 1;
-    if (wave == 0 && hh == 0 && l32 < a.H_q) {
-        if (split) {
-            float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + l32) * 2;
-            ml[0] = m_head;
-            ml[1] = l_head;
-        } else if (a.lse) {
-            a.lse[qrow * a.H_q + l32] =
-                (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
-        }
-    }
+    if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
+        a.lse[qrow * a.H_q + l32] = (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);   // O row (head) of accumulator element i
         const float l = __shfl(l_head, hq);
         if (hq >= a.H_q) continue;
-        if (split) {
-            float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + 32 * wave + l32;
+        const float inv = (l > 0.f) ? 1.f / l : 0.f;
+        __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + 32 * wave + l32;
 #pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = oacc[nb][i];
-        } else {
-            const float inv = (l > 0.f) ? 1.f / l : 0.f;
-            __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + 32 * wave + l32;
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
-        }
+        for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
     }
 }
 
@@ -587,15 +640,15 @@ hipError_t launch_t(const AttnArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
-template <int D_QK, int D_V, int V0S>
+template <int D_QK, int D_V>
 hipError_t launch_slab(const AttnArgs &a, hipStream_t st)
 {
-    const size_t lds = (size_t)2 * kSlabTile * D_V * 2 + 2 * 32 * (kSlabTile * 2 + 16) + (2 * 4 * 32 + 4 * 32 + 4 * 32) * sizeof(float);
-    static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, V0S>,
+    const size_t lds = (size_t)2 * kSlabTile * D_QK * 2 + 2 * 32 * (kSlabTile * 2 + 16) + (4 * 32 + 4 * 32) * sizeof(float);
+    static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return attr;
-    dim3 grid((unsigned)((int64_t)a.B * a.Tq), (unsigned)a.n_splits);
-    hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, V0S>), grid, dim3(256), lds, st, a);
+    dim3 grid((unsigned)((int64_t)a.B * a.Tq));
+    hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
@@ -610,8 +663,9 @@ hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st)
 {
     if ((int64_t)a.B * a.Tq <= 0) return hipSuccess;
     if (d_qk == 576 && d_v == 512) {
-        static const bool tile_form = getenv("IC_ATTN_TILE") != nullptr;
-        if (!tile_form && a.v_off == 0) return launch_slab<576, 512, 0>(a, st);
+        // whole-selection launches (many queries) take the row-slab form, split launches (decode)
+        // the small-tile form with two workgroups per CU
+        if (a.n_splits == 1 && a.v_off == 0) return launch_slab<576, 512>(a, st);
         return launch_t<576, 512, 576>(a, st);
     }
     if (d_qk == 64 && d_v == 64) return launch_t<64, 64, 128>(a, st);

@@ -107,7 +107,6 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     }
 
     const bool cached = nv <= a.cache_elems;   // workgroup-uniform
-    auto get_key = [&](int p) -> uint32_t { return cached ? cache[p] : score_key(row[p]); };
     // four consecutive keys starting at p (p % 4 == 0); entries at or beyond nv are unspecified
     auto get_key4 = [&](int p) -> u32x4 {
         u32x4 k4 = u32x4{0u, 0u, 0u, 0u};

@@ -222,6 +222,11 @@ ATTN_CASES = [
     (2, 3, 500, 32, 576, 512, 0, 576, 256, 497, False),  # few queries: split path + merge kernel
     (1, 20, 400, 20, 576, 512, 0, 576, 200, 380, True),  # ragged heads, ragged k_sel, holes in idx
     (2, 5, 90, 16, 64, 64, 64, 128, 70, 85, True),
+    # 512 or more queries: one workgroup per query over 64-row tiles (the prefill form)
+    (1, 600, 700, 32, 576, 512, 0, 576, 200, 100, True),  # ragged last tile, holes in idx
+    (2, 300, 400, 20, 576, 512, 0, 576, 130, 150, True),  # ragged heads
+    (1, 520, 520, 32, 576, 512, 0, 640, 64, 0, False),    # padded KV rows, one tile, short causal rows
+    (1, 512, 300, 32, 576, 512, 0, 576, 2, 40, False),    # two slots only
 ]
 
 
@@ -240,9 +245,10 @@ def test_sparse_attn(ic, oracle, case):
     assert np.allclose(lse.cpu().numpy(), want_lse, rtol=0, atol=2e-2)
 
 
-def test_sparse_attn_empty_rows_and_out_of_range(ic, oracle):
-    say("attn empty rows / out-of-range entries")
-    B, Tq, Lk, Hq, d_qk, d_v, row, ks = 1, 4, 50, 32, 576, 512, 576, 64
+@pytest.mark.parametrize("Tq", [4, 512])
+def test_sparse_attn_empty_rows_and_out_of_range(ic, oracle, Tq):
+    say("attn empty rows / out-of-range entries, Tq=%d" % Tq)
+    B, Lk, Hq, d_qk, d_v, row, ks = 1, 50, 32, 576, 512, 576, 64
     Q, KV = _mk_attn(9, B, Tq, Lk, Hq, d_qk, row)
     idx = np.full((B, Tq, ks), -1, dtype=np.int32)
     idx[0, 1, :5] = [3, 7, 9, 11, 49]
