@@ -397,164 +397,186 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         }
     }
 
-    // One tile.  stage_next: tile it+1 exists (store it);  load_next2: tile it+2 exists (refill
-    // the gather registers).  The LDS pipeline is the busiest unit of this kernel (it spends about
-    // as long on a 4-byte access as on a 16-byte one), so everything that crosses it is packed
-    // into as few, as wide instructions as possible.
-    auto step = [&](int it, auto stage_next, auto load_next2) {
+    // One step = the producer role for tile `it` and the consumer role for tile it-1 (have_prev).
+    // stage_next: tile it+1 exists (store it);  load_next2: tile it+2 exists (refill the gather
+    // registers).  The LDS pipeline is the busiest unit of this kernel (it spends about as long on
+    // a 4-byte access as on a 16-byte one), so everything that crosses it is packed into wide
+    // instructions and spread over the step: A-operand reads under the S^T MFMAs, the previous
+    // tile's P/V operand reads under the softmax arithmetic, the staging stores under the PV MFMAs.
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    auto step = [&](int it, auto have_prev, auto have_cur, auto stage_next, auto load_next2) {
+        constexpr bool kPrev = decltype(have_prev)::value, kCur = decltype(have_cur)::value;
+        constexpr bool kStage = decltype(stage_next)::value, kLoad = decltype(load_next2)::value;
         const int buf = it & 1;
-        const Ids ids_n3 = fetch_ids(it + 3);
-        const unsigned char *tb = tbuf + buf * TBUFB;
+        Ids ids_n3 = ids_n2;
+        if constexpr (kCur) ids_n3 = fetch_ids(it + 3);
+        const unsigned char *tb = tbuf + buf * TBUFB;                 // tile it
+        const unsigned char *tp = tbuf + (buf ^ 1) * TBUFB;           // tile it-1
+        unsigned char *pb = pbuf + buf * PBUFB;                       // P of tile it
+        const unsigned char *pp = pbuf + (buf ^ 1) * PBUFB;           // P of tile it-1
+
+        // reference maxima of tile it-1 first: the softmax of tile it builds on them
+        f32x4 mjc = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if constexpr (kPrev) mjc = *(const f32x4 *)(pp + l32 * PSTR + kSlabTile * 2);
 
         // S^T for the wave's 16 rows x 32 heads: two accumulation chains per head block
         f32x4 s4[2][2];
+        if constexpr (kCur) {
 #pragma unroll
-        for (int hb = 0; hb < 2; ++hb)
+            for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
-            for (int par = 0; par < 2; ++par) s4[hb][par] = f32x4{0.f, 0.f, 0.f, 0.f};
-        constexpr int KRING = 6;                          // A-operand reads in flight ahead of the MFMAs
-        bf16x8 ka[KRING];
-        auto ka_read = [&](int ks) { return *(const bf16x8 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1)); };
+                for (int par = 0; par < 2; ++par) s4[hb][par] = f32x4{0.f, 0.f, 0.f, 0.f};
+            constexpr int KRING = 6;                      // A-operand reads in flight ahead of the MFMAs
+            bf16x8 ka[KRING];
+            auto ka_read = [&](int ks) { return *(const bf16x8 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1)); };
 #pragma unroll
-        for (int r = 0; r < KRING; ++r) ka[r] = ka_read(r);
+            for (int r = 0; r < KRING; ++r) ka[r] = ka_read(r);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            s4[0][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks % KRING], qreg[0][ks], s4[0][ks & 1], 0, 0, 0);
-            s4[1][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks % KRING], qreg[1][ks], s4[1][ks & 1], 0, 0, 0);
-            if (ks + KRING < KS) ka[ks % KRING] = ka_read(ks + KRING);
-        }
-        // rows of the lane: 4 g + i.  A head row of the P tile is 128 bytes of probabilities
-        // followed by the four waves' reference maxima in its 16 bytes of padding.
-        unsigned char *pb = pbuf + buf * PBUFB;
-#pragma unroll
-        for (int hb = 0; hb < 2; ++hb) {
-            float z[4];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const bool ok = (vm_cur >> (4 * g + i)) & 1u;
-                z[i] = ok ? (s4[hb][0][i] + s4[hb][1][i]) * a.scale_log2e : -INFINITY;
-                mx = fmaxf(mx, z[i]);
+            for (int ks = 0; ks < KS; ++ks) {
+                s4[0][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks % KRING], qreg[0][ks], s4[0][ks & 1], 0, 0, 0);
+                s4[1][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks % KRING], qreg[1][ks], s4[1][ks & 1], 0, 0, 0);
+                if (ks + KRING < KS) ka[ks % KRING] = ka_read(ks + KRING);
             }
-            mx = xmax16_32(mx);
-            // lazy reference: keep the common reference until this tile exceeds it by more than
-            // 2^kLazyLog2 (probabilities up to that factor are harmless in bf16/fp32), so that the
-            // rescaling paths below run only on real jumps of the maximum
-            const float m_new = (mx > m_all[hb] + kLazyLog2) ? mx : m_all[hb];   // m_all >= m_ref always
-            const float resc = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref[hb] - m_new);
-            float psum = 0.f;
-            s16x4 pk;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float p = (z[i] == -INFINITY) ? 0.f : fast_exp2(z[i] - m_new);
-                psum += p;
-                pk[i] = __builtin_bit_cast(short, (__bf16)p);
-            }
-            l_own[hb] = l_own[hb] * resc + psum;
-            m_ref[hb] = m_new;
-            unsigned char *prow = pb + (16 * hb + l16) * PSTR;
-            *(s16x4 *)(prow + (16 * wave + 4 * g) * 2) = pk;
-            if (g == 0) *(float *)(prow + kSlabTile * 2 + 4 * wave) = m_new;
         }
-        __syncthreads();
 
-        // operands of the consumer role, all requested at once right behind the barrier: the four
-        // reference maxima and the probabilities of head l32, and every value operand of the tile
-        typedef __attribute__((ext_vector_type(8))) short s16x8;
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-        const f32x4 mjc = *(const f32x4 *)(pb + l32 * PSTR + kSlabTile * 2);
+        // consumer operands of tile it-1: probabilities of head l32 and every value operand.  They
+        // stream in while the softmax below keeps the vector ALU busy.
         bf16x8 pa[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pa[j] = *(const bf16x8 *)(pb + l32 * PSTR + (16 * j + 8 * hh) * 2);
         s16x4 vq[4][NBW][2];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) {
-                vq[j][nb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
-                vq[j][nb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
-            }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // new common reference of head l32 (= 16 (g&1) + l16); the producer role needs it for heads
-        // l16 and 16 + l16, one of which lives in the neighbouring 16-lane group
-        const float m_new_c = fmaxf(fmaxf(mjc[0], mjc[1]), fmaxf(mjc[2], mjc[3]));
-        {
-            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m_new_c), __float_as_uint(m_new_c), false, false);
-            // sw[0] = groups [0,0,2,2], sw[1] = groups [1,1,3,3]: heads l16 and 16 + l16
-            m_all[0] = __uint_as_float(sw[0]);
-            m_all[1] = __uint_as_float(sw[1]);
-        }
-        const float alpha = (m_new_c == -INFINITY) ? 1.f : fast_exp2(m_c - m_new_c);
-        m_c = m_new_c;
-        float fj[4];
+        float alpha = 1.f, fj[4] = {1.f, 1.f, 1.f, 1.f};
         bool any_f = false;
+        if constexpr (kPrev) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            fj[j] = (m_new_c == -INFINITY) ? 1.f : fast_exp2(mjc[j] - m_new_c);
-            any_f |= (fj[j] != 1.f);
-        }
-        if (__ballot(alpha != 1.f) != 0ull) {
-            // the rescale factors of the 16 heads a lane accumulates, through a per-wave LDS row
-            float *ab = abuf + wave * 32;
-            if (hh == 0) ab[l32] = alpha;
-            f32x4 ar[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) ar[q] = *(const f32x4 *)(ab + 8 * q + 4 * hh);
-            // The accumulators live in accumulation registers; move each value out and back right
-            // here (opaque to the compiler), otherwise it copies all 64 of them to vector registers
-            // ahead of the branch in every tile.  The MFMAs that wrote them retired a tile ago and
-            // the next MFMA that reads them is far behind the trailing no-ops.
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float t;
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(oacc[nb][i]));
-                    t *= ar[i >> 2][i & 3];
-                    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(oacc[nb][i]) : "v"(t));
-                }
-            asm volatile("s_nop 7\n\ts_nop 7");
-        }
-        if (__ballot(any_f) != 0ull) {
+            for (int j = 0; j < 4; ++j) pa[j] = *(const bf16x8 *)(pp + l32 * PSTR + (16 * j + 8 * hh) * 2);
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pa[j][e] = (__bf16)((float)pa[j][e] * fj[j]);
+                for (int nb = 0; nb < NBW; ++nb) {
+                    vq[j][nb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tp + tr0 + 16 * j * ROWB + 256 * nb));
+                    vq[j][nb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tp + tr1 + 16 * j * ROWB + 256 * nb));
+                }
+            // new common reference of head l32 (= 16 (g&1) + l16); the producer role needs it for
+            // heads l16 and 16 + l16, one of which lives in the neighbouring 16-lane group
+            const float m_new_c = fmaxf(fmaxf(mjc[0], mjc[1]), fmaxf(mjc[2], mjc[3]));
+            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m_new_c), __float_as_uint(m_new_c), false, false);
+            m_all[0] = __uint_as_float(sw[0]);            // groups [0,0,2,2]: head l16
+            m_all[1] = __uint_as_float(sw[1]);            // groups [1,1,3,3]: head 16 + l16
+            alpha = (m_new_c == -INFINITY) ? 1.f : fast_exp2(m_c - m_new_c);
+            m_c = m_new_c;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                fj[j] = (m_new_c == -INFINITY) ? 1.f : fast_exp2(mjc[j] - m_new_c);
+                any_f |= (fj[j] != 1.f);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // producer role: rows 4 g + i of the wave.  A head row of the P tile is 128 bytes of
+        // probabilities followed by the four waves' reference maxima in its 16 bytes of padding.
+        if constexpr (kCur) {
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                float z[4];
+                float mx = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool ok = (vm_cur >> (4 * g + i)) & 1u;
+                    z[i] = ok ? (s4[hb][0][i] + s4[hb][1][i]) * a.scale_log2e : -INFINITY;
+                    mx = fmaxf(mx, z[i]);
+                }
+                mx = xmax16_32(mx);
+                // lazy reference: keep the common reference until this tile exceeds it by more than
+                // 2^kLazyLog2 (probabilities up to that factor are harmless in bf16/fp32), so that
+                // the rescaling paths below run only on real jumps of the maximum
+                const float m_new = (mx > m_all[hb] + kLazyLog2) ? mx : m_all[hb];   // m_all >= m_ref always
+                const float resc = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref[hb] - m_new);
+                float psum = 0.f;
+                s16x4 pk;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p = (z[i] == -INFINITY) ? 0.f : fast_exp2(z[i] - m_new);
+                    psum += p;
+                    pk[i] = __builtin_bit_cast(short, (__bf16)p);
+                }
+                l_own[hb] = l_own[hb] * resc + psum;
+                m_ref[hb] = m_new;
+                unsigned char *prow = pb + (16 * hb + l16) * PSTR;
+                *(s16x4 *)(prow + (16 * wave + 4 * g) * 2) = pk;
+                if (g == 0) *(float *)(prow + kSlabTile * 2 + 4 * wave) = m_new;
+            }
+        }
+        // P of tile it is written; every wave has all its reads of tile it-1 back
+        __syncthreads();
+
+        if constexpr (kPrev) {
+            if (__ballot(alpha != 1.f) != 0ull) {
+                // the rescale factors of the 16 heads a lane accumulates, through a per-wave LDS row
+                float *ab = abuf + wave * 32;
+                if (hh == 0) ab[l32] = alpha;
+                f32x4 ar[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ar[q] = *(const f32x4 *)(ab + 8 * q + 4 * hh);
+                // The accumulators live in accumulation registers; move each value out and back
+                // right here (opaque to the compiler), otherwise it copies all 64 of them to vector
+                // registers ahead of the branch in every tile.  The MFMAs that wrote them retired
+                // a tile ago and the next MFMA that reads them is far behind the trailing no-ops.
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float t;
+                        asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(oacc[nb][i]));
+                        t *= ar[i >> 2][i & 3];
+                        asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(oacc[nb][i]) : "v"(t));
+                    }
+                asm volatile("s_nop 7\n\ts_nop 7");
+            }
+            if (__ballot(any_f) != 0ull) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pa[j][e] = (__bf16)((float)pa[j][e] * fj[j]);
+            }
         }
         const unsigned vm_n2 = ids_mask(ids_n2);
 
-        // O += P V, with the staging of tile it+1 (every wave is past the previous tile's reads of
-        // the other buffer) and the gather of tile it+2 issued in the shadow of the MFMAs
+        // O += P V for tile it-1, with the staging of tile it+1 (nobody reads that buffer any more)
+        // and the gather of tile it+2 issued in the shadow of the MFMAs
         unsigned char *tn = tbuf + (buf ^ 1) * TBUFB + st_off;
         const unsigned short *pl = row_ptr(ids_n2.lo), *ph = row_ptr(ids_n2.hi);
         auto stage = [&](int ks) {
-            if constexpr (decltype(stage_next)::value) {
+            if constexpr (kStage) {
                 if (ks < KS) {
                     *(u32x4 *)(tn + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
-                    if constexpr (decltype(load_next2)::value) cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
+                    if constexpr (kLoad) cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
                 }
             }
         };
+        if constexpr (kPrev) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) {
-                const s16x4 v0 = vq[j][nb][0], v1 = vq[j][nb][1];
-                const s16x8 vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-                oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[j], __builtin_bit_cast(bf16x8, vv), oacc[nb], 0, 0, 0);
-                stage(4 * j + nb);
+                for (int nb = 0; nb < NBW; ++nb) {
+                    const s16x4 v0 = vq[j][nb][0], v1 = vq[j][nb][1];
+                    const s16x8 vv = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa[j], __builtin_bit_cast(bf16x8, vv), oacc[nb], 0, 0, 0);
+                    stage(4 * j + nb);
+                }
+#pragma unroll
+            for (int ks = 4 * NBW; ks < KS; ++ks) stage(ks);
+            if constexpr (kStage) {
+                // keep the order: one MFMA, then one LDS store and (when there is one) one gather load
+#pragma unroll
+                for (int k = 0; k < 4 * NBW; ++k) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                    if constexpr (kLoad) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
             }
+        } else {
 #pragma unroll
-        for (int ks = 4 * NBW; ks < KS; ++ks) stage(ks);
-        if constexpr (decltype(stage_next)::value) {
-            // keep the order: one MFMA, then one LDS store and (when there is one) one gather load
-#pragma unroll
-            for (int k = 0; k < 4 * NBW; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                if constexpr (decltype(load_next2)::value) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
+            for (int ks = 0; ks < KS; ++ks) stage(ks);
         }
         vm_cur = vm_n1;
         vm_n1 = vm_n2;
@@ -562,14 +584,24 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     };
 
     {
-        int it = 0;
+        constexpr std::true_type T{};
+        constexpr std::false_type F{};
+        // step 0 has no previous tile, step ntiles has no current one
+        if (ntiles == 1) {
+            step(0, F, T, F, F);
+        } else if (ntiles == 2) {
+            step(0, F, T, T, F);
+            step(1, T, T, F, F);
+        } else {
+            step(0, F, T, T, T);
+            int it = 1;
 #pragma unroll 1
-        for (; it + 2 < ntiles; ++it) step(it, std::true_type{}, std::true_type{});
-        if (it + 1 < ntiles) {
-            step(it, std::true_type{}, std::false_type{});
+            for (; it + 2 < ntiles; ++it) step(it, T, T, T, T);
+            step(it, T, T, T, F);
             ++it;
+            step(it, T, T, F, F);
         }
-        if (it < ntiles) step(it, std::false_type{}, std::false_type{});
+        step(ntiles, T, F, F, F);
     }
 
     // ---- epilogue: combine the producers' row sums, normalise, store ----
