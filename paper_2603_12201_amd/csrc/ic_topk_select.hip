@@ -20,8 +20,9 @@ namespace {
 __device__ __forceinline__ uint32_t score_key(float x)
 {
     uint32_t u = __float_as_uint(x);
-    if (u == 0x80000000u) u = 0u;                      // -0 and +0 are the same score
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u); // larger float <=> larger key
+    u = (u == 0x80000000u) ? 0u : u;                   // -0 and +0 are the same score
+    const uint32_t flip = (uint32_t)((int32_t)u >> 31) | 0x80000000u;   // all ones for negatives, else the sign bit
+    return u ^ flip;                                   // larger float <=> larger key
 }
 
 __device__ __forceinline__ float key_score(uint32_t key)
@@ -240,6 +241,150 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     }
 }
 
+// ---- register-resident form (rows of up to NT*4*NCH scores) ----------------------------------
+// Same radix select for rows that do not fit the LDS cache: the row is read from memory exactly
+// once and then lives in registers as keys (a thread owns 4 consecutive positions of every chunk
+// of 4*NT positions), so the three digit passes and the ordered emit never touch memory again.  Prefix counts inside a wave come
+// from ballots and mbcnt (no shuffles through the LDS crossbar); the waves are combined through
+// one packed LDS word per wave and chunk.
+template <int NT, int NCH>
+__global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
+{
+    constexpr int NW = NT / 64;
+    __shared__ uint32_t hist[kBins1];
+    __shared__ uint32_t wsum[2 * NW];
+    __shared__ uint32_t bc[4];
+    __shared__ __attribute__((aligned(16))) uint32_t wtot[2][NW < 4 ? 4 : NW];   // emit: equal << 16 | greater per wave
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x;
+    const int b = a.b0 + r / a.Ri;
+    const int i = a.i0 + r % a.Ri;
+    if (i >= a.Tq) return;
+    int64_t nv64 = a.q_pos0 + (int64_t)i + 1;
+    nv64 = nv64 < 0 ? 0 : (nv64 > a.Lk ? a.Lk : nv64);
+    const int nv = (int)nv64;
+    const float *row = a.strip + (int64_t)r * a.ld;
+    int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
+    float *osel = a.sel ? a.sel + ((int64_t)b * a.Tq + i) * a.k_sel : nullptr;
+
+    if (nv <= a.k_sel) {                       // every visible key is selected
+        for (int m = tid; m < a.k_sel; m += NT) {
+            oidx[m] = m < nv ? m : -1;
+            if (osel) osel[m] = m < nv ? row[m] : -INFINITY;
+        }
+        return;
+    }
+
+    // Keys of the row.  Rows start 256-byte aligned and are padded to a multiple of 64 floats, so
+    // the last vector may run past nv (never past the row).  Positions at or beyond nv get key 0:
+    // it is below the key of every finite score, lands in the lowest histogram bin and is never
+    // reached by a search for k <= nv real entries.
+    u32x4 key[NCH];
+    {
+        // unconditional loads (address clamped into the row, value masked); a group of kGroup
+        // vectors is in flight while the previous group is turned into keys
+        constexpr int kGroup = NCH < 8 ? NCH : 8;
+        f32x4 raw[2][kGroup];
+        auto load_group = [&](int c0, f32x4 (&dst)[kGroup]) {
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j) dst[j] = *(const f32x4 *)(row + min(((c0 + j) * NT + tid) * 4, (int)a.ld - 4));
+        };
+        load_group(0, raw[0]);
+#pragma unroll
+        for (int c0 = 0; c0 < NCH; c0 += kGroup) {
+            if (c0 + kGroup < NCH) load_group(c0 + kGroup, raw[(c0 / kGroup + 1) & 1]);
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j) {
+                const int p = ((c0 + j) * NT + tid) * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) key[c0 + j][e] = (p + e < nv) ? score_key(raw[(c0 / kGroup) & 1][j][e]) : 0u;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // ---- three digit passes: 12 + 12 + 8 bits, most significant first ----
+    uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)a.k_sel;
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 20 : (pass == 1 ? 8 : 0);
+        const uint32_t dmask = pass == 2 ? 255u : 4095u;
+        for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if ((key[c][e] & prefix_mask) == prefix) atomicAdd(&hist[(key[c][e] >> shift) & dmask], 1u);
+        __syncthreads();
+        find_digit<NT, kBins1 / NT>(hist, need, wsum, bc, tid, lane, wave);
+        prefix |= bc[0] << shift;
+        prefix_mask |= dmask << shift;
+        need = bc[1];
+        __syncthreads();
+    }
+    const uint32_t tau = prefix;               // key of the k-th largest score
+    const uint32_t need_eq = need;             // how many entries equal to tau are selected
+
+    // ---- ordered emit: slot = #greater before + min(#equal before, need_eq) ----
+    uint32_t run_g = 0, run_e = 0;
+    int tid_e = tid;
+    asm volatile("" : "+v"(tid_e));                    // recompute positions here: the 4*NCH values computed
+                                                       // for the load masks would otherwise stay live all along
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        if (c * NT * 4 >= nv) continue;                // workgroup-uniform; nothing left in this chunk
+        const int p = (c * NT + tid_e) * 4;
+        uint32_t lower_g = 0, lower_e = 0, wave_g = 0, wave_e = 0;
+        bool g[4], q[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            g[e] = key[c][e] > tau;
+            q[e] = key[c][e] == tau;
+            const unsigned long long bg = __ballot(g[e]), bq = __ballot(q[e]);
+            lower_g += __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
+            lower_e += __builtin_amdgcn_mbcnt_hi((uint32_t)(bq >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bq, 0u));
+            wave_g += (uint32_t)__popcll(bg);
+            wave_e += (uint32_t)__popcll(bq);
+        }
+        // positions are thread-major: all four entries of every lower lane come first, then the
+        // lane's own in order
+        if (lane == 0) wtot[c & 1][wave] = (wave_e << 16) | wave_g;   // at most 256 each
+        __syncthreads();
+        uint32_t before_g = run_g + lower_g, before_e = run_e + lower_e, tot_g = 0, tot_e = 0;
+#pragma unroll
+        for (int w4 = 0; w4 < NW; w4 += 4) {
+            const u32x4 t4 = *(const u32x4 *)&wtot[c & 1][w4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (w4 + j >= NW) continue;
+                const uint32_t tg = t4[j] & 0xFFFFu, te = t4[j] >> 16;
+                if (w4 + j < wave) {
+                    before_g += tg;
+                    before_e += te;
+                }
+                tot_g += tg;
+                tot_e += te;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (g[e] || (q[e] && before_e < need_eq)) {
+                const uint32_t slot = before_g + (before_e < need_eq ? before_e : need_eq);
+                if (slot < (uint32_t)a.k_sel) {        // always true for a consistent select
+                    oidx[slot] = p + e;
+                    if (osel) osel[slot] = key_score(key[c][e]);
+                }
+            }
+            before_g += g[e] ? 1u : 0u;
+            before_e += q[e] ? 1u : 0u;
+        }
+        run_g += tot_g;
+        run_e += tot_e;
+    }
+}
+
 size_t select_lds_bytes(int cache_elems)
 {
     return (size_t)(kBins1 + 2 * 16 + 4 + cache_elems) * sizeof(uint32_t);
@@ -253,11 +398,11 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
 {
     if (n_rows <= 0) return hipSuccess;
     SelectArgs a = a_in;
-    int cache = max_row_len <= select_cache_limit() ? (max_row_len + 63) / 64 * 64 : select_cache_limit();
+    int cache = max_row_len <= select_cache_limit() ? (max_row_len + 63) / 64 * 64 : 0;
     if (max_row_len <= a.k_sel) cache = 0;     // short rows never reach the radix path
     a.cache_elems = cache;
     const size_t lds = select_lds_bytes(cache);
-    // opt in once per process to the largest LDS footprint either variant can ask for
+    // opt in once per process to the largest LDS footprint either cached variant can ask for
     static hipError_t attr256 = hipFuncSetAttribute((const void *)select_kernel<256>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                                     (int)select_lds_bytes(8192));
@@ -268,8 +413,14 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     if (attr1024 != hipSuccess) return attr1024;
     if (max_row_len <= 8192)
         hipLaunchKernelGGL((select_kernel<256>), dim3((unsigned)n_rows), dim3(256), lds, st, a);
-    else
+    else if (max_row_len <= select_cache_limit())
         hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);
+    else if (max_row_len <= 65536)
+        // too long for the LDS cache, short enough for the registers of one workgroup (the decode
+        // shape: few rows of 64K scores): read once, select in registers
+        hipLaunchKernelGGL((select_reg_kernel<1024, 16>), dim3((unsigned)n_rows), dim3(1024), 0, st, a);
+    else
+        hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);   // streams the row on every sweep
     return hipGetLastError();
 }
 

@@ -141,6 +141,7 @@ TOPK_CASES = [
     (2, 1, 1000, 32, 128, 999, 256),     # decode
     (1, 33, 9000, 32, 128, 8967, 2048),  # long rows: 1024-thread select, LDS-cached row
     (1, 40, 300, 64, 128, 260, 1),       # k = 1: argmax
+    (2, 2, 40000, 32, 128, 39998, 512),  # rows past the LDS cache: read once, selected in registers
 ]
 
 
