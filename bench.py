@@ -91,7 +91,7 @@ class Stack:
 
 
 def algorithmic(cfg):
-    """Algorithmic work of ONE layer's kernels (per-unit figures)."""
+    """Algorithmic work of ONE layer's kernels: flops per causal pair, bytes per key / score / query token."""
     B, Tq, Lk, p0 = cfg["B"], cfg["Tq"], cfg["Lk"], cfg["q_pos0"]
     pairs = sum(max(0, min(Lk, p0 + i + 1)) for i in range(Tq)) * B if Tq <= 4096 else \
         B * (Tq * (Tq + 1) // 2 if p0 == 0 and Tq == Lk else Tq * Lk)
