@@ -4,7 +4,7 @@
  * The library computes, on one GPU, the attention-side hot path of DeepSeek Sparse
  * Attention with IndexCache's cross-layer index reuse:
  *   (1) the causal lightning-indexer score  I[t,s] = sum_j w[t,j] * ReLU(q[t,j,:] . k[s,:])
- *       ("multi-head ReLU-gated dot product" over all preceding tokens, paper Sec. 2.1;
+ *       (the ReLU-gated, head-weighted dot-product indexer over the earlier tokens, paper Sec. 2.1;
  *       score vector I_t of Sec. 3 Notation),
  *   (2) the per-query index set T_t = Top-k(I_t) (Sec. 3 Notation),
  *   (3) sparse core attention over exactly the selected rows (Sec. 2.1, MLA/MQA form),

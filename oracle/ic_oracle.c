@@ -11,15 +11,15 @@
  *
  * What is defined here and where it comes from:
  *   - indexer score  I[t,s] = sum_j w[t,j] * ReLU( q[t,j,:] . k[s,:] )
- *       "multi-head ReLU-gated dot product" that "scores all preceding tokens
- *       against the current query" (paper Sec. 2.1; score vector I_t in R^L of
- *       Sec. 3 Notation).  The explicit formula, one key vector per position
+ *       the indexer of Sec. 2.1: every indexer head takes the dot product of
+ *       the query with each earlier key, a ReLU gates it, the heads are summed
+ *       with per-head weights (score vector I_t in R^L of Sec. 3 Notation).  The explicit formula, one key vector per position
  *       shared by all indexer heads and w outside the ReLU, is the reading
  *       this build takes for the cited DSA indexer.
  *   - T_t = Top-k(I_t) (Sec. 3 Notation), ties broken towards the lower
  *       position, fewer than k visible keys => all of them, -1 padded.
- *   - sparse core attention over exactly the selected rows (Sec. 2.1: the main
- *       attention "is computed only over this sparse subset"), MQA/MLA form
+ *   - sparse core attention over exactly the selected rows (Sec. 2.1: the core
+ *       attention sees nothing but the selected subset), MQA/MLA form
  *       with one shared KV row per position.
  *   - dense causal attention (textbook) used only to pin the sparse one.
  * The Full/Shared layer loop of Fig. 2(b) lives in oracle.py on top of these.
