@@ -22,6 +22,7 @@
  *       attention sees nothing but the selected subset), MQA/MLA form
  *       with one shared KV row per position.
  *   - dense causal attention (textbook) used only to pin the sparse one.
+ *   - pairwise cross-layer overlap of the index sets (App. A).
  * The Full/Shared layer loop of Fig. 2(b) lives in oracle.py on top of these.
  *
  * Causality: key s is visible to query row i of a sequence iff
@@ -359,6 +360,47 @@ int ico_dense_causal_attn(const uint16_t *Q, const uint16_t *KV,
             free(z);
         }
     }
+    return 0;
+}
+
+/* ---- cross-layer top-k overlap (App. A) ---------------------------------
+ * For every ordered pair of layers (i, j): how many of layer j's selected
+ * positions layer i selected too, summed over the query rows, and the size of
+ * layer i's sets, summed likewise.  The appendix reports |T(i) ^ T(j)| / k
+ * averaged over rows that all hold k entries; with rows that hold fewer
+ * (positions < k) the ratio of the two sums below is this build's reading:
+ *   overlap(i, j) = sum_t |T_t(i) ^ T_t(j)| / sum_t |T_t(i)|.
+ * idx: n_layers tensors [nq, k_sel], entries < 0 or >= Lk are not members;
+ * the members of one row are distinct.  inter: [n_layers * n_layers],
+ * sizes: [n_layers].  Plain marking of layer i's row, then counting j's. */
+int ico_topk_overlap(const int32_t *const *idx, int n_layers, long nq, int k_sel, int Lk,
+                     uint64_t *inter, uint64_t *sizes)
+{
+    if (!idx || !inter || !sizes || n_layers <= 0 || nq < 0 || k_sel <= 0 || Lk <= 0) return 1;
+    unsigned char *mark = (unsigned char *)calloc((size_t)Lk, 1);
+    if (!mark) return 2;
+    memset(inter, 0, sizeof(uint64_t) * (size_t)n_layers * n_layers);
+    memset(sizes, 0, sizeof(uint64_t) * (size_t)n_layers);
+    for (long t = 0; t < nq; ++t) {
+        for (int i = 0; i < n_layers; ++i) {
+            const int32_t *ri = idx[i] + t * k_sel;
+            for (int m = 0; m < k_sel; ++m)
+                if (ri[m] >= 0 && ri[m] < Lk) {
+                    mark[ri[m]] = 1;
+                    sizes[i] += 1;
+                }
+            for (int j = 0; j < n_layers; ++j) {
+                const int32_t *rj = idx[j] + t * k_sel;
+                uint64_t c = 0;
+                for (int m = 0; m < k_sel; ++m)
+                    if (rj[m] >= 0 && rj[m] < Lk && mark[rj[m]]) c += 1;
+                inter[(size_t)i * n_layers + j] += c;
+            }
+            for (int m = 0; m < k_sel; ++m)
+                if (ri[m] >= 0 && ri[m] < Lk) mark[ri[m]] = 0;
+        }
+    }
+    free(mark);
     return 0;
 }
 

@@ -153,6 +153,25 @@ def dense_causal_attn(Q, KV, d_v, v_off, sm_scale, q_pos0):
     return O
 
 
+def topk_overlap(idx_layers, Lk):
+    """Cross-layer overlap of the index sets (App. A).  idx_layers: list of int32 arrays
+    [..., k_sel] of one shape.  Returns (overlap [n,n] float64 = inter / sizes[:,None],
+    inter [n,n] uint64, sizes [n] uint64); overlap(i,j) = sum_t |T_t(i) ^ T_t(j)| / sum_t |T_t(i)|."""
+    n = len(idx_layers)
+    arrs = [np.ascontiguousarray(a, dtype=np.int32) for a in idx_layers]
+    k_sel = arrs[0].shape[-1]
+    nq = arrs[0].size // k_sel
+    assert all(a.shape == arrs[0].shape for a in arrs)
+    ptrs = (C.c_void_p * n)(*[a.ctypes.data for a in arrs])
+    inter = np.zeros((n, n), dtype=np.uint64)
+    sizes = np.zeros((n,), dtype=np.uint64)
+    rc = lib().ico_topk_overlap(ptrs, C.c_int(n), C.c_long(nq), C.c_int(k_sel), C.c_int(Lk), _p(inter), _p(sizes))
+    assert rc == 0, rc
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ov = inter.astype(np.float64) / sizes.astype(np.float64)[:, None]
+    return ov, inter, sizes
+
+
 # ---- pattern strings and the layer loop (Fig. 2, Sec. 3 Overview) -------------
 
 def pattern_from_string(s):
