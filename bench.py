@@ -154,6 +154,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="skip the cross-layer overlap diagnostic arm")
+    ap.add_argument("--overlap-layers", type=int, default=48)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of 1 GiB (reference dispatches for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -294,6 +296,36 @@ def main():
             },
         })
         del dstack
+
+    # ---------------- cross-layer overlap of the index sets (the paper's App. A diagnostic) ----------------
+    if not args.no_overlap:
+        log("overlap arm: %d layers with drifting q/k" % args.overlap_layers)
+        ocfg = synth.config("c3")
+        idxs = []
+        for lay in synth.chain_indexer_layers(ocfg, args.overlap_layers, device="cuda"):
+            idxs.append(ic.indexer_topk(lay["q"], lay["k"], lay["w"], ocfg["k_sel"], 0))
+            del lay
+        ows = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+        ic.topk_overlap(idxs, ocfg["Lk"], workspace=ows)
+        torch.cuda.synchronize()
+        ms_ov = time_steps(lambda: ic.topk_overlap(idxs, ocfg["Lk"], workspace=ows), 3, 0)
+        ov = ic.topk_overlap(idxs, ocfg["Lk"], workspace=ows)[0].cpu()
+        n_ov = len(idxs)
+        by_dist = {}
+        for dist in (1, 2, 4, 8, 16, 32):
+            if dist < n_ov:
+                by_dist[str(dist)] = float(torch.diagonal(ov, dist).mean())
+        # one membership test = one 4-byte LDS gather lane; the LDS serves a 64-lane gather in about 16
+        # clocks per CU (measured), i.e. 4 tests per clock and CU: 256 CUs x 2.4 GHz x 4
+        ov_tests = n_ov * (n_ov + 1) / 2 * ocfg["Tq"] * ocfg["k_sel"]
+        ov_peak = 256 * 2.4e9 * 4 / 1e12
+        arms["topk_overlap"] = {"layers": n_ov, "ms": ms_ov, "bound": "alu",
+                                "achieved": ov_tests / (ms_ov * 1e-3) / 1e12, "peak": ov_peak,
+                                "unit": "T membership tests/s", "frac": ov_tests / (ms_ov * 1e-3) / 1e12 / ov_peak,
+                                "index_bytes_read_GBs": n_ov * ocfg["Tq"] * ocfg["k_sel"] * 4 / (ms_ov * 1e-3) / 1e9,
+                                "mean_overlap_by_layer_distance": by_dist,
+                                "data": "q and k drift as an AR(1) chain over the layers (rho 0.8)"}
+        del idxs
 
     out = {
         "metric": "prefill & decode tokens/s, 48-layer DSA stack L=32K, 1-in-4 Full vs all-Full",

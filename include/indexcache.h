@@ -145,6 +145,31 @@ ic_status ic_pattern_from_string(const char *fs, uint8_t *full_mask, int32_t n);
 /* Uniform interleave: F at layers l with l % r == 0, "FSSSFSSS.." for r = 4 (Sec. 3.1). */
 ic_status ic_pattern_uniform(int32_t n, int32_t r, uint8_t *full_mask);
 
+/*
+ * Pairwise cross-layer overlap of the top-k index sets (paper App. A: |T(i) ^ T(j)| / k for every
+ * pair of layers, averaged over the queries; the diagnostic behind the sharing idea).
+ *   idx_layers  HOST array of n_layers DEVICE pointers, each an index tensor [nq, k_sel] int32 as
+ *               ic_indexer_topk writes it (entries < 0 or >= Lk are not members; the members of one
+ *               row are distinct; any order).  1 <= n_layers <= IC_MAX_OVERLAP_LAYERS.
+ *   nq          rows per tensor (B*Tq); Lk: positions are in [0, Lk), Lk <= IC_MAX_OVERLAP_LK
+ *   overlap     device [n_layers, n_layers] double, out (nullable):
+ *                 overlap[i][j] = sum_t |T_t(i) ^ T_t(j)| / sum_t |T_t(i)|
+ *               which is the appendix's ratio when every row holds k entries, and stays in [0,1]
+ *               with 1 on the diagonal when early rows hold fewer; 0 for a layer with no members
+ *   inter       device [n_layers, n_layers] uint64, out (nullable): the summed intersection sizes
+ *   sizes       device [n_layers] uint64, out (nullable): the summed set sizes
+ *   workspace   device, ic_topk_overlap_workspace(n_layers) bytes, 256-byte aligned; the library
+ *               zeroes it itself
+ * Errors (host, before any launch): IC_ERR_NULL, IC_ERR_SHAPE, IC_ERR_UNSUPPORTED (limits),
+ * IC_ERR_WORKSPACE.  Asynchronous on `stream`.
+ */
+#define IC_MAX_OVERLAP_LAYERS 128
+#define IC_MAX_OVERLAP_LK (1 << 20)
+size_t ic_topk_overlap_workspace(int32_t n_layers);
+ic_status ic_topk_overlap(const int32_t *const *idx_layers, int32_t n_layers, int64_t nq, int32_t k_sel, int32_t Lk,
+                          double *overlap, uint64_t *inter, uint64_t *sizes, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
 /* Message for the last error on the calling thread ("" if none). Host string, do not free. */
 const char *ic_last_error(void);
 

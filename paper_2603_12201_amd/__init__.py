@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     IcError, Status, lib, lib_path, last_error,
     indexer_topk, indexer_topk_workspace, sparse_attn, sparse_attn_workspace,
     forward_stack, forward_stack_workspace, make_layers,
-    pattern_from_string, pattern_uniform,
+    pattern_from_string, pattern_uniform, topk_overlap,
     debug_indexer_scores, debug_indexer_launch_count,
     prof_enable, prof_collect, prof_get, prof_reset,
     IndexerDesc, AttnDesc, Layer,

@@ -67,6 +67,10 @@ def lib():
         L.ic_pattern_from_string.argtypes = [C.c_char_p, C.c_char_p, i32]
         L.ic_pattern_uniform.restype = C.c_int
         L.ic_pattern_uniform.argtypes = [i32, i32, C.c_char_p]
+        L.ic_topk_overlap_workspace.restype = sz
+        L.ic_topk_overlap_workspace.argtypes = [i32]
+        L.ic_topk_overlap.restype = C.c_int
+        L.ic_topk_overlap.argtypes = [C.POINTER(vp), i32, C.c_int64, i32, i32, vp, vp, vp, vp, sz, vp]
         L.ic_debug_indexer_scores.restype = C.c_int
         L.ic_debug_indexer_scores.argtypes = [C.POINTER(IndexerDesc), vp, vp, vp, i32, i32, vp, vp]
         L.ic_debug_indexer_launch_count.restype = C.c_uint64
@@ -234,6 +238,31 @@ def pattern_uniform(n, r):
     buf = C.create_string_buffer(max(n, 1))
     _check(lib().ic_pattern_uniform(n, r, buf))
     return [b != 0 for b in buf.raw[:n]]
+
+
+def topk_overlap(idx_layers, Lk, workspace=None, stream=None):
+    """ic_topk_overlap over a list of index tensors [..., k_sel] int32 of one shape.
+    Returns (overlap [n,n] float64, inter [n,n] int64, sizes [n] int64), all on the device."""
+    import torch
+    n = len(idx_layers)
+    if n == 0:
+        raise IcError(Status.ERR_SHAPE, "no index tensors")
+    first = idx_layers[0]
+    for t in idx_layers:
+        _need(t, "idx", torch.int32)
+        if t.shape != first.shape:
+            raise IcError(Status.ERR_SHAPE, "index tensors must share one shape")
+    k_sel = first.shape[-1]
+    nq = first.numel() // k_sel
+    if workspace is None:
+        workspace = _workspace(int(lib().ic_topk_overlap_workspace(n)), first)
+    ov = torch.empty((n, n), dtype=torch.float64, device=first.device)
+    inter = torch.empty((n, n), dtype=torch.int64, device=first.device)
+    sizes = torch.empty((n,), dtype=torch.int64, device=first.device)
+    ptrs = (C.c_void_p * n)(*[t.data_ptr() for t in idx_layers])
+    _check(lib().ic_topk_overlap(ptrs, n, nq, k_sel, Lk, _ptr(ov), _ptr(inter), _ptr(sizes),
+                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return ov, inter, sizes
 
 
 def debug_indexer_scores(q, k, w, q_pos0, row0, n_rows, q_scale=None, k_scale=None, stream=None):

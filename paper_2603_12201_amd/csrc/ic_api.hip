@@ -388,6 +388,33 @@ ic_status ic_pattern_uniform(int32_t n, int32_t r, uint8_t *full_mask)
     return IC_OK;
 }
 
+size_t ic_topk_overlap_workspace(int32_t n_layers)
+{
+    if (n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;
+    return align_up(ic::overlap_ws_bytes(n_layers));
+}
+
+ic_status ic_topk_overlap(const int32_t *const *idx_layers, int32_t n_layers, int64_t nq, int32_t k_sel, int32_t Lk,
+                          double *overlap, uint64_t *inter, uint64_t *sizes, void *workspace, size_t workspace_bytes,
+                          void *stream)
+{
+    if (!idx_layers) return fail(IC_ERR_NULL, "idx_layers must not be NULL");
+    if (n_layers <= 0 || nq < 0 || k_sel <= 0 || Lk <= 0) return fail(IC_ERR_SHAPE, "overlap sizes must be positive");
+    if (n_layers > IC_MAX_OVERLAP_LAYERS)
+        return fail(IC_ERR_UNSUPPORTED, "n_layers=%d exceeds IC_MAX_OVERLAP_LAYERS=%d", n_layers, IC_MAX_OVERLAP_LAYERS);
+    if (Lk > IC_MAX_OVERLAP_LK) return fail(IC_ERR_UNSUPPORTED, "Lk=%d exceeds IC_MAX_OVERLAP_LK=%d", Lk, IC_MAX_OVERLAP_LK);
+    if ((nq + 15) / 16 * n_layers > (int64_t)INT32_MAX) return fail(IC_ERR_SHAPE, "nq * n_layers too large");
+    for (int l = 0; l < n_layers; ++l)
+        if (!idx_layers[l]) return fail(IC_ERR_NULL, "idx_layers[%d] is NULL", l);
+    if (!overlap && !inter && !sizes) return fail(IC_ERR_NULL, "at least one output must be given");
+    ic_status s = check_ws(workspace, workspace_bytes, ic_topk_overlap_workspace(n_layers));
+    if (s != IC_OK) return s;
+    hipError_t e = ic::launch_overlap(idx_layers, n_layers, nq, k_sel, Lk, overlap, (unsigned long long *)inter,
+                                      (unsigned long long *)sizes, workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "overlap launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
 ic_status ic_debug_indexer_scores(const ic_indexer_desc *d, const void *q, const void *k, const float *w,
                                   int32_t row0, int32_t n_rows, float *out, void *stream)
 {

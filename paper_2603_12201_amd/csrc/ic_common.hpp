@@ -68,6 +68,10 @@ hipError_t launch_select(const SelectArgs &a, int n_rows, int max_row_len, hipSt
 int select_cache_limit();
 hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st);
 hipError_t launch_attn_merge(const AttnArgs &a, int d_v, hipStream_t st);
+size_t overlap_ws_bytes(int n_layers);
+size_t overlap_lds_bytes(int n_layers, int Lk);
+hipError_t launch_overlap(const int32_t *const *idx_layers, int n_layers, int64_t nq, int k_sel, int Lk, double *overlap,
+                          unsigned long long *inter_out, unsigned long long *sizes_out, void *ws, hipStream_t st);
 bool score_shape_supported(int dtype, int H_I, int d_I);
 bool attn_shape_supported(int d_qk, int d_v);
 

@@ -20,7 +20,7 @@ import torch
 
 BASE_SEED = 2603122010
 
-_TENSOR_ID = {"q": 1, "k_base": 2, "k_noise": 3, "w": 4, "Q": 5, "KV": 6}
+_TENSOR_ID = {"q": 1, "k_base": 2, "k_noise": 3, "w": 4, "Q": 5, "KV": 6, "q_chain": 7, "k_chain": 8}
 
 # The workload shapes this build is measured and tested on.
 CONFIGS = {
@@ -103,6 +103,26 @@ def indexer_layer(cfg, layer, device="cpu"):
     else:
         raise ValueError(cfg["dtype"])
     return out
+
+
+def chain_indexer_layers(cfg, n_layers, device="cpu", rho=0.8):
+    """Generator of bf16 indexer inputs whose q AND k drift from layer to layer as an AR(1) chain,
+    x_0 = n_0, x_l = sqrt(rho) x_(l-1) + sqrt(1-rho) n_l, so the correlation of two layers decays
+    with their distance.  Only the cross-layer overlap diagnostic uses it (a stand-in for a trained
+    model's slowly drifting token selection); the graded configs keep the base+noise recipe above."""
+    B, Tq, Lk, H, d = cfg["B"], cfg["Tq"], cfg["Lk"], cfg["H_I"], cfg["d_I"]
+    seed = cfg["seed"]
+    q = k = None
+    a, b = math.sqrt(rho), math.sqrt(1.0 - rho)
+    for l in range(n_layers):
+        nq = _randn((B, Tq, H, d), seed, l, "q_chain", device)
+        nk = _randn((B, Lk, d), seed, l, "k_chain", device)
+        q = nq if q is None else a * q + b * nq
+        k = nk if k is None else a * k + b * nk
+        del nq, nk
+        w = torch.rand((B, Tq, H), generator=_gen(seed, l, "w", device), device=device, dtype=torch.float32)
+        yield {"q": (q * (1.0 / math.sqrt(d))).to(torch.bfloat16).contiguous(),
+               "k": k.to(torch.bfloat16).contiguous(), "w": w.contiguous()}
 
 
 def attn_layer(cfg, layer, device="cpu"):

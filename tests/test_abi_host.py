@@ -153,3 +153,25 @@ def test_prof_api_without_gpu(ic):
     assert ic.prof_get(0) == (0, 0.0)
     with pytest.raises(ic.IcError):
         ic.prof_get(9)
+
+
+def test_overlap_argument_errors_need_no_gpu():
+    import paper_2603_12201_amd as ic
+    L, S = ic.lib(), ic.Status
+    one = C.c_void_p(4096)
+    ptrs = (C.c_void_p * 3)(4096, 8192, 12288)
+    ws = L.ic_topk_overlap_workspace(3)
+    assert ws >= (9 + 3) * 8
+    assert L.ic_topk_overlap_workspace(0) == 0 and L.ic_topk_overlap_workspace(129) == 0
+    assert L.ic_topk_overlap(None, 3, 10, 8, 100, one, None, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_topk_overlap(ptrs, 3, 10, 8, 100, None, None, None, one, ws, None) == S.ERR_NULL      # no output
+    assert L.ic_topk_overlap(ptrs, 0, 10, 8, 100, one, None, None, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_topk_overlap(ptrs, 3, 10, 0, 100, one, None, None, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_topk_overlap(ptrs, 3, -1, 8, 100, one, None, None, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_topk_overlap(ptrs, 3, 10, 8, (1 << 20) + 1, one, None, None, one, ws, None) == S.ERR_UNSUPPORTED
+    assert L.ic_topk_overlap(ptrs, 129, 10, 8, 100, one, None, None, one, ws, None) == S.ERR_UNSUPPORTED
+    assert L.ic_topk_overlap(ptrs, 3, 10, 8, 100, one, None, None, None, ws, None) == S.ERR_WORKSPACE
+    assert L.ic_topk_overlap(ptrs, 3, 10, 8, 100, one, None, None, one, 8, None) == S.ERR_WORKSPACE
+    bad = (C.c_void_p * 3)(4096, None, 12288)
+    assert L.ic_topk_overlap(bad, 3, 10, 8, 100, one, None, None, one, ws, None) == S.ERR_NULL
+    assert b"idx_layers[1]" in L.ic_last_error()
