@@ -23,6 +23,8 @@
  *       with one shared KV row per position.
  *   - dense causal attention (textbook) used only to pin the sparse one.
  *   - pairwise cross-layer overlap of the index sets (App. A).
+ *   - cosine similarity of two attention outputs (App. C); the exhaustive pattern search over
+ *     a similarity matrix that pins the dynamic program lives in oracle.py.
  * The Full/Shared layer loop of Fig. 2(b) lives in oracle.py on top of these.
  *
  * Causality: key s is visible to query row i of a sequence iff
@@ -401,6 +403,37 @@ int ico_topk_overlap(const int32_t *const *idx, int n_layers, long nq, int k_sel
         }
     }
     free(mark);
+    return 0;
+}
+
+/* ---- similarity of two attention outputs (App. C) -------------------------
+ * Cosine similarity of corresponding rows of two bf16 tensors [n_rows, row_len]
+ * (one row = one query token's output over all heads), and its mean over the
+ * rows: the appendix's "how well does layer j's index serve layer i" number is
+ * this mean between the output under the layer's own indices and the output
+ * under the reused ones.  Reading where the paper is silent: the cosine is
+ * taken per token and averaged; a pair of all-zero rows counts as 1, a zero
+ * row against a non-zero one as 0.  per_row may be NULL. */
+int ico_cosine_rows(const uint16_t *A, const uint16_t *B, long n_rows, long row_len, double *per_row, double *mean)
+{
+    if (!A || !B || !mean || n_rows <= 0 || row_len <= 0) return 1;
+    double acc = 0.0;
+    for (long r = 0; r < n_rows; ++r) {
+        double ab = 0.0, aa = 0.0, bb = 0.0;
+        for (long c = 0; c < row_len; ++c) {
+            const double x = widen_bf16(A[r * row_len + c]), y = widen_bf16(B[r * row_len + c]);
+            ab += x * y;
+            aa += x * x;
+            bb += y * y;
+        }
+        double cs;
+        if (aa == 0.0 && bb == 0.0) cs = 1.0;
+        else if (aa == 0.0 || bb == 0.0) cs = 0.0;
+        else cs = ab / (sqrt(aa) * sqrt(bb));
+        if (per_row) per_row[r] = cs;
+        acc += cs;
+    }
+    *mean = acc / (double)n_rows;
     return 0;
 }
 

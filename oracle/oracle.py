@@ -172,6 +172,50 @@ def topk_overlap(idx_layers, Lk):
     return ov, inter, sizes
 
 
+def cosine_rows(A, B):
+    """Mean over the rows of the cosine similarity of corresponding rows of two bf16 tensors
+    (uint16 bit patterns, same shape [..., row_len] flattened to [n_rows, row_len] by the caller).
+    Returns (mean, per_row float64)."""
+    assert A.dtype == np.uint16 and B.dtype == np.uint16 and A.shape == B.shape and A.ndim == 2
+    A = np.ascontiguousarray(A); B = np.ascontiguousarray(B)
+    per = np.empty((A.shape[0],), dtype=np.float64)
+    mean = C.c_double(0.0)
+    rc = lib().ico_cosine_rows(_p(A), _p(B), C.c_long(A.shape[0]), C.c_long(A.shape[1]), _p(per), C.byref(mean))
+    assert rc == 0, rc
+    return float(mean.value), per
+
+
+def pattern_total(S, mask):
+    """Objective of the similarity-based search (App. C): sum over the Shared layers l of
+    S[l, src(l)], src(l) the nearest preceding Full layer."""
+    tot = 0.0
+    for l in range(len(mask)):
+        if not mask[l]:
+            tot += float(S[l, source_layer(mask, l)])
+    return tot
+
+
+def pattern_search_exhaustive(S, n_full):
+    """argmax over every pattern with exactly n_full Full layers (the first one Full) of
+    pattern_total: the definition written out, for small N.  Returns (best total, list of all
+    patterns that reach it)."""
+    import itertools
+    N = S.shape[0]
+    assert 1 <= n_full <= N
+    best, arg = -np.inf, []
+    for rest in itertools.combinations(range(1, N), n_full - 1):
+        mask = [False] * N
+        mask[0] = True
+        for l in rest:
+            mask[l] = True
+        t = pattern_total(S, mask)
+        if t > best + 1e-12:
+            best, arg = t, [mask]
+        elif abs(t - best) <= 1e-12:
+            arg.append(mask)
+    return best, arg
+
+
 # ---- pattern strings and the layer loop (Fig. 2, Sec. 3 Overview) -------------
 
 def pattern_from_string(s):
