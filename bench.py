@@ -156,6 +156,7 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="skip the cross-layer overlap diagnostic arm")
     ap.add_argument("--overlap-layers", type=int, default=48)
+    ap.add_argument("--similarity-layers", type=int, default=8)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of 1 GiB (reference dispatches for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -165,6 +166,7 @@ def main():
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    import numpy as np
     import torch
     ic = ensure_built()
     import synth
@@ -325,6 +327,36 @@ def main():
                                 "index_bytes_read_GBs": n_ov * ocfg["Tq"] * ocfg["k_sel"] * 4 / (ms_ov * 1e-3) / 1e9,
                                 "mean_overlap_by_layer_distance": by_dist,
                                 "data": "q and k drift as an AR(1) chain over the layers (rho 0.8)"}
+        # similarity-based pattern search (App. C) on the first layers of the same stack: S[i][j] from the
+        # attention outputs under own vs reused indices, then the exact dynamic program
+        n_sim = min(args.similarity_layers, n_ov)
+        if n_sim >= 2:
+            log("similarity arm: %d layers" % n_sim)
+            at = [synth.attn_layer(ocfg, l, device="cuda") for l in range(min(n_sim, 2))]
+            at = [at[l % len(at)] for l in range(n_sim)]           # the big Q/KV inputs are cycled, the indices are not
+            o_own = torch.empty((ocfg["B"], ocfg["Tq"], ocfg["H_q"], ocfg["d_v"]), dtype=torch.bfloat16, device="cuda")
+            arr = ic.make_layers(at, ocfg["k_sel"], 0, ocfg["d_v"], ocfg["v_off"], synth.sm_scale(ocfg), [o_own] * n_sim)
+            t0 = time.perf_counter()
+            S = ic.similarity_matrix(arr, idxs[:n_sim])
+            torch.cuda.synchronize()
+            ms_sim = (time.perf_counter() - t0) * 1e3
+            o_b = torch.empty_like(o_own)
+            o_b.copy_(o_own)
+            a2, b2 = o_own.view(ocfg["Tq"], -1), o_b.view(ocfg["Tq"], -1)
+            ms_cos = time_steps(lambda: ic.cosine_rows(a2, b2), 5, 1)
+            cos_bytes = 2 * a2.numel() * 2
+            Sh = S.cpu().numpy()
+            t0 = time.perf_counter()
+            mask, total = ic.pattern_search_dp(Sh, max(1, n_sim // 4))
+            ms_dp = (time.perf_counter() - t0) * 1e3
+            arms["similarity_search"] = {
+                "layers": n_sim, "matrix_ms": ms_sim, "attention_launches": n_sim * (n_sim + 1) // 2,
+                "cosine_kernel": {"ms": ms_cos, "bound": "hbm", "achieved": cos_bytes / (ms_cos * 1e-3) / 1e9,
+                                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": cos_bytes / (ms_cos * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                "mean_similarity_by_layer_distance": {str(d): float(np.mean([Sh[i, i - d] for i in range(d, n_sim)]))
+                                                      for d in (1, 2, 4) if d < n_sim},
+                "dp_pattern": "".join("F" if m else "S" for m in mask), "dp_total": total, "dp_host_ms": ms_dp}
+            del at, o_own, o_b
         del idxs
 
     out = {

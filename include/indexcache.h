@@ -163,6 +163,37 @@ ic_status ic_pattern_uniform(int32_t n, int32_t r, uint8_t *full_mask);
  * Errors (host, before any launch): IC_ERR_NULL, IC_ERR_SHAPE, IC_ERR_UNSUPPORTED (limits),
  * IC_ERR_WORKSPACE.  Asynchronous on `stream`.
  */
+/*
+ * Similarity-based pattern search (paper App. C).
+ *
+ * ic_cosine_rows: mean over the rows of the cosine similarity of corresponding rows of two bf16
+ * device tensors [n_rows, row_len] (a row = one query token's attention output over all heads).
+ * Reading where the paper is silent: the cosine is taken per token and averaged; two all-zero rows
+ * count as 1, a zero row against a non-zero one as 0.  mean: device double, out; per_row: device
+ * [n_rows] float, out, nullable; workspace: ic_cosine_rows_workspace() bytes, 256-byte aligned.
+ *
+ * ic_similarity_matrix: S[i][j], j < i = that similarity between layer i's sparse attention under
+ * its OWN index tensor (written to layers[i].O) and under layer j's index tensor (as if layer i
+ * were a Shared layer reading layer j); S[i][i] = 1, S[i][j] = 0 for j > i.  layers: the
+ * attention part (at, Q, KV, O) of n_layers layers of one shape; idx_layers: HOST array of
+ * n_layers DEVICE index tensors [B,Tq,k_sel]; S: device [n_layers, n_layers] double, out;
+ * workspace: ic_similarity_matrix_workspace(layers, n_layers) bytes.  n_layers (n_layers-1) / 2 + n_layers
+ * attention launches on `stream`.
+ *
+ * ic_pattern_search_dp (host only): the pattern with exactly n_full Full layers (the first layer
+ * Full) that maximises the sum over the Shared layers l of S[l][src(l)], src(l) the nearest
+ * preceding Full layer -- exact dynamic program over (last Full layer, number of Full layers so
+ * far).  S: HOST [n_layers, n_layers] double, only j < i is read; full_mask: out; total: out,
+ * nullable.  Among equal optima the pattern found is unspecified.
+ */
+size_t ic_cosine_rows_workspace(void);
+ic_status ic_cosine_rows(const void *A, const void *B, int64_t n_rows, int64_t row_len, double *mean, float *per_row,
+                         void *workspace, size_t workspace_bytes, void *stream);
+size_t ic_similarity_matrix_workspace(const ic_layer *layers, int32_t n_layers);
+ic_status ic_similarity_matrix(const ic_layer *layers, int32_t n_layers, const int32_t *const *idx_layers, double *S,
+                               void *workspace, size_t workspace_bytes, void *stream);
+ic_status ic_pattern_search_dp(const double *S, int32_t n_layers, int32_t n_full, uint8_t *full_mask, double *total);
+
 #define IC_MAX_OVERLAP_LAYERS 128
 #define IC_MAX_OVERLAP_LK (1 << 20)
 size_t ic_topk_overlap_workspace(int32_t n_layers);

@@ -185,6 +185,25 @@ def cosine_rows(A, B):
     return float(mean.value), per
 
 
+def similarity_matrix(layers, idx_layers, d_v, v_off, sm_scale):
+    """S[i, j], j < i: mean per-token cosine similarity between layer i's sparse attention under its
+    own indices and under layer j's (App. C), from the fp64 attention outputs; diagonal 1, upper 0."""
+    n = len(layers)
+    S = np.eye(n)
+    for i in range(n):
+        own, _ = sparse_attn(layers[i]["Q"], layers[i]["KV"], idx_layers[i], d_v, v_off, sm_scale)
+        a = own.reshape(-1, own.shape[-2] * own.shape[-1])
+        for j in range(i):
+            reuse, _ = sparse_attn(layers[i]["Q"], layers[i]["KV"], idx_layers[j], d_v, v_off, sm_scale)
+            b = reuse.reshape(a.shape)
+            na, nb = np.linalg.norm(a, axis=1), np.linalg.norm(b, axis=1)
+            with np.errstate(divide="ignore", invalid="ignore"):
+                cs = (a * b).sum(1) / (na * nb)
+            cs = np.where((na == 0) & (nb == 0), 1.0, np.where((na == 0) | (nb == 0), 0.0, cs))
+            S[i, j] = cs.mean()
+    return S
+
+
 def pattern_total(S, mask):
     """Objective of the similarity-based search (App. C): sum over the Shared layers l of
     S[l, src(l)], src(l) the nearest preceding Full layer."""

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     indexer_topk, indexer_topk_workspace, sparse_attn, sparse_attn_workspace,
     forward_stack, forward_stack_workspace, make_layers,
     pattern_from_string, pattern_uniform, topk_overlap,
+    cosine_rows, similarity_matrix, pattern_search_dp,
     debug_indexer_scores, debug_indexer_launch_count,
     prof_enable, prof_collect, prof_get, prof_reset,
     IndexerDesc, AttnDesc, Layer,

@@ -67,6 +67,15 @@ def lib():
         L.ic_pattern_from_string.argtypes = [C.c_char_p, C.c_char_p, i32]
         L.ic_pattern_uniform.restype = C.c_int
         L.ic_pattern_uniform.argtypes = [i32, i32, C.c_char_p]
+        L.ic_cosine_rows_workspace.restype = sz
+        L.ic_cosine_rows.restype = C.c_int
+        L.ic_cosine_rows.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, vp, sz, vp]
+        L.ic_similarity_matrix_workspace.restype = sz
+        L.ic_similarity_matrix_workspace.argtypes = [C.POINTER(Layer), i32]
+        L.ic_similarity_matrix.restype = C.c_int
+        L.ic_similarity_matrix.argtypes = [C.POINTER(Layer), i32, C.POINTER(vp), vp, vp, sz, vp]
+        L.ic_pattern_search_dp.restype = C.c_int
+        L.ic_pattern_search_dp.argtypes = [C.POINTER(C.c_double), i32, i32, C.c_char_p, C.POINTER(C.c_double)]
         L.ic_topk_overlap_workspace.restype = sz
         L.ic_topk_overlap_workspace.argtypes = [i32]
         L.ic_topk_overlap.restype = C.c_int
@@ -263,6 +272,51 @@ def topk_overlap(idx_layers, Lk, workspace=None, stream=None):
     _check(lib().ic_topk_overlap(ptrs, n, nq, k_sel, Lk, _ptr(ov), _ptr(inter), _ptr(sizes),
                                  _ptr(workspace), workspace.numel(), _stream(stream)))
     return ov, inter, sizes
+
+
+def cosine_rows(A, B, want_rows=False, stream=None):
+    """ic_cosine_rows: mean per-row cosine similarity of two bf16 tensors shaped [n_rows, row_len].
+    Returns a 0-d float64 device tensor (and the per-row float32 values if want_rows)."""
+    import torch
+    _need(A, "A", torch.bfloat16, 2)
+    _need(B, "B", torch.bfloat16, 2)
+    if A.shape != B.shape:
+        raise IcError(Status.ERR_SHAPE, "A %s and B %s differ in shape" % (tuple(A.shape), tuple(B.shape)))
+    mean = torch.empty((), dtype=torch.float64, device=A.device)
+    rows = torch.empty((A.shape[0],), dtype=torch.float32, device=A.device) if want_rows else None
+    ws = _workspace(int(lib().ic_cosine_rows_workspace()), A)
+    _check(lib().ic_cosine_rows(_ptr(A), _ptr(B), A.shape[0], A.shape[1], _ptr(mean), _ptr(rows),
+                                _ptr(ws), ws.numel(), _stream(stream)))
+    return (mean, rows) if want_rows else mean
+
+
+def similarity_matrix(layer_arr, idx_layers, workspace=None, stream=None):
+    """ic_similarity_matrix over a host array built by make_layers (attention part) and one index
+    tensor per layer.  Returns S [n,n] float64 on the device (lower triangle; diagonal 1)."""
+    import torch
+    n = len(layer_arr)
+    if len(idx_layers) != n:
+        raise IcError(Status.ERR_SHAPE, "%d index tensors for %d layers" % (len(idx_layers), n))
+    for t in idx_layers:
+        _need(t, "idx", torch.int32, 3)
+    if workspace is None:
+        workspace = _workspace(int(lib().ic_similarity_matrix_workspace(layer_arr, n)), idx_layers[0])
+    S = torch.empty((n, n), dtype=torch.float64, device=idx_layers[0].device)
+    ptrs = (C.c_void_p * n)(*[t.data_ptr() for t in idx_layers])
+    _check(lib().ic_similarity_matrix(layer_arr, n, ptrs, _ptr(S), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return S
+
+
+def pattern_search_dp(S, n_full):
+    """ic_pattern_search_dp (host): S is an [n,n] array-like of floats (lower triangle used).
+    Returns (list of bools, True = Full; total similarity)."""
+    rows = [list(map(float, r)) for r in S]
+    n = len(rows)
+    flat = (C.c_double * (n * n))(*[rows[i][j] for i in range(n) for j in range(n)])
+    buf = C.create_string_buffer(max(n, 1))
+    total = C.c_double(0.0)
+    _check(lib().ic_pattern_search_dp(flat, n, n_full, buf, C.byref(total)))
+    return [b != 0 for b in buf.raw[:n]], float(total.value)
 
 
 def debug_indexer_scores(q, k, w, q_pos0, row0, n_rows, q_scale=None, k_scale=None, stream=None):

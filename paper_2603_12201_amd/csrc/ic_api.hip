@@ -388,6 +388,134 @@ ic_status ic_pattern_uniform(int32_t n, int32_t r, uint8_t *full_mask)
     return IC_OK;
 }
 
+size_t ic_cosine_rows_workspace(void) { return kAlign; }
+
+ic_status ic_cosine_rows(const void *A, const void *B, int64_t n_rows, int64_t row_len, double *mean, float *per_row,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!A || !B || !mean) return fail(IC_ERR_NULL, "A, B and mean must not be NULL");
+    if (n_rows <= 0 || row_len <= 0 || n_rows > INT32_MAX) return fail(IC_ERR_SHAPE, "n_rows and row_len must be positive");
+    ic_status s = check_ws(workspace, workspace_bytes, ic_cosine_rows_workspace());
+    if (s != IC_OK) return s;
+    hipError_t e = ic::launch_cosine(A, B, n_rows, row_len, mean, per_row, (double *)workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "cosine launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
+namespace {
+
+// layers of the similarity matrix share one attention shape (any layer's index tensor fits any layer)
+ic_status check_sim_layers(const ic_layer *layers, int32_t n_layers)
+{
+    if (!layers) return fail(IC_ERR_NULL, "layers is NULL");
+    if (n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS)
+        return fail(IC_ERR_SHAPE, "n_layers must be in [1, %d]", IC_MAX_OVERLAP_LAYERS);
+    for (int l = 0; l < n_layers; ++l) {
+        ic_status s = check_attn(&layers[l].at);
+        if (s != IC_OK) return s;
+        if (!layers[l].Q || !layers[l].KV || !layers[l].O) return fail(IC_ERR_NULL, "layer %d: Q, KV and O must not be NULL", l);
+        const ic_attn_desc &a = layers[l].at, &b = layers[0].at;
+        if (a.B != b.B || a.Tq != b.Tq || a.k_sel != b.k_sel || a.H_q != b.H_q || a.d_v != b.d_v)
+            return fail(IC_ERR_SHAPE, "layer %d: attention shape differs from layer 0", l);
+    }
+    return IC_OK;
+}
+
+size_t sim_o_bytes(const ic_attn_desc *a) { return align_up((size_t)a->B * a->Tq * a->H_q * a->d_v * 2); }
+
+} // namespace
+
+size_t ic_similarity_matrix_workspace(const ic_layer *layers, int32_t n_layers)
+{
+    if (!layers || n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;
+    size_t at = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const size_t a = attn_ws_bytes(&layers[l].at);
+        if (a > at) at = a;
+    }
+    return sim_o_bytes(&layers[0].at) + align_up(at) + kAlign;
+}
+
+ic_status ic_similarity_matrix(const ic_layer *layers, int32_t n_layers, const int32_t *const *idx_layers, double *S,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    ic_status s = check_sim_layers(layers, n_layers);
+    if (s != IC_OK) return s;
+    if (!idx_layers || !S) return fail(IC_ERR_NULL, "idx_layers and S must not be NULL");
+    for (int l = 0; l < n_layers; ++l)
+        if (!idx_layers[l]) return fail(IC_ERR_NULL, "idx_layers[%d] is NULL", l);
+    s = check_ws(workspace, workspace_bytes, ic_similarity_matrix_workspace(layers, n_layers));
+    if (s != IC_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    void *o_reuse = ws;
+    void *attn_ws = ws + sim_o_bytes(&layers[0].at);
+    double *acc = (double *)(ws + ic_similarity_matrix_workspace(layers, n_layers) - kAlign);
+    hipError_t e = ic::launch_sim_init(S, n_layers, st);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "similarity init failed: %s", hipGetErrorString(e));
+    const ic_attn_desc *a0 = &layers[0].at;
+    const int64_t n_rows = (int64_t)a0->B * a0->Tq, row_len = (int64_t)a0->H_q * a0->d_v;
+    for (int i = 0; i < n_layers; ++i) {
+        const ic_layer *L = &layers[i];
+        s = run_attn(&L->at, L->Q, L->KV, idx_layers[i], L->O, nullptr, attn_ws, st);       // own indices
+        if (s != IC_OK) return s;
+        for (int j = 0; j < i; ++j) {
+            s = run_attn(&L->at, L->Q, L->KV, idx_layers[j], o_reuse, nullptr, attn_ws, st); // as a Shared layer reading j
+            if (s != IC_OK) return s;
+            e = ic::launch_cosine(L->O, o_reuse, n_rows, row_len, S + (size_t)i * n_layers + j, nullptr, acc, st);
+            if (e != hipSuccess) return fail(IC_ERR_HIP, "cosine launch failed: %s", hipGetErrorString(e));
+        }
+    }
+    return IC_OK;
+}
+
+ic_status ic_pattern_search_dp(const double *S, int32_t n_layers, int32_t n_full, uint8_t *full_mask, double *total)
+{
+    if (!S || !full_mask) return fail(IC_ERR_NULL, "S and full_mask must not be NULL");
+    if (n_layers <= 0 || n_full <= 0 || n_full > n_layers)
+        return fail(IC_ERR_SHAPE, "need 1 <= n_full <= n_layers (n_full=%d n_layers=%d)", n_full, n_layers);
+    const int N = n_layers, M = n_full;
+    // run[j][i] = sum of S[m][j] over j < m < i: what the Shared layers between Full layers j and i collect
+    std::vector<double> run((size_t)N * (N + 1), 0.0);
+    for (int j = 0; j < N; ++j)
+        for (int i = j + 1; i <= N; ++i)
+            run[(size_t)j * (N + 1) + i] = (i == j + 1) ? 0.0 : run[(size_t)j * (N + 1) + i - 1] + S[(size_t)(i - 1) * N + j];
+    const double NEG = -1e300;
+    std::vector<double> dp((size_t)N * (M + 1), NEG);       // dp[i][c]: layer i Full, c Full layers in 0..i
+    std::vector<int> from((size_t)N * (M + 1), -1);
+    dp[(size_t)0 * (M + 1) + 1] = 0.0;                         // the first layer is always Full
+    for (int i = 1; i < N; ++i)
+        for (int c = 2; c <= M && c <= i + 1; ++c)
+            for (int j = c - 2; j < i; ++j) {
+                const double prev = dp[(size_t)j * (M + 1) + c - 1];
+                if (prev <= NEG) continue;
+                const double v = prev + run[(size_t)j * (N + 1) + i];
+                if (v > dp[(size_t)i * (M + 1) + c]) {
+                    dp[(size_t)i * (M + 1) + c] = v;
+                    from[(size_t)i * (M + 1) + c] = j;
+                }
+            }
+    double best = NEG;
+    int last = -1;
+    for (int i = M - 1; i < N; ++i) {                          // the last Full layer; everything after it reads it
+        const double prev = dp[(size_t)i * (M + 1) + M];
+        if (prev <= NEG) continue;
+        const double v = prev + run[(size_t)i * (N + 1) + N];
+        if (v > best) {
+            best = v;
+            last = i;
+        }
+    }
+    if (last < 0) return fail(IC_ERR_SHAPE, "no pattern with %d Full layers", M);
+    for (int l = 0; l < N; ++l) full_mask[l] = 0;
+    for (int i = last, c = M; i >= 0 && c >= 1; --c) {
+        full_mask[i] = 1;
+        i = from[(size_t)i * (M + 1) + c];
+    }
+    if (total) *total = best;
+    return IC_OK;
+}
+
 size_t ic_topk_overlap_workspace(int32_t n_layers)
 {
     if (n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;

@@ -72,6 +72,9 @@ size_t overlap_ws_bytes(int n_layers);
 size_t overlap_lds_bytes(int n_layers, int Lk);
 hipError_t launch_overlap(const int32_t *const *idx_layers, int n_layers, int64_t nq, int k_sel, int Lk, double *overlap,
                           unsigned long long *inter_out, unsigned long long *sizes_out, void *ws, hipStream_t st);
+hipError_t launch_cosine(const void *A, const void *B, int64_t n_rows, int64_t row_len, double *mean, float *per_row,
+                         double *acc, hipStream_t st);
+hipError_t launch_sim_init(double *S, int n, hipStream_t st);
 bool score_shape_supported(int dtype, int H_I, int d_I);
 bool attn_shape_supported(int d_qk, int d_v);
 

@@ -175,3 +175,48 @@ def test_overlap_argument_errors_need_no_gpu():
     bad = (C.c_void_p * 3)(4096, None, 12288)
     assert L.ic_topk_overlap(bad, 3, 10, 8, 100, one, None, None, one, ws, None) == S.ERR_NULL
     assert b"idx_layers[1]" in L.ic_last_error()
+
+
+def test_pattern_search_dp_matches_exhaustive_search(oracle):
+    """Host-only: the dynamic program against the definition (every pattern enumerated)."""
+    import numpy as np
+    import paper_2603_12201_amd as ic
+    rng = np.random.default_rng(8)
+    for n in (1, 2, 5, 9, 12):
+        S = np.tril(rng.random((n, n)), -1)
+        for m in sorted({1, 2, (n + 1) // 2, n}):
+            if m > n:
+                continue
+            mask, total = ic.pattern_search_dp(S, m)
+            best, arg = oracle.pattern_search_exhaustive(S, m)
+            assert mask[0] and sum(mask) == m
+            assert abs(total - best) <= 1e-12 and abs(oracle.pattern_total(S, mask) - best) <= 1e-12
+            if len(arg) == 1:
+                assert mask == arg[0]
+    # block-structured similarities: the optimum puts the Full layers on the block heads
+    blocks = [0, 0, 0, 3, 3, 5, 5, 5, 5, 9]
+    S = np.array([[1.0 if blocks[l] == blocks[j] else 0.2 for j in range(10)] for l in range(10)])
+    mask, total = ic.pattern_search_dp(S, 4)
+    assert [l for l in range(10) if mask[l]] == [0, 3, 5, 9] and abs(total - 6.0) < 1e-12
+    # paper-sized problem (47 layers, a quarter kept) runs at once and is at least as good as uniform
+    S = np.tril(rng.random((47, 47)), -1)
+    mask, total = ic.pattern_search_dp(S, 12)
+    assert mask[0] and sum(mask) == 12
+    uni = ic.pattern_uniform(47, 4)
+    assert sum(uni) == 12 and total >= oracle.pattern_total(S, uni) - 1e-12
+
+
+def test_similarity_argument_errors_need_no_gpu():
+    import paper_2603_12201_amd as ic
+    L, S = ic.lib(), ic.Status
+    one = C.c_void_p(4096)
+    assert L.ic_cosine_rows(None, one, 4, 8, one, None, one, 256, None) == S.ERR_NULL
+    assert L.ic_cosine_rows(one, one, 0, 8, one, None, one, 256, None) == S.ERR_SHAPE
+    assert L.ic_cosine_rows(one, one, 4, 8, one, None, None, 256, None) == S.ERR_WORKSPACE
+    assert L.ic_cosine_rows(one, one, 4, 8, one, None, one, 8, None) == S.ERR_WORKSPACE
+    flat = (C.c_double * 4)(0, 0, 0.5, 0)
+    buf = C.create_string_buffer(2)
+    assert L.ic_pattern_search_dp(flat, 2, 3, buf, None) == S.ERR_SHAPE
+    assert L.ic_pattern_search_dp(flat, 2, 0, buf, None) == S.ERR_SHAPE
+    assert L.ic_pattern_search_dp(None, 2, 1, buf, None) == S.ERR_NULL
+    assert L.ic_pattern_search_dp(flat, 2, 1, buf, None) == S.OK and buf.raw[:2] == bytes([1, 0])
