@@ -297,7 +297,24 @@ def main():
                                            "frac": dalg["attn_bytes"] / (d_att * 1e-3) / 1e9 / HBM_PEAK_GBS},
             },
         })
-        del dstack
+        # the same caches read through a page table (64-position pages in random physical order),
+        # first with every sequence at full length, then with a seeded mix of lengths in [Lk/2, Lk]
+        log("paged decode arm")
+        g = torch.Generator().manual_seed(2603)
+        page, Lk_d = 64, dcfg["Lk"]
+        pt = torch.randperm(dcfg["B"] * Lk_d // page, generator=g).to(torch.int32).reshape(dcfg["B"], Lk_d // page).cuda()
+        arr_p = ic.make_layers(dstack.layers, dcfg["k_sel"], 0, dcfg["d_v"], dcfg["v_off"], synth.sm_scale(dcfg),
+                               [dstack.O] * dcfg["n_layers"], Lk=Lk_d)
+        paged = {"page_size": page}
+        for name, lens in (("full_length", torch.full((dcfg["B"],), Lk_d, dtype=torch.int32)),
+                           ("ragged", torch.randint(Lk_d // 2, Lk_d + 1, (dcfg["B"],), generator=g).to(torch.int32))):
+            pc = ic.paged_cache(lens.cuda(), pt, page)
+            ms14 = time_steps(lambda: ic.forward_stack_paged(arr_p, m_fsss, pc, dstack.idx_cache, dstack.ws), args.decode_steps, 3)
+            msall = time_steps(lambda: ic.forward_stack_paged(arr_p, m_ffff, pc, dstack.idx_cache, dstack.ws), args.decode_steps, 3)
+            paged[name] = {"mean_len": float(lens.float().mean()), "ms_per_step_1in4": ms14, "ms_per_step_all_full": msall,
+                           "tokens_per_s_1in4": dcfg["B"] / (ms14 * 1e-3), "speedup_1in4_vs_all_full": msall / ms14}
+        arms["decode_paged"] = paged
+        del dstack, arr_p
 
     # ---------------- cross-layer overlap of the index sets (the paper's App. A diagnostic) ----------------
     if not args.no_overlap:

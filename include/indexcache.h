@@ -140,6 +140,41 @@ size_t ic_forward_stack_workspace(const ic_layer *layers, int32_t n_layers);
 ic_status ic_forward_stack(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask,
                            int32_t *idx_cache, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Decode against a full, paged KV cache with sequences of different lengths (the paper's third
+ * serving measurement, Sec. 4.3: decode throughput with the KV cache filled).
+ *
+ * ic_paged_cache describes how every cache of the call (index keys and KV rows) is laid out:
+ *   seq_lens    device [B] int32, nullable: the visible length Lk_b <= Lk of sequence b.  The Tq
+ *               query rows of a sequence are then its LAST Tq positions (Tq = 1 in decode: the new
+ *               token, whose own row is already in the cache), and q_pos0 of the descriptor is
+ *               ignored.  NULL: every sequence has Lk positions and q_pos0 applies.
+ *   page_table  device [B, max_pages] int32, nullable: physical page of logical page p of sequence
+ *               b; logical position s lives in row page_table[b][s / page_size] * page_size +
+ *               s % page_size of the POOL passed in place of k / KV ([n_pages * page_size, d_I] or
+ *               [.., row_elems]).  NULL: dense [B, Lk, ..] layout.  Entries beyond a sequence's
+ *               length are never read.
+ *   page_size   positions per page, a power of two >= 64;  max_pages * page_size >= Lk
+ * Lk in the descriptors is the bound on the lengths (it sizes launches and the workspace, which is
+ * what the un-paged workspace queries return).  Index tensors hold LOGICAL positions.  A paged
+ * index-key cache must be bf16.  One ic_paged_cache serves all layers of ic_forward_stack_paged
+ * (each layer brings its own pools in layers[l].k and layers[l].KV).
+ */
+typedef struct {
+    int32_t page_size;
+    int32_t max_pages;
+    const int32_t *page_table;
+    const int32_t *seq_lens;
+} ic_paged_cache;
+
+ic_status ic_indexer_topk_paged(const ic_indexer_desc *d, const ic_paged_cache *pc, const void *q, const void *k_pool,
+                                const float *w, int32_t *idx, float *sel_scores, void *workspace, size_t workspace_bytes,
+                                void *stream);
+ic_status ic_sparse_attn_paged(const ic_attn_desc *d, const ic_paged_cache *pc, const void *Q, const void *KV_pool,
+                               const int32_t *idx, void *O, float *lse, void *workspace, size_t workspace_bytes, void *stream);
+ic_status ic_forward_stack_paged(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const ic_paged_cache *pc,
+                                 int32_t *idx_cache, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host-only helpers for the pattern string c = c_1..c_N in {F,S}^N (Sec. 3 Overview). */
 ic_status ic_pattern_from_string(const char *fs, uint8_t *full_mask, int32_t n);
 /* Uniform interleave: F at layers l with l % r == 0, "FSSSFSSS.." for r = 4 (Sec. 3.1). */

@@ -31,6 +31,10 @@ class AttnDesc(C.Structure):
                 ("row_elems", C.c_int32), ("k_sel", C.c_int32), ("sm_scale", C.c_float)]
 
 
+class PagedCache(C.Structure):
+    _fields_ = [("page_size", C.c_int32), ("max_pages", C.c_int32), ("page_table", C.c_void_p), ("seq_lens", C.c_void_p)]
+
+
 class Layer(C.Structure):
     _fields_ = [("ix", IndexerDesc), ("q", C.c_void_p), ("k", C.c_void_p), ("w", C.c_void_p),
                 ("at", AttnDesc), ("Q", C.c_void_p), ("KV", C.c_void_p), ("O", C.c_void_p)]
@@ -67,6 +71,12 @@ def lib():
         L.ic_pattern_from_string.argtypes = [C.c_char_p, C.c_char_p, i32]
         L.ic_pattern_uniform.restype = C.c_int
         L.ic_pattern_uniform.argtypes = [i32, i32, C.c_char_p]
+        L.ic_indexer_topk_paged.restype = C.c_int
+        L.ic_indexer_topk_paged.argtypes = [C.POINTER(IndexerDesc), C.POINTER(PagedCache), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ic_sparse_attn_paged.restype = C.c_int
+        L.ic_sparse_attn_paged.argtypes = [C.POINTER(AttnDesc), C.POINTER(PagedCache), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ic_forward_stack_paged.restype = C.c_int
+        L.ic_forward_stack_paged.argtypes = [C.POINTER(Layer), i32, C.c_char_p, C.POINTER(PagedCache), vp, vp, sz, vp]
         L.ic_cosine_rows_workspace.restype = sz
         L.ic_cosine_rows.restype = C.c_int
         L.ic_cosine_rows.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp, vp, sz, vp]
@@ -206,18 +216,82 @@ def sparse_attn(Q, KV, idx, d_v, v_off, sm_scale, want_lse=False, workspace=None
     return (O, lse) if want_lse else O
 
 
-def make_layers(layers, k_sel, q_pos0, d_v, v_off, sm_scale, outs):
+def paged_cache(seq_lens=None, page_table=None, page_size=0):
+    """ic_paged_cache from device tensors: seq_lens [B] int32 and/or page_table [B, max_pages] int32.
+    The returned struct keeps the tensors alive."""
+    import torch
+    if seq_lens is not None:
+        _need(seq_lens, "seq_lens", torch.int32, 1)
+    if page_table is not None:
+        _need(page_table, "page_table", torch.int32, 2)
+    pc = PagedCache(page_size, page_table.shape[1] if page_table is not None else 0,
+                    page_table.data_ptr() if page_table is not None else None,
+                    seq_lens.data_ptr() if seq_lens is not None else None)
+    pc._keep = (seq_lens, page_table)
+    return pc
+
+
+def indexer_topk_paged(q, k_pool, w, k_sel, Lk, pc, want_scores=False, workspace=None, stream=None):
+    """ic_indexer_topk_paged: q [B,Tq,H_I,d_I], k_pool [rows, d_I] (paged) or [B,Lk,d_I] (ragged only),
+    Lk = bound on the sequence lengths.  Returns idx of LOGICAL positions (and the selected scores)."""
+    import torch
+    _need(q, "q", ndim=4)
+    _need(w, "w", torch.float32, 3)
+    B, Tq, H, d = q.shape
+    desc = IndexerDesc(B, Tq, Lk, H, d, k_sel, 0, _dtype_code(q), 0, None, None)
+    if workspace is None:
+        workspace = _workspace(indexer_topk_workspace(desc), q)
+    idx = torch.empty((B, Tq, k_sel), dtype=torch.int32, device=q.device)
+    sel = torch.empty((B, Tq, k_sel), dtype=torch.float32, device=q.device) if want_scores else None
+    _check(lib().ic_indexer_topk_paged(C.byref(desc), C.byref(pc), _ptr(q), _ptr(k_pool), _ptr(w), _ptr(idx), _ptr(sel),
+                                       _ptr(workspace), workspace.numel(), _stream(stream)))
+    return (idx, sel) if want_scores else idx
+
+
+def sparse_attn_paged(Q, KV_pool, idx, Lk, d_v, v_off, sm_scale, pc, want_lse=False, workspace=None, stream=None):
+    """ic_sparse_attn_paged: Q [B,Tq,H_q,d_qk], KV_pool [rows, row_elems] (paged) or [B,Lk,row_elems]."""
+    import torch
+    _need(Q, "Q", torch.bfloat16, 4)
+    _need(KV_pool, "KV_pool", torch.bfloat16)
+    _need(idx, "idx", torch.int32, 3)
+    B, Tq, Hq, d_qk = Q.shape
+    d = AttnDesc(B, Tq, Lk, Hq, d_qk, d_v, v_off, KV_pool.shape[-1], idx.shape[2], sm_scale)
+    if workspace is None:
+        workspace = _workspace(sparse_attn_workspace(d), Q)
+    O = torch.empty((B, Tq, Hq, d_v), dtype=torch.bfloat16, device=Q.device)
+    lse = torch.empty((B, Tq, Hq), dtype=torch.float32, device=Q.device) if want_lse else None
+    _check(lib().ic_sparse_attn_paged(C.byref(d), C.byref(pc), _ptr(Q), _ptr(KV_pool), _ptr(idx), _ptr(O), _ptr(lse),
+                                      _ptr(workspace), workspace.numel(), _stream(stream)))
+    return (O, lse) if want_lse else O
+
+
+def forward_stack_paged(layer_arr, full_mask, pc, idx_cache, workspace, stream=None):
+    """ic_forward_stack_paged: as forward_stack, every layer's k / KV being a pool laid out by pc.
+    Build layer_arr with make_layers(..., Lk=bound)."""
+    mask = bytes(bytearray(int(bool(m)) for m in full_mask))
+    if len(mask) != len(layer_arr):
+        raise IcError(Status.ERR_SHAPE, "full_mask has %d entries for %d layers" % (len(mask), len(layer_arr)))
+    _check(lib().ic_forward_stack_paged(layer_arr, len(layer_arr), mask, C.byref(pc), _ptr(idx_cache),
+                                        _ptr(workspace), workspace.numel(), _stream(stream)))
+
+
+def make_layers(layers, k_sel, q_pos0, d_v, v_off, sm_scale, outs, Lk=None):
     """Build the host array of ic_layer from per-layer tensor dicts (q,k,w may be absent on
-    Shared layers) and output tensors.  The returned object keeps the tensors alive."""
+    Shared layers) and output tensors.  The returned object keeps the tensors alive.
+    Lk: bound on the sequence lengths when k / KV are page pools (forward_stack_paged);
+    by default the length is the caches' second dimension."""
     arr = (Layer * len(layers))()
     keep = []
     for l, (t, O) in enumerate(zip(layers, outs)):
         Q, KV = t["Q"], t["KV"]
         B, Tq, Hq, d_qk = Q.shape
-        arr[l].at = AttnDesc(B, Tq, KV.shape[1], Hq, d_qk, d_v, v_off, KV.shape[2], k_sel, sm_scale)
+        arr[l].at = AttnDesc(B, Tq, KV.shape[1] if Lk is None else Lk, Hq, d_qk, d_v, v_off, KV.shape[-1], k_sel, sm_scale)
         arr[l].Q, arr[l].KV, arr[l].O = Q.data_ptr(), KV.data_ptr(), O.data_ptr()
         if t.get("q") is not None:
-            arr[l].ix = indexer_desc(t["q"], t["k"], t["w"], k_sel, q_pos0, t.get("q_scale"), t.get("k_scale"))
+            if Lk is None:
+                arr[l].ix = indexer_desc(t["q"], t["k"], t["w"], k_sel, q_pos0, t.get("q_scale"), t.get("k_scale"))
+            else:
+                arr[l].ix = IndexerDesc(B, Tq, Lk, t["q"].shape[2], t["q"].shape[3], k_sel, 0, _dtype_code(t["q"]), 0, None, None)
             arr[l].q, arr[l].k, arr[l].w = t["q"].data_ptr(), t["k"].data_ptr(), t["w"].data_ptr()
         keep.append((t, O))
     arr._keep = keep

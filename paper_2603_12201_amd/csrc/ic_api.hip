@@ -139,8 +139,37 @@ size_t attn_ws_bytes(const ic_attn_desc *d)
     return align_up(nq * ns * d->H_q * d->d_v * sizeof(float)) + align_up(nq * ns * d->H_q * 2 * sizeof(float));
 }
 
+// ragged / paged cache description -> the kernels' view (all-zero when pc is NULL)
+ic::PagedView paged_view(const ic_paged_cache *pc)
+{
+    ic::PagedView v;
+    memset(&v, 0, sizeof v);
+    if (pc) {
+        v.seq_lens = pc->seq_lens;
+        v.page_table = pc->page_table;
+        v.max_pages = pc->max_pages;
+        int sh = 0;
+        while ((1 << sh) < pc->page_size) ++sh;
+        v.page_shift = sh;
+    }
+    return v;
+}
+
+ic_status check_paged(const ic_paged_cache *pc, int32_t Lk)
+{
+    if (!pc) return fail(IC_ERR_NULL, "paged cache descriptor is NULL");
+    if (!pc->seq_lens && !pc->page_table) return fail(IC_ERR_NULL, "paged cache: seq_lens and page_table are both NULL");
+    if (pc->page_table) {
+        if (pc->page_size < 64 || (pc->page_size & (pc->page_size - 1)) != 0)
+            return fail(IC_ERR_SHAPE, "page_size=%d must be a power of two >= 64", pc->page_size);
+        if (pc->max_pages <= 0 || (int64_t)pc->max_pages * pc->page_size < Lk)
+            return fail(IC_ERR_SHAPE, "page table rows of %d pages x %d positions do not cover Lk=%d", pc->max_pages, pc->page_size, Lk);
+    }
+    return IC_OK;
+}
+
 ic_status run_indexer(const ic_indexer_desc *d, const void *q, const void *k, const float *w, int32_t *idx,
-                      float *sel, void *ws, size_t ws_bytes, hipStream_t st)
+                      float *sel, void *ws, size_t ws_bytes, hipStream_t st, const ic_paged_cache *pc = nullptr)
 {
     const int64_t rows_cap = strip_rows(d, ws_bytes);
     const int Ri = (int)(d->Tq < rows_cap ? d->Tq : rows_cap);
@@ -159,6 +188,7 @@ ic_status run_indexer(const ic_indexer_desc *d, const void *q, const void *k, co
     sa.Tq = d->Tq;
     sa.Lk = d->Lk;
     sa.H_I = d->H_I;
+    sa.pv = paged_view(pc);
     ic::SelectArgs se;
     memset(&se, 0, sizeof se);
     se.strip = (const float *)ws;
@@ -169,6 +199,7 @@ ic_status run_indexer(const ic_indexer_desc *d, const void *q, const void *k, co
     se.k_sel = d->k_sel;
     se.idx = idx;
     se.sel = sel;
+    se.seq_lens = pc ? pc->seq_lens : nullptr;
     for (int b0 = 0; b0 < d->B; b0 += Bc) {
         const int bc = d->B - b0 < Bc ? d->B - b0 : Bc;
         for (int i0 = 0; i0 < d->Tq; i0 += Ri) {
@@ -178,6 +209,7 @@ ic_status run_indexer(const ic_indexer_desc *d, const void *q, const void *k, co
             sa.Ri = ri;
             int64_t max_vis = d->q_pos0 + i0 + ri;
             max_vis = max_vis < 0 ? 0 : (max_vis > d->Lk ? d->Lk : max_vis);
+            if (pc && pc->seq_lens) max_vis = d->Lk;   // ragged: lengths are device data, Lk bounds them
             if (max_vis > d->k_sel || sel) {   // rows with <= k_sel visible keys need no scores
                 ProfScope ps(0, st);
                 hipError_t e = ic::launch_score(sa, d->dtype, d->d_I, bc, st);
@@ -214,7 +246,7 @@ size_t indexer_min_ws(const ic_indexer_desc *d)
 }
 
 ic_status run_attn(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, void *O, float *lse,
-                   void *ws, hipStream_t st)
+                   void *ws, hipStream_t st, const ic_paged_cache *pc = nullptr)
 {
     ic::AttnArgs a;
     memset(&a, 0, sizeof a);
@@ -232,6 +264,7 @@ ic_status run_attn(const ic_attn_desc *d, const void *Q, const void *KV, const i
     a.k_sel = d->k_sel;
     attn_splits(d, &a.n_splits, &a.split_len);
     a.scale_log2e = d->sm_scale * 1.4426950408889634f;
+    a.pv = paged_view(pc);
     if (a.n_splits > 1) {
         const size_t nq = (size_t)d->B * d->Tq;
         a.part_o = (float *)ws;
@@ -334,13 +367,21 @@ size_t ic_forward_stack_workspace(const ic_layer *layers, int32_t n_layers)
     return need;
 }
 
-ic_status ic_forward_stack(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, int32_t *idx_cache,
-                           void *workspace, size_t workspace_bytes, void *stream)
+static ic_status forward_stack_impl(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const ic_paged_cache *pc,
+                                    int32_t *idx_cache, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!full_mask) return fail(IC_ERR_NULL, "full_mask is NULL");
     if (!idx_cache) return fail(IC_ERR_NULL, "idx_cache is NULL");
     ic_status s = check_stack(layers, n_layers, full_mask);
     if (s != IC_OK) return s;
+    if (pc) {
+        for (int l = 0; l < n_layers; ++l) {
+            s = check_paged(pc, layers[l].at.Lk);
+            if (s != IC_OK) return s;
+            if (full_mask[l] && pc->page_table && layers[l].ix.dtype != IC_BF16)
+                return fail(IC_ERR_UNSUPPORTED, "layer %d: a paged index-key cache must be bf16", l);
+        }
+    }
     size_t need = 0;
     for (int l = 0; l < n_layers; ++l) {
         size_t a = attn_ws_bytes(&layers[l].at);
@@ -354,13 +395,54 @@ ic_status ic_forward_stack(const ic_layer *layers, int32_t n_layers, const uint8
     for (int l = 0; l < n_layers; ++l) {
         const ic_layer *L = &layers[l];
         if (full_mask[l]) {   // Full: fresh indices overwrite the cache; Shared: cache left as it is
-            s = run_indexer(&L->ix, L->q, L->k, L->w, idx_cache, nullptr, workspace, workspace_bytes, st);
+            s = run_indexer(&L->ix, L->q, L->k, L->w, idx_cache, nullptr, workspace, workspace_bytes, st, pc);
             if (s != IC_OK) return s;
         }
-        s = run_attn(&L->at, L->Q, L->KV, idx_cache, L->O, nullptr, workspace, st);
+        s = run_attn(&L->at, L->Q, L->KV, idx_cache, L->O, nullptr, workspace, st, pc);
         if (s != IC_OK) return s;
     }
     return IC_OK;
+}
+
+ic_status ic_forward_stack(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, int32_t *idx_cache,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    return forward_stack_impl(layers, n_layers, full_mask, nullptr, idx_cache, workspace, workspace_bytes, stream);
+}
+
+ic_status ic_forward_stack_paged(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const ic_paged_cache *pc,
+                                 int32_t *idx_cache, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!pc) return fail(IC_ERR_NULL, "paged cache descriptor is NULL");
+    return forward_stack_impl(layers, n_layers, full_mask, pc, idx_cache, workspace, workspace_bytes, stream);
+}
+
+ic_status ic_indexer_topk_paged(const ic_indexer_desc *d, const ic_paged_cache *pc, const void *q, const void *k_pool,
+                                const float *w, int32_t *idx, float *sel_scores, void *workspace, size_t workspace_bytes,
+                                void *stream)
+{
+    ic_status s = check_indexer(d);
+    if (s != IC_OK) return s;
+    s = check_paged(pc, d->Lk);
+    if (s != IC_OK) return s;
+    if (pc->page_table && d->dtype != IC_BF16) return fail(IC_ERR_UNSUPPORTED, "a paged index-key cache must be bf16");
+    if (!q || !k_pool || !w || !idx) return fail(IC_ERR_NULL, "q, k_pool, w and idx must not be NULL");
+    s = check_ws(workspace, workspace_bytes, indexer_min_ws(d));
+    if (s != IC_OK) return s;
+    return run_indexer(d, q, k_pool, w, idx, sel_scores, workspace, workspace_bytes, (hipStream_t)stream, pc);
+}
+
+ic_status ic_sparse_attn_paged(const ic_attn_desc *d, const ic_paged_cache *pc, const void *Q, const void *KV_pool,
+                               const int32_t *idx, void *O, float *lse, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ic_status s = check_attn(d);
+    if (s != IC_OK) return s;
+    s = check_paged(pc, d->Lk);
+    if (s != IC_OK) return s;
+    if (!Q || !KV_pool || !idx || !O) return fail(IC_ERR_NULL, "Q, KV_pool, idx and O must not be NULL");
+    s = check_ws(workspace, workspace_bytes, attn_ws_bytes(d));
+    if (s != IC_OK) return s;
+    return run_attn(d, Q, KV_pool, idx, O, lse, workspace, (hipStream_t)stream, pc);
 }
 
 ic_status ic_pattern_from_string(const char *fs, uint8_t *full_mask, int32_t n)

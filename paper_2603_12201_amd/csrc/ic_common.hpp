@@ -18,6 +18,23 @@ constexpr int kWave = 64;
 
 // ---- kernel argument blocks ---------------------------------------------------------
 
+// Ragged and paged caches (decode with a full KV cache, paper Sec. 4.3 setting): per-sequence
+// lengths and a page table from logical to physical pages.  All-zero = the dense layout.
+struct PagedView {
+    const int32_t *seq_lens;    // [B] visible length of each sequence (nullptr: every sequence has Lk)
+    const int32_t *page_table;  // [B, max_pages] physical page of a logical page (nullptr: not paged)
+    int32_t page_shift;         // log2(positions per page), pages hold a power of two >= 64 positions
+    int32_t max_pages;
+};
+
+// physical row of logical position s of sequence b (paged layout only)
+__device__ __forceinline__ int64_t paged_row(const PagedView &pv, int b, int s)
+{
+    const int32_t page = pv.page_table[(int64_t)b * pv.max_pages + (s >> pv.page_shift)];
+    return ((int64_t)page << pv.page_shift) + (s & ((1 << pv.page_shift) - 1));
+}
+
+
 // Indexer scoring of query rows [i0, i0+Ri) of sequences [b0, b0+Bc) against their keys.
 // Scores land in a strip: row (b-b0)*Ri + (i-i0), element s, row stride ld floats.
 struct ScoreArgs {
@@ -33,6 +50,7 @@ struct ScoreArgs {
     int32_t b0, i0, Ri;   // chunk origin and rows per sequence in the strip
     int32_t n_qblocks;    // ceil(Ri / tokens per workgroup)
     int32_t KC;           // keys per workgroup along grid.y (multiple of 64)
+    PagedView pv;         // ragged / paged key cache (the Tq query rows are the LAST Tq positions of a sequence)
 };
 
 // Per-row top-k over a strip of scores.
@@ -45,6 +63,7 @@ struct SelectArgs {
     int32_t cache_elems;  // row elements the workgroup may cache in LDS (0 = none)
     int32_t *idx;         // [B,Tq,k_sel]
     float *sel;           // [B,Tq,k_sel] or nullptr
+    const int32_t *seq_lens;  // ragged: [B] visible lengths (nullptr: q_pos0 rule)
 };
 
 struct AttnArgs {
@@ -58,6 +77,7 @@ struct AttnArgs {
     int32_t B, Tq, Lk, H_q, v_off, row_elems, k_sel;
     int32_t n_splits, split_len; // key slots per split (multiple of 64)
     float scale_log2e;    // sm_scale * log2(e)
+    PagedView pv;         // ragged / paged KV cache (KV is then the page pool [n_pages << page_shift, row_elems])
 };
 
 // ---- launchers (defined next to their kernels) ----------------------------------------

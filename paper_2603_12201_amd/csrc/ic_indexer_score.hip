@@ -60,16 +60,17 @@ template <> struct Fmt<true> {
 
 // Global -> register -> LDS staging of one tile of 64 key rows (16-byte chunks, coalesced).
 // RB = bytes per key row.
+// tile: address of the tile's first key row; rows_valid >= 1 of its 64 rows exist.
 template <int RB, int LPT, int NT>
-__device__ __forceinline__ void tile_gload(u32x4 (&pre)[LPT], const unsigned char *kp, int kt, int Lk, int tid)
+__device__ __forceinline__ void tile_gload(u32x4 (&pre)[LPT], const unsigned char *tile, int rows_valid, int tid)
 {
     constexpr int CPR = RB / 16;
 #pragma unroll
     for (int r = 0; r < LPT; ++r) {
         const int c = tid + NT * r;
         const int row = c / CPR, col = c % CPR;
-        const int s = min(kt + row, Lk - 1);                // clamp: rows past Lk are masked later
-        pre[r] = *(const u32x4 *)(kp + ((int64_t)s * RB + col * 16));
+        const int s = min(row, rows_valid - 1);             // clamp: rows past the end are masked later
+        pre[r] = *(const u32x4 *)(tile + (s * RB + col * 16));
     }
 }
 
@@ -96,7 +97,8 @@ __device__ __forceinline__ float relu(float x)
 // keeps its q rows, and the waves take turns on the key subtiles (wave w multiplies subtile
 // w & 1 of the tiles with parity w >> 1) so that all four SIMDs share the little matrix work
 // while the kernel streams the key cache.
-template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM, bool FP8>
+// PG: the key cache may be ragged and / or paged (a.pv); false compiles the dense layout only.
+template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM, bool FP8, bool PG>
 __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
 {
     static_assert(!STREAM || (TPW == 1 && NW == 4), "the streaming form is one token, four waves");
@@ -122,16 +124,20 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     const int t_blk = a.i0 + qb * BT;
     if (t_blk >= i_end) return;
     const int t_blk_last = min(t_blk + BT, i_end) - 1;
+    // ragged cache: this sequence holds Lk_b keys and its Tq query rows are its last Tq positions
+    const bool ragged = PG && a.pv.seq_lens, paged = PG && a.pv.page_table;
+    const int Lk_b = ragged ? max(0, min(a.pv.seq_lens[b], a.Lk)) : a.Lk;
+    const int64_t q_pos0 = ragged ? (int64_t)Lk_b - a.Tq : a.q_pos0;
 
-    int64_t vis64 = a.q_pos0 + (int64_t)t_blk_last + 1;    // keys visible to the block's last token
-    vis64 = vis64 < 0 ? 0 : (vis64 > a.Lk ? a.Lk : vis64);
+    int64_t vis64 = q_pos0 + (int64_t)t_blk_last + 1;      // keys visible to the block's last token
+    vis64 = vis64 < 0 ? 0 : (vis64 > Lk_b ? Lk_b : vis64);
     const int kc0 = (int)blockIdx.y * a.KC;
     const int kend = min(kc0 + a.KC, (int)vis64);
     if (kc0 >= kend) return;                               // whole workgroup: nothing visible here
 
     const int t_w0 = STREAM ? t_blk : t_blk + wave * TPW;  // this wave's first token
-    int64_t wv64 = a.q_pos0 + (int64_t)min(t_w0 + TPW, i_end);
-    wv64 = wv64 < 0 ? 0 : (wv64 > a.Lk ? a.Lk : wv64);
+    int64_t wv64 = q_pos0 + (int64_t)min(t_w0 + TPW, i_end);
+    wv64 = wv64 < 0 ? 0 : (wv64 > Lk_b ? Lk_b : wv64);
     const int wave_vis = (t_w0 < i_end) ? (int)wv64 : 0;   // keys >= wave_vis matter to none of its tokens
 
     // ---- stationary operands: q rows (A operand) and head weights of the wave's tokens ----
@@ -164,16 +170,20 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     }
 
     // ---- key tile pipeline: global -> registers -> LDS, double buffered, one barrier per tile ----
-    const unsigned char *kp = (const unsigned char *)a.k + (int64_t)b * a.Lk * RB;
+    const unsigned char *kp = (const unsigned char *)a.k + (paged ? 0 : (int64_t)b * a.Lk * RB);
     const float *ksc = FP8 ? a.k_scale + (int64_t)b * a.Lk : nullptr;
+    // first row of the 64-key tile at kt (tiles never straddle a page: pages hold a multiple of 64 positions)
+    auto tile_ptr = [&](int kt) -> const unsigned char * {
+        return kp + (paged ? paged_row(a.pv, b, kt) : (int64_t)kt) * RB;
+    };
     // PD register sets keep PD tiles in flight from HBM/L2 (set t % PD holds tile t); a tile is
     // copied to LDS one iteration before it is multiplied.
     u32x4 pre[PD][LPT];
     const int ntiles = (kend - kc0 + TILE - 1) / TILE;
-    tile_gload<RB, LPT, NT>(pre[0], kp, kc0, a.Lk, tid);
+    tile_gload<RB, LPT, NT>(pre[0], tile_ptr(kc0), Lk_b - kc0, tid);
 #pragma unroll
     for (int d = 1; d < PD; ++d)
-        if (d < ntiles) tile_gload<RB, LPT, NT>(pre[d], kp, kc0 + d * TILE, a.Lk, tid);
+        if (d < ntiles) tile_gload<RB, LPT, NT>(pre[d], tile_ptr(kc0 + d * TILE), Lk_b - (kc0 + d * TILE), tid);
     tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[0][0], tid);
     __syncthreads();
 
@@ -189,9 +199,9 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         if (FP8) {
             // positive per-token scales commute with the ReLU gate: I = sq[t] sk[s] sum_j w_j ReLU(q8_j . k8)
             const float sq = (pair && half) ? sqr[(j + 1) % TPW] : sqr[j];
-            v *= sq * ksc[min(s, a.Lk - 1)];
+            v *= sq * ksc[min(s, Lk_b - 1)];
         }
-        if (lane_on && (interior || (t < i_end && s < a.Lk && (int64_t)s <= a.q_pos0 + t))) {
+        if (lane_on && (interior || (t < i_end && s < Lk_b && (int64_t)s <= q_pos0 + t))) {
             const int64_t srow = (int64_t)blockIdx.z * a.Ri + (t - a.i0);
             a.strip[srow * a.ld + s] = v;
         }
@@ -204,12 +214,12 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         if (it >= ntiles) break;                            // workgroup-uniform
         const int kt = kc0 + it * TILE;
         const int buf = it & 1;
-        if (it + PD < ntiles) tile_gload<RB, LPT, NT>(pre[ph], kp, kt + PD * TILE, a.Lk, tid);
+        if (it + PD < ntiles) tile_gload<RB, LPT, NT>(pre[ph], tile_ptr(kt + PD * TILE), Lk_b - (kt + PD * TILE), tid);
 
         // Interior tile: all 64 keys are visible to every token of this wave and every token is a
         // real row, so nothing needs masking and the whole tile is one straight-line block.
-        const bool interior = (t_w0 + TPW <= i_end) && (kt + TILE <= a.Lk) &&
-                              ((int64_t)(kt + TILE - 1) <= a.q_pos0 + t_w0);
+        const bool interior = (t_w0 + TPW <= i_end) && (kt + TILE <= Lk_b) &&
+                              ((int64_t)(kt + TILE - 1) <= q_pos0 + t_w0);
         if (interior && !STREAM) {
             // Software pipeline over the units (key subtile, token, head tile): the MFMA chain of unit
             // c+1 is issued before the ReLU/weight/sum epilogue of unit c, so the matrix pipe works
@@ -304,7 +314,10 @@ hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
     const int n_kc = (int)((max_vis + a.KC - 1) / a.KC);
     if (n_kc <= 0 || a.n_qblocks <= 0 || Bc <= 0) return hipSuccess;
     dim3 grid((unsigned)a.n_qblocks, (unsigned)n_kc, (unsigned)Bc);
-    hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW, PD, MINB, STREAM, FP8>), grid, dim3(64 * NW), 0, st, a);
+    if (a.pv.seq_lens || a.pv.page_table)
+        hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW, PD, MINB, STREAM, FP8, true>), grid, dim3(64 * NW), 0, st, a);
+    else
+        hipLaunchKernelGGL((score_kernel<HT, DI, TPW, NW, PD, MINB, STREAM, FP8, false>), grid, dim3(64 * NW), 0, st, a);
     return hipGetLastError();
 }
 
@@ -330,6 +343,7 @@ hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipSt
     const int i_last = min(a.i0 + a.Ri, a.Tq) - 1;
     int64_t max_vis = a.q_pos0 + i_last + 1;
     max_vis = max_vis < 0 ? 0 : (max_vis > a.Lk ? a.Lk : max_vis);
+    if (a.pv.seq_lens) max_vis = a.Lk;          // ragged: the lengths live on the device, Lk is their bound
     if (max_vis == 0) return hipSuccess;
     // keys per workgroup (tiles of 64 keys): prefill wants enough workgroups to fill 256 CUs
     // several times; the streaming variant wants exactly one resident round (3 per CU).

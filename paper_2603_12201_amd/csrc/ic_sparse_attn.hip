@@ -28,14 +28,15 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // Tile staging.  A thread owns tile row tid / 8 and the 16-byte chunks (tid % 8) + 8 r of that
 // row: eight neighbouring lanes read one full 128-byte line, and no index needs a division.
-template <int ROW_F, int LPT>
+template <int ROW_F, int LPT, bool PG>
 __device__ __forceinline__ void attn_gload(u32x4 (&pre)[LPT], const unsigned short *kv_seq, const int32_t *ti,
-                                           int row_elems, int tid)
+                                           int row_elems, int tid, const PagedView &pv, int b)
 {
     constexpr int CPR = ROW_F / 8;
     const int row = tid >> 3, c0 = tid & 7;
-    const int32_t v = ti[row];
-    const unsigned short *src = kv_seq + (int64_t)(v < 0 ? 0 : v) * row_elems + c0 * 8;
+    const int32_t v = ti[row];                             // empty slots read row 0 (never a page-table entry)
+    const int64_t prow = v < 0 ? 0 : (PG && pv.page_table ? paged_row(pv, b, v) : (int64_t)v);
+    const unsigned short *src = kv_seq + prow * row_elems + c0 * 8;
 #pragma unroll
     for (int r = 0; r < LPT; ++r)
         if (c0 + 8 * r < CPR) pre[r] = *(const u32x4 *)(src + 64 * r);
@@ -52,7 +53,8 @@ __device__ __forceinline__ void attn_lstore(const u32x4 (&pre)[LPT], unsigned ch
         if (c0 + 8 * r < CPR) *(u32x4 *)(dst + 128 * r) = pre[r];
 }
 
-template <int D_QK, int D_V, int ROW_F>
+// PG: the KV cache may be ragged and / or paged (a.pv); false compiles the dense layout only.
+template <int D_QK, int D_V, int ROW_F, bool PG>
 __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 {
     constexpr int ROWB = ROW_F * 2 + 16;                  // LDS row stride in bytes
@@ -78,13 +80,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
     const int ntiles = (slot1 - slot0 + kTile - 1) / kTile;
 
     const int32_t *idx_row = a.idx + qrow * a.k_sel;
-    const unsigned short *kv_seq = (const unsigned short *)a.KV + (int64_t)b * a.Lk * a.row_elems;
+    const unsigned short *kv_seq = (const unsigned short *)a.KV + (PG && a.pv.page_table ? 0 : (int64_t)b * a.Lk * a.row_elems);
+    const int Lk_b = PG && a.pv.seq_lens ? min(a.pv.seq_lens[b], a.Lk) : a.Lk;     // ragged cache: rows of this sequence
 
     auto fetch_idx = [&](int it) -> int32_t {             // threads 0..31: validated row id of a slot
         const int slot = slot0 + it * kTile + tid;
         int32_t v = -1;
         if (it < ntiles && slot < slot1) v = idx_row[slot];
-        return (v >= 0 && v < a.Lk) ? v : -1;
+        return (v >= 0 && v < Lk_b) ? v : -1;
     };
 
     // ---- Q as the B operand of S^T = K Q^T: lane (head l16, k-group g) ----
@@ -110,7 +113,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
     __syncthreads();
     u32x4 pre[LPT];
     if (ntiles > 0) {
-        attn_gload<ROW_F, LPT>(pre, kv_seq, tidx, a.row_elems, tid);
+        attn_gload<ROW_F, LPT, PG>(pre, kv_seq, tidx, a.row_elems, tid, a.pv, b);
         attn_lstore<ROW_F, LPT, ROWB>(pre, tile0, tid);
     }
     __syncthreads();
@@ -126,7 +129,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
         const int buf = it & 1;
         int32_t nxt_idx = -1;
         if (tid < kTile) nxt_idx = fetch_idx(it + 2);
-        if (it + 1 < ntiles) attn_gload<ROW_F, LPT>(pre, kv_seq, tidx + ((it + 1) % 3) * kTile, a.row_elems, tid);
+        if (it + 1 < ntiles) attn_gload<ROW_F, LPT, PG>(pre, kv_seq, tidx + ((it + 1) % 3) * kTile, a.row_elems, tid, a.pv, b);
 
         if (wave_ok) {
             const unsigned char *tb = tile0 + buf * TILEB;
@@ -291,7 +294,7 @@ __device__ __forceinline__ unsigned rows_mask(unsigned long long ba, unsigned lo
     return lo | (hi << 8);
 }
 
-template <int D_QK, int D_V>                              // value columns = the first D_V features of a row
+template <int D_QK, int D_V, bool PG>                     // value columns = the first D_V features of a row; PG as above
 __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
 {
     constexpr int KS = D_QK / 32;                         // contraction steps of S^T = 16-byte chunks per gather lane
@@ -318,7 +321,8 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     const int ntiles = (slot1 + kSlabTile - 1) / kSlabTile;
 
     const int32_t *idx_row = a.idx + qrow * a.k_sel;
-    const unsigned short *kv_seq = (const unsigned short *)a.KV + (int64_t)b * a.Lk * a.row_elems;
+    const unsigned short *kv_seq = (const unsigned short *)a.KV + (PG && a.pv.page_table ? 0 : (int64_t)b * a.Lk * a.row_elems);
+    const int Lk_b = PG && a.pv.seq_lens ? min(a.pv.seq_lens[b], a.Lk) : a.Lk;     // ragged cache: rows of this sequence
 
     // Loads inside the tile loop are unconditional (clamped addresses, result discarded when out
     // of range): the wait counters are positional, and a load that may or may not have been
@@ -328,11 +332,15 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         const int s_lo = slot0 + it * kSlabTile + 16 * wave + gr, s_hi = s_lo + 8;
         const int32_t v_lo = idx_row[min(s_lo, a.k_sel - 1)], v_hi = idx_row[min(s_hi, a.k_sel - 1)];
         Ids r;
-        r.lo = (s_lo < slot1 && v_lo >= 0 && v_lo < a.Lk) ? v_lo : -1;
-        r.hi = (s_hi < slot1 && v_hi >= 0 && v_hi < a.Lk) ? v_hi : -1;
+        r.lo = (s_lo < slot1 && v_lo >= 0 && v_lo < Lk_b) ? v_lo : -1;
+        r.hi = (s_hi < slot1 && v_hi >= 0 && v_hi < Lk_b) ? v_hi : -1;
         return r;
     };
-    auto row_ptr = [&](int32_t v) { return kv_seq + (int64_t)(v < 0 ? 0 : v) * a.row_elems + 8 * gp; };
+    auto row_ptr = [&](int32_t v) {
+        // empty slots read row 0 of the cache (never a page-table entry: the sequence may own no page)
+        const int64_t prow = v < 0 ? 0 : (PG && a.pv.page_table ? paged_row(a.pv, b, v) : (int64_t)v);
+        return kv_seq + prow * a.row_elems + 8 * gp;
+    };
     auto ids_mask = [&](const Ids &d) { return rows_mask(__ballot(d.lo >= 0), __ballot(d.hi >= 0)); };
 
     // Q as the B operand: lane (head 16 hb + l16, features 8 g..) for both head blocks
@@ -664,11 +672,17 @@ hipError_t launch_t(const AttnArgs &a, hipStream_t st)
 {
     constexpr int ROWB = ROW_F * 2 + 16;
     const size_t lds = (size_t)2 * kTile * ROWB + 3 * kTile * sizeof(int32_t);
-    static hipError_t attr = hipFuncSetAttribute((const void *)attn_kernel<D_QK, D_V, ROW_F>,
+    static hipError_t attr = hipFuncSetAttribute((const void *)attn_kernel<D_QK, D_V, ROW_F, false>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static hipError_t attr_pg = hipFuncSetAttribute((const void *)attn_kernel<D_QK, D_V, ROW_F, true>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return attr;
+    if (attr_pg != hipSuccess) return attr_pg;
     dim3 grid((unsigned)((int64_t)a.B * a.Tq), (unsigned)a.n_splits);
-    hipLaunchKernelGGL((attn_kernel<D_QK, D_V, ROW_F>), grid, dim3(256), lds, st, a);
+    if (a.pv.seq_lens || a.pv.page_table)
+        hipLaunchKernelGGL((attn_kernel<D_QK, D_V, ROW_F, true>), grid, dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((attn_kernel<D_QK, D_V, ROW_F, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
@@ -676,11 +690,17 @@ template <int D_QK, int D_V>
 hipError_t launch_slab(const AttnArgs &a, hipStream_t st)
 {
     const size_t lds = (size_t)2 * kSlabTile * D_QK * 2 + 2 * 32 * (kSlabTile * 2 + 16) + (4 * 32 + 4 * 32) * sizeof(float);
-    static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V>,
+    static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, false>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static hipError_t attr_pg = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, true>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return attr;
+    if (attr_pg != hipSuccess) return attr_pg;
     dim3 grid((unsigned)((int64_t)a.B * a.Tq));
-    hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V>), grid, dim3(256), lds, st, a);
+    if (a.pv.seq_lens || a.pv.page_table)
+        hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, true>), grid, dim3(256), lds, st, a);
+    else
+        hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 

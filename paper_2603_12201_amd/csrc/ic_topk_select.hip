@@ -92,8 +92,10 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     const int b = a.b0 + r / a.Ri;
     const int i = a.i0 + r % a.Ri;
     if (i >= a.Tq) return;
-    int64_t nv64 = a.q_pos0 + (int64_t)i + 1;
-    nv64 = nv64 < 0 ? 0 : (nv64 > a.Lk ? a.Lk : nv64);
+    // ragged cache: the sequence holds Lk_b keys and its Tq query rows are its last Tq positions
+    const int Lk_b = a.seq_lens ? max(0, min(a.seq_lens[b], a.Lk)) : a.Lk;
+    int64_t nv64 = (a.seq_lens ? (int64_t)Lk_b - a.Tq : a.q_pos0) + (int64_t)i + 1;
+    nv64 = nv64 < 0 ? 0 : (nv64 > Lk_b ? Lk_b : nv64);
     const int nv = (int)nv64;
     const float *row = a.strip + (int64_t)r * a.ld;
     int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
@@ -261,8 +263,10 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
     const int b = a.b0 + r / a.Ri;
     const int i = a.i0 + r % a.Ri;
     if (i >= a.Tq) return;
-    int64_t nv64 = a.q_pos0 + (int64_t)i + 1;
-    nv64 = nv64 < 0 ? 0 : (nv64 > a.Lk ? a.Lk : nv64);
+    // ragged cache: the sequence holds Lk_b keys and its Tq query rows are its last Tq positions
+    const int Lk_b = a.seq_lens ? max(0, min(a.seq_lens[b], a.Lk)) : a.Lk;
+    int64_t nv64 = (a.seq_lens ? (int64_t)Lk_b - a.Tq : a.q_pos0) + (int64_t)i + 1;
+    nv64 = nv64 < 0 ? 0 : (nv64 > Lk_b ? Lk_b : nv64);
     const int nv = (int)nv64;
     const float *row = a.strip + (int64_t)r * a.ld;
     int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;

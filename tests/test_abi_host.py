@@ -220,3 +220,47 @@ def test_similarity_argument_errors_need_no_gpu():
     assert L.ic_pattern_search_dp(flat, 2, 0, buf, None) == S.ERR_SHAPE
     assert L.ic_pattern_search_dp(None, 2, 1, buf, None) == S.ERR_NULL
     assert L.ic_pattern_search_dp(flat, 2, 1, buf, None) == S.OK and buf.raw[:2] == bytes([1, 0])
+
+
+def test_paged_cache_argument_errors(ic):
+    L, S = ic.lib(), ic.Status
+    one = C.c_void_p(4096)
+    ixd = _ixd(ic)
+    atd = _atd(ic, k_sel=256)
+    ws = max(L.ic_indexer_topk_workspace(C.byref(ixd)), L.ic_sparse_attn_workspace(C.byref(atd)))
+    Lk = ixd.Lk
+    pages = -(-Lk // 64)
+
+    def pc(page_size=64, max_pages=pages, table=4096, lens=4096):
+        return ic.PagedCache(page_size, max_pages, table, lens)
+
+    def ix(p, d=ixd):
+        return L.ic_indexer_topk_paged(C.byref(d), C.byref(p) if p is not None else None, one, one, one, one, None, one, ws, None)
+
+    def at(p):
+        return L.ic_sparse_attn_paged(C.byref(atd), C.byref(p) if p is not None else None, one, one, one, one, None, one, ws, None)
+
+    for call in (ix, at):
+        assert call(None) == S.ERR_NULL
+        assert call(pc(table=None, lens=None)) == S.ERR_NULL             # neither ragged nor paged
+        assert call(pc(page_size=48)) == S.ERR_SHAPE                     # not a power of two
+        assert call(pc(page_size=32, max_pages=4 * pages)) == S.ERR_SHAPE   # below one key tile
+        assert call(pc(max_pages=pages - 1)) == S.ERR_SHAPE              # table rows do not cover Lk
+        assert call(pc(max_pages=0)) == S.ERR_SHAPE
+        assert len(L.ic_last_error()) > 0
+    # the page geometry is ignored when only the lengths are given
+    assert L.ic_indexer_topk_paged(C.byref(ixd), C.byref(pc(page_size=0, max_pages=0, table=None)), None, one, one, one,
+                                   None, one, ws, None) == S.ERR_NULL    # got past the cache check: q is NULL
+    fp8 = _ixd(ic, dtype=1)
+    fp8.q_scale = fp8.k_scale = 4096
+    assert ix(pc(), fp8) == S.ERR_UNSUPPORTED                            # paged fp8 index keys
+    assert L.ic_indexer_topk_paged(C.byref(ixd), C.byref(pc()), one, one, one, one, None, one, 16, None) == S.ERR_WORKSPACE
+    # the stack entry point applies the same checks to every layer
+    arr = (ic.Layer * 2)()
+    for l in range(2):
+        arr[l].ix, arr[l].at = _ixd(ic), _atd(ic, k_sel=64)
+        arr[l].q = arr[l].k = arr[l].w = arr[l].Q = arr[l].KV = arr[l].O = 4096
+    wss = L.ic_forward_stack_workspace(arr, 2)
+    assert L.ic_forward_stack_paged(arr, 2, bytes([1, 0]), None, one, one, wss, None) == S.ERR_NULL
+    assert L.ic_forward_stack_paged(arr, 2, bytes([1, 0]), C.byref(pc(max_pages=1)), one, one, wss, None) == S.ERR_SHAPE
+    assert L.ic_forward_stack_paged(arr, 2, bytes([0, 1]), C.byref(pc()), one, one, wss, None) == S.ERR_PATTERN
