@@ -117,13 +117,15 @@ ic_status check_attn(const ic_attn_desc *d)
     return IC_OK;
 }
 
-// Key-slot splits per query: one workgroup per query when there are enough queries to fill the
-// chip (two workgroups per CU), otherwise split the k_sel slots so that about 512 workgroups exist.
+// Key-slot splits per query.  MLA rows with the values in front run one workgroup per CU: one per
+// query when there are at least 256 queries, otherwise the k_sel slots are split so that about 256
+// workgroups exist.  The other layouts run two workgroups per CU and aim for 512.
 void attn_splits(const ic_attn_desc *d, int *n_splits, int *split_len)
 {
     const int64_t nq = (int64_t)d->B * d->Tq;
     const int tiles = (d->k_sel + 63) / 64;
-    int64_t want = nq >= 512 ? 1 : (512 + nq - 1) / nq;
+    const int64_t wgs = (d->d_qk == 576 && d->v_off == 0) ? 256 : 512;
+    int64_t want = nq >= wgs ? 1 : (wgs + nq - 1) / nq;
     if (want > tiles) want = tiles;
     const int tiles_per = (int)((tiles + want - 1) / want);
     *split_len = tiles_per * 64;

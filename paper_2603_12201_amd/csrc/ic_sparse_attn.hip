@@ -294,7 +294,9 @@ __device__ __forceinline__ unsigned rows_mask(unsigned long long ba, unsigned lo
     return lo | (hi << 8);
 }
 
-template <int D_QK, int D_V, bool PG>                     // value columns = the first D_V features of a row; PG as above
+// SPLIT: blockIdx.y selects a.split_len key slots of the query and the result is a partial
+// (unnormalised accumulators, reference maximum, row sum) for the merge kernel.
+template <int D_QK, int D_V, bool PG, bool SPLIT>         // value columns = the first D_V features of a row; PG as above
 __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
 {
     constexpr int KS = D_QK / 32;                         // contraction steps of S^T = 16-byte chunks per gather lane
@@ -316,9 +318,10 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     const int gr = lane >> 3, gp = lane & 7;              // gather role: row (and row + 8), 16-byte piece
     const int64_t qrow = blockIdx.x;
     const int b = (int)(qrow / a.Tq);
-    constexpr int slot0 = 0;                              // this form always covers a query's whole selection
-    const int slot1 = a.k_sel;
-    const int ntiles = (slot1 + kSlabTile - 1) / kSlabTile;
+    const int sp = SPLIT ? (int)blockIdx.y : 0;
+    const int slot0 = SPLIT ? sp * a.split_len : 0;
+    const int slot1 = SPLIT ? min(slot0 + a.split_len, a.k_sel) : a.k_sel;
+    const int ntiles = (slot1 - slot0 + kSlabTile - 1) / kSlabTile;
 
     const int32_t *idx_row = a.idx + qrow * a.k_sel;
     const unsigned short *kv_seq = (const unsigned short *)a.KV + (PG && a.pv.page_table ? 0 : (int64_t)b * a.Lk * a.row_elems);
@@ -623,6 +626,23 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     __syncthreads();
     const float l_head = lbuf[l32] + lbuf[32 + l32] + lbuf[64 + l32] + lbuf[96 + l32];   // head l32
     const float m_head = m_c;
+    if constexpr (SPLIT) {
+        // partial of this split: accumulators and row sum in the reference m_head
+        if (wave == 0 && hh == 0 && l32 < a.H_q) {
+            float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + l32) * 2;
+            ml[0] = m_head;
+            ml[1] = l_head;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);
+            if (hq >= a.H_q) continue;
+            float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + 32 * wave + l32;
+#pragma unroll
+            for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = oacc[nb][i];
+        }
+        return;
+    }
     if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
         a.lse[qrow * a.H_q + l32] = (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
 #pragma unroll
@@ -686,22 +706,24 @@ hipError_t launch_t(const AttnArgs &a, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int D_QK, int D_V, bool PG, bool SPLIT>
+hipError_t launch_slab_t(const AttnArgs &a, size_t lds, hipStream_t st)
+{
+    static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, PG, SPLIT>,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (attr != hipSuccess) return attr;
+    dim3 grid((unsigned)((int64_t)a.B * a.Tq), (unsigned)(SPLIT ? a.n_splits : 1));
+    hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, PG, SPLIT>), grid, dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
 template <int D_QK, int D_V>
 hipError_t launch_slab(const AttnArgs &a, hipStream_t st)
 {
     const size_t lds = (size_t)2 * kSlabTile * D_QK * 2 + 2 * 32 * (kSlabTile * 2 + 16) + (4 * 32 + 4 * 32) * sizeof(float);
-    static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, false>,
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    static hipError_t attr_pg = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, true>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (attr != hipSuccess) return attr;
-    if (attr_pg != hipSuccess) return attr_pg;
-    dim3 grid((unsigned)((int64_t)a.B * a.Tq));
-    if (a.pv.seq_lens || a.pv.page_table)
-        hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, true>), grid, dim3(256), lds, st, a);
-    else
-        hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, false>), grid, dim3(256), lds, st, a);
-    return hipGetLastError();
+    const bool pg = a.pv.seq_lens || a.pv.page_table;
+    if (a.n_splits > 1) return pg ? launch_slab_t<D_QK, D_V, true, true>(a, lds, st) : launch_slab_t<D_QK, D_V, false, true>(a, lds, st);
+    return pg ? launch_slab_t<D_QK, D_V, true, false>(a, lds, st) : launch_slab_t<D_QK, D_V, false, false>(a, lds, st);
 }
 
 } // namespace
@@ -715,9 +737,10 @@ hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st)
 {
     if ((int64_t)a.B * a.Tq <= 0) return hipSuccess;
     if (d_qk == 576 && d_v == 512) {
-        // whole-selection launches (many queries) take the row-slab form, split launches (decode)
-        // the small-tile form with two workgroups per CU
-        if (a.n_splits == 1 && a.v_off == 0) return launch_slab<576, 512>(a, st);
+        // the row-slab form: one workgroup per query, or per split of a query's selection when
+        // there are too few queries to fill the chip (decode); rows with the values elsewhere than
+        // in their first features take the small-tile form
+        if (a.v_off == 0) return launch_slab<576, 512>(a, st);
         return launch_t<576, 512, 576>(a, st);
     }
     if (d_qk == 64 && d_v == 64) return launch_t<64, 64, 128>(a, st);

@@ -33,10 +33,26 @@ __device__ __forceinline__ float key_score(uint32_t key)
 
 constexpr int kBins1 = 4096;   // histogram bins: digits of 12, 12 and 8 key bits
 
+// Inclusive prefix sum over the 64 lanes of a wave on the data-parallel-primitive path of the
+// vector ALU (no LDS traffic): shifts by 1, 2, 4, 8 lanes inside each row of 16 lanes, then the
+// last lane of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.  Lanes
+// without a source add zero.  Packed fields are summed independently as long as none overflows.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
+{
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);   // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);   // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);   // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);   // row_shr:8
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return x;
+}
+
 // Workgroup-wide descending scan over `nbins` counters: finds the digit d with
 // count(bins > d) < need <= count(bins >= d) and writes {d, need - count(bins > d)} to bc.
-// Every thread owns BPT consecutive bins, highest bins first.
-template <int NT, int BPT>
+// Every thread owns BPT consecutive bins, highest bins first.  A bin is the sum of R adjacent
+// counters (R > 1: the histogram was spread over R copies against same-address collisions).
+template <int NT, int BPT, int R = 1>
 __device__ __forceinline__ void find_digit(const uint32_t *cnt, uint32_t need, uint32_t *wsum, uint32_t *bc,
                                            int tid, int lane, int wave)
 {
@@ -46,7 +62,17 @@ __device__ __forceinline__ void find_digit(const uint32_t *cnt, uint32_t need, u
     uint32_t mine = 0;
 #pragma unroll
     for (int j = 0; j < BPT; ++j) {
-        c[j] = cnt[top - j];
+        if constexpr (R == 1) {
+            c[j] = cnt[top - j];
+        } else {
+            static_assert(R % 4 == 0, "copies are read as 16-byte vectors");
+            c[j] = 0;
+#pragma unroll
+            for (int q = 0; q < R / 4; ++q) {
+                const u32x4 v = *(const u32x4 *)(cnt + (top - j) * R + 4 * q);
+                c[j] += v[0] + v[1] + v[2] + v[3];
+            }
+        }
         mine += c[j];
     }
     uint32_t incl = mine;
@@ -253,10 +279,18 @@ template <int NT, int NCH>
 __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
 {
     constexpr int NW = NT / 64;
-    __shared__ uint32_t hist[kBins1];
+    // First digit: all 4*NT*NCH keys hit the histogram and most of them fall into a few dozen bins
+    // (scores of one row share a handful of exponents), so every bin has kSpread counters and a
+    // lane adds to counter lane % kSpread: an eighth of the same-address collisions.  The later
+    // digits count few keys and use the first kBins1 words as a plain histogram.
+    constexpr int kSpread = 8;
+    extern __shared__ __attribute__((aligned(16))) uint32_t hist[];   // [kBins1 * kSpread]
     __shared__ uint32_t wsum[2 * NW];
     __shared__ uint32_t bc[4];
     __shared__ __attribute__((aligned(16))) uint32_t wtot[2][NW < 4 ? 4 : NW];   // emit: equal << 16 | greater per wave
+    static_assert(NCH % 2 == 0 && NCH * NW == 256, "the one-scan emit covers 256 (chunk, wave) cells with one wave");
+    __shared__ __attribute__((aligned(16))) uint32_t cellsum[NCH / 2][NW];    // selected entries of (chunk pair, wave), 16-bit fields
+    __shared__ __attribute__((aligned(16))) uint32_t cellbase[NCH * NW];      // selected entries ahead of cell (chunk, wave)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = blockIdx.x;
@@ -309,10 +343,25 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
     }
 
     // ---- three digit passes: 12 + 12 + 8 bits, most significant first ----
-    uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)a.k_sel;
+    uint32_t prefix, prefix_mask, need;
+    {
+        for (int e = tid; e < kBins1 * kSpread / 4; e += NT) ((u32x4 *)hist)[e] = u32x4{0u, 0u, 0u, 0u};
+        __syncthreads();
+        const uint32_t copy = (uint32_t)lane & (kSpread - 1);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) atomicAdd(&hist[((key[c][e] >> 20) * kSpread) | copy], 1u);
+        __syncthreads();
+        find_digit<NT, kBins1 / NT, kSpread>(hist, (uint32_t)a.k_sel, wsum, bc, tid, lane, wave);
+        prefix = bc[0] << 20;
+        prefix_mask = 4095u << 20;
+        need = bc[1];
+        __syncthreads();
+    }
 #pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 20 : (pass == 1 ? 8 : 0);
+    for (int pass = 1; pass < 3; ++pass) {
+        const int shift = pass == 1 ? 8 : 0;
         const uint32_t dmask = pass == 2 ? 255u : 4095u;
         for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
         __syncthreads();
@@ -331,11 +380,71 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
     const uint32_t tau = prefix;               // key of the k-th largest score
     const uint32_t need_eq = need;             // how many entries equal to tau are selected
 
-    // ---- ordered emit: slot = #greater before + min(#equal before, need_eq) ----
-    uint32_t run_g = 0, run_e = 0;
     int tid_e = tid;
     asm volatile("" : "+v"(tid_e));                    // recompute positions here: the 4*NCH values computed
                                                        // for the load masks would otherwise stay live all along
+    // ---- ordered emit, common case: every entry equal to tau is selected (the k-th score is
+    // unique, or all of its ties fit).  Then "selected" is the single test key >= tau, and the
+    // slot of an entry is the number of selected entries ahead of it in position order, i.e.
+    // (chunk, wave, lane, element).  One packed wave scan per chunk pair, one scan over the 256
+    // (chunk, wave) cells, two barriers in all. ----
+    const uint32_t total_eq = hist[tau & 255u];        // the last histogram is still in place
+    if (total_eq == need_eq) {
+        uint32_t cw[NCH / 2], inc[NCH / 2];
+#pragma unroll
+        for (int j = 0; j < NCH / 2; ++j) {
+            uint32_t n0 = 0, n1 = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                n0 += key[2 * j][e] >= tau ? 1u : 0u;
+                n1 += key[2 * j + 1][e] >= tau ? 1u : 0u;
+            }
+            cw[j] = n0 | (n1 << 16);
+            inc[j] = wave_incl_scan(cw[j]);
+        }
+        if (lane == 63) {
+#pragma unroll
+            for (int j = 0; j < NCH / 2; ++j) cellsum[j][wave] = inc[j];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane L owns cells 4L..4L+3 = chunk L/4, waves 4(L%4)..+3
+            const int c = lane >> 2;
+            const u32x4 t4 = *(const u32x4 *)&cellsum[c >> 1][4 * (lane & 3)];
+            uint32_t v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (t4[j] >> (16 * (c & 1))) & 0xFFFFu;
+            const uint32_t own = v[0] + v[1] + v[2] + v[3];
+            const uint32_t ex = wave_incl_scan(own) - own;
+            u32x4 o4;
+            o4[0] = ex;
+            o4[1] = ex + v[0];
+            o4[2] = ex + v[0] + v[1];
+            o4[3] = ex + v[0] + v[1] + v[2];
+            *(u32x4 *)&cellbase[4 * lane] = o4;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (c * NT * 4 >= nv) continue;            // workgroup-uniform; nothing left in this chunk
+            const int p = (c * NT + tid_e) * 4;
+            uint32_t slot = cellbase[c * NW + wave] + (((inc[c >> 1] - cw[c >> 1]) >> (16 * (c & 1))) & 0xFFFFu);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (key[c][e] >= tau) {
+                    if (slot < (uint32_t)a.k_sel) {    // always true for a consistent select
+                        oidx[slot] = p + e;
+                        if (osel) osel[slot] = key_score(key[c][e]);
+                    }
+                    ++slot;
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- ordered emit, ties cut at the boundary: slot = #greater before + min(#equal before, need_eq) ----
+    uint32_t run_g = 0, run_e = 0;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         if (c * NT * 4 >= nv) continue;                // workgroup-uniform; nothing left in this chunk
@@ -413,8 +522,12 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     static hipError_t attr1024 = hipFuncSetAttribute((const void *)select_kernel<1024>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      (int)select_lds_bytes(select_cache_limit()));
+    constexpr int kRegHistBytes = kBins1 * 8 * (int)sizeof(uint32_t);   // spread first-digit histogram of the register form
+    static hipError_t attr_reg = hipFuncSetAttribute((const void *)select_reg_kernel<1024, 16>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kRegHistBytes);
     if (attr256 != hipSuccess) return attr256;
     if (attr1024 != hipSuccess) return attr1024;
+    if (attr_reg != hipSuccess) return attr_reg;
     if (max_row_len <= 8192)
         hipLaunchKernelGGL((select_kernel<256>), dim3((unsigned)n_rows), dim3(256), lds, st, a);
     else if (max_row_len <= select_cache_limit())
@@ -422,7 +535,7 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     else if (max_row_len <= 65536)
         // too long for the LDS cache, short enough for the registers of one workgroup (the decode
         // shape: few rows of 64K scores): read once, select in registers
-        hipLaunchKernelGGL((select_reg_kernel<1024, 16>), dim3((unsigned)n_rows), dim3(1024), 0, st, a);
+        hipLaunchKernelGGL((select_reg_kernel<1024, 16>), dim3((unsigned)n_rows), dim3(1024), kRegHistBytes, st, a);
     else
         hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);   // streams the row on every sweep
     return hipGetLastError();

@@ -180,6 +180,29 @@ def test_topk_tie_break_on_equal_scores(ic, oracle):
         assert np.all(idx[0, i, n:] == -1)
 
 
+@pytest.mark.parametrize("Lk", [3000, 9000, 40000, 70000])
+def test_topk_ties_cut_at_the_boundary_on_long_rows(ic, oracle, Lk):
+    # one head, one-hot q, keys from a handful of small integers: scores are exact on both sides
+    # and fall into a few large tie classes, so the k-th score has far more ties than fit and the
+    # lowest positions among them must win; every select variant (by row length) is covered
+    say("topk tie classes, Lk=%d" % Lk)
+    B, Tq, H, d, ks = 1, 3, 1, 64, 256
+    g = torch.Generator().manual_seed(Lk)
+    q = torch.zeros((B, Tq, H, d)); q[..., 3] = 1.0
+    k = torch.zeros((B, Lk, d)); k[0, :, 3] = torch.randint(0, 8, (Lk,), generator=g).float()
+    w = torch.ones((B, Tq, H))
+    p0 = Lk - Tq
+    idx = ic.indexer_topk(q.bfloat16().cuda(), k.bfloat16().cuda(), w.cuda(), ks, p0).cpu().numpy()
+    sc = oracle.indexer_scores(synth.bits(q.bfloat16()), synth.bits(k.bfloat16()), synth.bits(w), p0)
+    vals = k[0, :, 3].numpy()
+    for i in range(Tq):
+        nv = p0 + i + 1
+        assert parity.check_idx_row(idx[0, i], sc[0, i], nv, ks, oracle) == "tie"
+        # by hand: all 7s come first in position order; there are more of them than k
+        want = np.nonzero(vals[:nv] == 7)[0][:ks]
+        assert want.size == ks and np.array_equal(idx[0, i], want)
+
+
 def test_topk_monotone_scores(ic, oracle):
     # one head, one-hot q, keys increasing along that coordinate: scores increase with position,
     # so the last k visible positions win (the adversarial order for a streaming filter)
