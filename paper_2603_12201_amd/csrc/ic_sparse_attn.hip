@@ -346,8 +346,10 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     };
     auto ids_mask = [&](const Ids &d) { return rows_mask(__ballot(d.lo >= 0), __ballot(d.hi >= 0)); };
 
-    // Q as the B operand: lane (head 16 hb + l16, features 8 g..) for both head blocks
-    bf16x8 qreg[2][KS];
+    // Q as the B operand: lane (head 16 hb + l16, features 8 g..) for both head blocks.  All of its
+    // loads are issued before anything waits for one of them, and the ids and rows of the first
+    // tile are requested in their shadow.
+    u32x4 qraw[2][KS];
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb) {
         const int head = 16 * hb + l16;
@@ -355,15 +357,10 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         const unsigned short *qp = (const unsigned short *)a.Q + (qrow * a.H_q + (ok ? head : 0)) * D_QK + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            u32x4 raw = u32x4{0u, 0u, 0u, 0u};
-            if (ok) raw = *(const u32x4 *)(qp + 32 * ks);
-            // pin Q to the accumulation half of the register file (MFMA reads B operands from
-            // there directly): the vector half is needed for the gather and the LDS operands
-            asm volatile("" : "+a"(raw));
-            qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+            qraw[hb][ks] = u32x4{0u, 0u, 0u, 0u};
+            if (ok) qraw[hb][ks] = *(const u32x4 *)(qp + 32 * ks);
         }
     }
-
     f32x16 oacc[NBW];
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
@@ -394,10 +391,22 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     };
     unsigned vm_cur, vm_n1;
     Ids ids_n2;
+    bf16x8 qreg[2][KS];
     {
         const Ids d0 = fetch_ids(0), d1 = fetch_ids(1);
         ids_n2 = fetch_ids(2);
         gload(d0);
+        __builtin_amdgcn_sched_barrier(0);
+        // pin Q to the accumulation half of the register file (MFMA reads B operands from there
+        // directly): the vector half is needed for the gather and the LDS operands
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = qraw[hb][ks];
+                asm volatile("" : "+a"(raw));
+                qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+            }
         vm_cur = ids_mask(d0);
         vm_n1 = ids_mask(d1);
         const unsigned short *pl = row_ptr(d1.lo), *ph = row_ptr(d1.hi);
