@@ -316,33 +316,54 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     const int l16 = lane & 15, g = lane >> 4;
     const int l32 = lane & 31, hh = lane >> 5;
     const int gr = lane >> 3, gp = lane & 7;              // gather role: row (and row + 8), 16-byte piece
-    const int64_t qrow = blockIdx.x;
-    const int b = (int)(qrow / a.Tq);
     const int sp = SPLIT ? (int)blockIdx.y : 0;
     const int slot0 = SPLIT ? sp * a.split_len : 0;
     const int slot1 = SPLIT ? min(slot0 + a.split_len, a.k_sel) : a.k_sel;
     const int ntiles = (slot1 - slot0 + kSlabTile - 1) / kSlabTile;
+    // Chained form (whole selections of at least three tiles, grid smaller than the number of
+    // queries): the workgroup walks queries blockIdx.x, + gridDim.x, ... and treats their tiles as
+    // one stream, so that the gather and staging of the next query's first tiles and the load of
+    // its Q run under the last steps and the output stores of the current one.
+    const int64_t nq = (int64_t)a.B * a.Tq;
+    const bool chain = !SPLIT && ntiles >= 3 && (int64_t)gridDim.x < nq;   // workgroup-uniform
+    int64_t qrow = blockIdx.x;
+    int64_t qnext = chain ? qrow + gridDim.x : nq;        // >= nq: this is the workgroup's last query
 
-    const int32_t *idx_row = a.idx + qrow * a.k_sel;
-    const unsigned short *kv_seq = (const unsigned short *)a.KV + (PG && a.pv.page_table ? 0 : (int64_t)b * a.Lk * a.row_elems);
-    const int Lk_b = PG && a.pv.seq_lens ? min(a.pv.seq_lens[b], a.Lk) : a.Lk;     // ragged cache: rows of this sequence
+    // what the gather needs to know about a query: its index row, its cache and its length
+    struct Src { const int32_t *idx_row; const unsigned short *kv; int b, len; bool live; };
+    auto src_of = [&](int64_t q) {
+        Src r;
+        r.live = q < nq;
+        const int64_t qq = r.live ? q : (int64_t)blockIdx.x;          // a dead source still reads valid memory
+        r.b = (int)(qq / a.Tq);
+        r.idx_row = a.idx + qq * a.k_sel;
+        r.kv = (const unsigned short *)a.KV + (PG && a.pv.page_table ? 0 : (int64_t)r.b * a.Lk * a.row_elems);
+        r.len = PG && a.pv.seq_lens ? min(a.pv.seq_lens[r.b], a.Lk) : a.Lk;   // ragged cache: rows of this sequence
+        return r;
+    };
+    Src cs = src_of(qrow), ns = src_of(qnext);            // current and next query
 
     // Loads inside the tile loop are unconditional (clamped addresses, result discarded when out
     // of range): the wait counters are positional, and a load that may or may not have been
     // issued would force every later wait down to "everything has landed".
     struct Ids { int32_t lo, hi; };                       // validated ids of tile rows 16w+gr and 16w+gr+8
+    // tile `it` of the stream: tiles at or beyond ntiles are the first tiles of the next query
     auto fetch_ids = [&](int it) -> Ids {
-        const int s_lo = slot0 + it * kSlabTile + 16 * wave + gr, s_hi = s_lo + 8;
-        const int32_t v_lo = idx_row[min(s_lo, a.k_sel - 1)], v_hi = idx_row[min(s_hi, a.k_sel - 1)];
+        const bool nx = !SPLIT && it >= ntiles;
+        const Src &q = nx ? ns : cs;
+        const int s_lo = slot0 + (nx ? it - ntiles : it) * kSlabTile + 16 * wave + gr, s_hi = s_lo + 8;
+        const int32_t v_lo = q.idx_row[min(s_lo, a.k_sel - 1)], v_hi = q.idx_row[min(s_hi, a.k_sel - 1)];
         Ids r;
-        r.lo = (s_lo < slot1 && v_lo >= 0 && v_lo < Lk_b) ? v_lo : -1;
-        r.hi = (s_hi < slot1 && v_hi >= 0 && v_hi < Lk_b) ? v_hi : -1;
+        // no short-circuit: one basic block, so the loaded ids are not waited for before their use
+        r.lo = ((int)q.live & (int)(s_lo < slot1) & (int)(v_lo >= 0) & (int)(v_lo < q.len)) ? v_lo : -1;
+        r.hi = ((int)q.live & (int)(s_hi < slot1) & (int)(v_hi >= 0) & (int)(v_hi < q.len)) ? v_hi : -1;
         return r;
     };
-    auto row_ptr = [&](int32_t v) {
+    auto row_ptr = [&](int32_t v, int it) {
+        const Src &q = (!SPLIT && it >= ntiles) ? ns : cs;
         // empty slots read row 0 of the cache (never a page-table entry: the sequence may own no page)
-        const int64_t prow = v < 0 ? 0 : (PG && a.pv.page_table ? paged_row(a.pv, b, v) : (int64_t)v);
-        return kv_seq + prow * a.row_elems + 8 * gp;
+        const int64_t prow = v < 0 ? 0 : (PG && a.pv.page_table ? paged_row(a.pv, q.b, v) : (int64_t)v);
+        return q.kv + prow * a.row_elems + 8 * gp;
     };
     auto ids_mask = [&](const Ids &d) { return rows_mask(__ballot(d.lo >= 0), __ballot(d.hi >= 0)); };
 
@@ -350,17 +371,20 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     // loads are issued before anything waits for one of them, and the ids and rows of the first
     // tile are requested in their shadow.
     u32x4 qraw[2][KS];
+    auto load_q = [&](int64_t q) {
 #pragma unroll
-    for (int hb = 0; hb < 2; ++hb) {
-        const int head = 16 * hb + l16;
-        const bool ok = head < a.H_q;
-        const unsigned short *qp = (const unsigned short *)a.Q + (qrow * a.H_q + (ok ? head : 0)) * D_QK + 8 * g;
+        for (int hb = 0; hb < 2; ++hb) {
+            const int head = 16 * hb + l16;
+            const bool ok = head < a.H_q;
+            const unsigned short *qp = (const unsigned short *)a.Q + (q * a.H_q + (ok ? head : 0)) * D_QK + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            qraw[hb][ks] = u32x4{0u, 0u, 0u, 0u};
-            if (ok) qraw[hb][ks] = *(const u32x4 *)(qp + 32 * ks);
+            for (int ks = 0; ks < KS; ++ks) {
+                qraw[hb][ks] = u32x4{0u, 0u, 0u, 0u};
+                if (ok) qraw[hb][ks] = *(const u32x4 *)(qp + 32 * ks);
+            }
         }
-    }
+    };
+    load_q(qrow);
     f32x16 oacc[NBW];
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
@@ -384,21 +408,17 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     // The gather registers are refilled chunk by chunk: as soon as chunk ks of tile t+1 has been
     // stored to LDS, the same registers receive chunk ks of tile t+2.
     u32x4 cur[KS];
-    auto gload = [&](const Ids &d) {
-        const unsigned short *pl = row_ptr(d.lo), *ph = row_ptr(d.hi);
+    auto gload = [&](const Ids &d, int it) {
+        const unsigned short *pl = row_ptr(d.lo, it), *ph = row_ptr(d.hi, it);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
     };
     unsigned vm_cur, vm_n1;
     Ids ids_n2;
     bf16x8 qreg[2][KS];
-    {
-        const Ids d0 = fetch_ids(0), d1 = fetch_ids(1);
-        ids_n2 = fetch_ids(2);
-        gload(d0);
-        __builtin_amdgcn_sched_barrier(0);
-        // pin Q to the accumulation half of the register file (MFMA reads B operands from there
-        // directly): the vector half is needed for the gather and the LDS operands
+    // pin Q to the accumulation half of the register file (MFMA reads B operands from there
+    // directly): the vector half is needed for the gather and the LDS operands
+    auto pin_q = [&]() {
 #pragma unroll
         for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
@@ -407,9 +427,68 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
                 asm volatile("" : "+a"(raw));
                 qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
             }
+    };
+    // Chained form: Q of the next query goes straight into the accumulation registers while the
+    // outputs of the current one are stored.  The compiler does not count these loads, which only
+    // makes its own waits conservative; settle_q waits for them and ties every later use to that wait.
+    auto load_q_direct = [&](int64_t q) {
+        // the lane's offset into Q is recomputed from the lane id here: kept live across the tile
+        // loop it would be spilled, and its reload would wait behind the gathers in flight
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int hd = ln & 15, gq = ln >> 4;
+        const unsigned short *q0 = (const unsigned short *)a.Q + q * a.H_q * D_QK + 8 * gq;
+        if (a.H_q >= 32) {                                // workgroup-uniform: every lane has a head
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const unsigned short *src = q0 + (16 * hb + hd) * D_QK + 32 * ks;
+                    u32x4 raw;
+                    asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(raw) : "v"(src));
+                    qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+                }
+        } else {
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                const int head = 16 * hb + hd;
+                const bool ok = head < a.H_q;
+                u32x4 raw[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) raw[ks] = u32x4{0u, 0u, 0u, 0u};
+                if (ok) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        const unsigned short *src = q0 + head * D_QK + 32 * ks;
+                        asm volatile("global_load_dwordx4 %0, %1, off" : "+a"(raw[ks]) : "v"(src));
+                    }
+                }
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw[ks]);
+            }
+        }
+    };
+    auto settle_q = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)");
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = __builtin_bit_cast(u32x4, qreg[hb][ks]);
+                asm volatile("" : "+a"(raw));
+                qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+            }
+    };
+    int g0 = 0;                                           // stream position of the query's tile 0 (buffer parity)
+    {
+        const Ids d0 = fetch_ids(0), d1 = fetch_ids(1);
+        ids_n2 = fetch_ids(2);
+        gload(d0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        pin_q();
         vm_cur = ids_mask(d0);
         vm_n1 = ids_mask(d1);
-        const unsigned short *pl = row_ptr(d1.lo), *ph = row_ptr(d1.hi);
+        const unsigned short *pl = row_ptr(d1.lo, 1), *ph = row_ptr(d1.hi, 1);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             *(u32x4 *)(tbuf + st_off + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
@@ -428,7 +507,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     auto step = [&](int it, auto have_prev, auto have_cur, auto stage_next, auto load_next2) {
         constexpr bool kPrev = decltype(have_prev)::value, kCur = decltype(have_cur)::value;
         constexpr bool kStage = decltype(stage_next)::value, kLoad = decltype(load_next2)::value;
-        const int buf = it & 1;
+        const int buf = (g0 + it) & 1;
         Ids ids_n3 = ids_n2;
         if constexpr (kCur) ids_n3 = fetch_ids(it + 3);
         const unsigned char *tb = tbuf + buf * TBUFB;                 // tile it
@@ -564,7 +643,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         // O += P V for tile it-1, with the staging of tile it+1 (nobody reads that buffer any more)
         // and the gather of tile it+2 issued in the shadow of the MFMAs
         unsigned char *tn = tbuf + (buf ^ 1) * TBUFB + st_off;
-        const unsigned short *pl = row_ptr(ids_n2.lo), *ph = row_ptr(ids_n2.hi);
+        const unsigned short *pl = row_ptr(ids_n2.lo, it + 2), *ph = row_ptr(ids_n2.hi, it + 2);
         auto stage = [&](int ks) {
             if constexpr (kStage) {
                 if (ks < KS) {
@@ -598,15 +677,61 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) stage(ks);
         }
-        vm_cur = vm_n1;
-        vm_n1 = vm_n2;
-        ids_n2 = ids_n3;
+        if constexpr (kCur) {                             // the drain step leaves the stream where it is
+            vm_cur = vm_n1;
+            vm_n1 = vm_n2;
+            ids_n2 = ids_n3;
+        }
     };
 
-    {
-        constexpr std::true_type T{};
-        constexpr std::false_type F{};
-        // step 0 has no previous tile, step ntiles has no current one
+    // ---- epilogue of a query: combine the producers' row sums, normalise, store ----
+    auto finish = [&]() {
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+            const float l = xsum16_32(l_own[hb]);
+            // bring the wave's sum to the common reference before publishing it
+            const float f = (m_all[hb] == -INFINITY) ? 0.f : fast_exp2(m_ref[hb] - m_all[hb]);
+            if (g == 0) lbuf[wave * 32 + 16 * hb + l16] = l * f;
+        }
+        __syncthreads();
+        const float l_head = lbuf[l32] + lbuf[32 + l32] + lbuf[64 + l32] + lbuf[96 + l32];   // head l32
+        const float m_head = m_c;
+        if constexpr (SPLIT) {
+            // partial of this split: accumulators and row sum in the reference m_head
+            if (wave == 0 && hh == 0 && l32 < a.H_q) {
+                float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + l32) * 2;
+                ml[0] = m_head;
+                ml[1] = l_head;
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);
+                if (hq >= a.H_q) continue;
+                float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + 32 * wave + l32;
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = oacc[nb][i];
+            }
+        } else {
+            if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
+                a.lse[qrow * a.H_q + l32] =
+                    (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);   // O row (head) of accumulator element i
+                const float l = __shfl(l_head, hq);
+                if (hq >= a.H_q) continue;
+                const float inv = (l > 0.f) ? 1.f / l : 0.f;
+                __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + 32 * wave + l32;
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
+            }
+        }
+    };
+
+    constexpr std::true_type T{};
+    constexpr std::false_type F{};
+    if (!chain) {
+        // one query (or one split of it): step 0 has no previous tile, step ntiles has no current one
         if (ntiles == 1) {
             step(0, F, T, F, F);
         } else if (ntiles == 2) {
@@ -622,47 +747,41 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             step(it, T, T, F, F);
         }
         step(ntiles, T, F, F, F);
-    }
-
-    // ---- epilogue: combine the producers' row sums, normalise, store ----
-#pragma unroll
-    for (int hb = 0; hb < 2; ++hb) {
-        const float l = xsum16_32(l_own[hb]);
-        // bring the wave's sum to the common reference before publishing it
-        const float f = (m_all[hb] == -INFINITY) ? 0.f : fast_exp2(m_ref[hb] - m_all[hb]);
-        if (g == 0) lbuf[wave * 32 + 16 * hb + l16] = l * f;
-    }
-    __syncthreads();
-    const float l_head = lbuf[l32] + lbuf[32 + l32] + lbuf[64 + l32] + lbuf[96 + l32];   // head l32
-    const float m_head = m_c;
-    if constexpr (SPLIT) {
-        // partial of this split: accumulators and row sum in the reference m_head
-        if (wave == 0 && hh == 0 && l32 < a.H_q) {
-            float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + l32) * 2;
-            ml[0] = m_head;
-            ml[1] = l_head;
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);
-            if (hq >= a.H_q) continue;
-            float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + 32 * wave + l32;
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = oacc[nb][i];
-        }
+        finish();
         return;
     }
-    if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
-        a.lse[qrow * a.H_q + l32] = (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
+    if constexpr (!SPLIT) {
+        // Chained queries.  The last two steps of a query stage and gather the first tiles of the
+        // next one (dead tiles after the workgroup's last query: row 0, masked), so a query ends
+        // in exactly the state the prologue sets up: tile 0 in LDS, tile 1 in the gather
+        // registers, ids of tile 2 at hand.
+        for (;;) {
+            step(0, F, T, T, T);
+#pragma unroll 1
+            for (int it = 1; it < ntiles; ++it) step(it, T, T, T, T);
+            step(ntiles, T, F, F, F);
+            const bool more = qnext < nq;
+            if (more) load_q_direct(qnext);               // lands while the outputs are stored
+            finish();
+            if (!more) break;
+            qrow = qnext;
+            qnext += gridDim.x;
+            cs = ns;
+            ns = src_of(qnext);
+            g0 = (g0 + ntiles) & 1;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);   // O row (head) of accumulator element i
-        const float l = __shfl(l_head, hq);
-        if (hq >= a.H_q) continue;
-        const float inv = (l > 0.f) ? 1.f / l : 0.f;
-        __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + 32 * wave + l32;
+            for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-        for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
+                for (int i = 0; i < 16; ++i) oacc[nb][i] = 0.f;
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb) {
+                m_all[hb] = -INFINITY;
+                m_ref[hb] = -INFINITY;
+                l_own[hb] = 0.f;
+            }
+            m_c = -INFINITY;
+            settle_q();
+        }
     }
 }
 
@@ -721,7 +840,19 @@ hipError_t launch_slab_t(const AttnArgs &a, size_t lds, hipStream_t st)
     static hipError_t attr = hipFuncSetAttribute((const void *)attn_slab_kernel<D_QK, D_V, PG, SPLIT>,
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (attr != hipSuccess) return attr;
-    dim3 grid((unsigned)((int64_t)a.B * a.Tq), (unsigned)(SPLIT ? a.n_splits : 1));
+    int64_t wgs = (int64_t)a.B * a.Tq;
+    if (!SPLIT && a.k_sel > 2 * kSlabTile) {
+        // whole selections of three or more tiles: one workgroup per CU walks a chain of queries
+        static int n_cu = 0;
+        if (n_cu == 0) {
+            int dev = 0, v = 0;
+            if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+                return hipErrorInvalidDevice;
+            n_cu = v;
+        }
+        if (wgs > n_cu) wgs = n_cu;
+    }
+    dim3 grid((unsigned)wgs, (unsigned)(SPLIT ? a.n_splits : 1));
     hipLaunchKernelGGL((attn_slab_kernel<D_QK, D_V, PG, SPLIT>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
