@@ -213,11 +213,76 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     const uint32_t tau = prefix;               // key of the k-th largest score
     const uint32_t need_eq = need;             // how many entries equal to tau are selected
 
-    // ---- ordered emit: slot = #greater before + min(#equal before, need_eq) ----
+    // ---- ordered emit, common case: the row is cached, has at most kFastChunks sweeps, and every
+    // entry equal to tau is selected (the k-th score is unique, or all of its ties fit).  Then
+    // "selected" is the single test key >= tau and the slot of an entry is the number of selected
+    // entries ahead of it in (chunk, wave, lane, element) order: one packed wave scan per chunk
+    // pair, one scan over the (chunk, wave) cells, two barriers in all. ----
+    constexpr int kFastChunks = 8;
+    const int nchunks = (nv + 4 * NT - 1) / (4 * NT);
+    const uint32_t total_eq = hist1[tau & 255u];       // the last histogram is still in place
+    if (cached && nchunks <= kFastChunks && total_eq == need_eq) {
+        uint32_t *cellsum = hist1 + 256;               // [kFastChunks / 2][NW]  (beyond the 256 live bins)
+        uint32_t *cellbase = cellsum + kFastChunks / 2 * NW;   // [kFastChunks * NW]
+        uint32_t cw[kFastChunks / 2], inc[kFastChunks / 2];
+#pragma unroll
+        for (int j = 0; j < kFastChunks / 2; ++j) {
+            uint32_t n2[2] = {0u, 0u};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int p = (2 * j + h) * 4 * NT + 4 * tid;
+                if (2 * j + h < nchunks) {             // workgroup-uniform
+                    const u32x4 k4 = get_key4(p);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) n2[h] += (p + e < nv && k4[e] >= tau) ? 1u : 0u;
+                }
+            }
+            cw[j] = n2[0] | (n2[1] << 16);
+            inc[j] = wave_incl_scan(cw[j]);
+        }
+        if (lane == 63) {                              // (the cells lie beyond the 256 bins still being read)
+#pragma unroll
+            for (int j = 0; j < kFastChunks / 2; ++j) cellsum[j * NW + wave] = inc[j];
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // cells in (chunk, wave) order, 64 at a time
+            uint32_t carry = 0;
+#pragma unroll
+            for (int base = 0; base < kFastChunks * NW; base += 64) {
+                const int cell = base + lane, c = cell / NW, w = cell % NW;
+                const bool real = cell < kFastChunks * NW;
+                const uint32_t v = real ? (cellsum[(c >> 1) * NW + w] >> (16 * (c & 1))) & 0xFFFFu : 0u;
+                const uint32_t in = wave_incl_scan(v);
+                if (real) cellbase[cell] = carry + in - v;
+                carry += __shfl(in, 63);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < kFastChunks; ++c) {
+            if (c >= nchunks) continue;                // workgroup-uniform
+            const int p = c * 4 * NT + 4 * tid;
+            const u32x4 k4 = get_key4(p);
+            uint32_t slot = cellbase[c * NW + wave] + (((inc[c >> 1] - cw[c >> 1]) >> (16 * (c & 1))) & 0xFFFFu);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (p + e < nv && k4[e] >= tau) {
+                    if (slot < (uint32_t)a.k_sel) {    // always true for a consistent select
+                        oidx[slot] = p + e;
+                        if (osel) osel[slot] = key_score(k4[e]);
+                    }
+                    ++slot;
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- ordered emit, general case: slot = #greater before + min(#equal before, need_eq) ----
     // A thread owns 4 consecutive positions; counts of greater / equal entries travel packed in
     // one word (equal << 16 | greater) through a wave scan and a 16-entry scan of the wave totals.
     uint32_t run = 0;                                  // packed counts of all previous chunks
-    const int nchunks = (nv + 4 * NT - 1) / (4 * NT);
 #pragma unroll 1
     for (int c = 0; c < nchunks; ++c) {
         const int p = c * 4 * NT + 4 * tid;
