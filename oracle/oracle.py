@@ -235,6 +235,70 @@ def pattern_search_exhaustive(S, n_full):
     return best, arg
 
 
+# ---- greedy layer selection (Alg. 1, Sec. 3.2) with a surrogate loss -----------------------
+
+def pattern_loss_from_similarity(S, mask):
+    """Stand-in for EvalLoss(M, D, c) of Alg. 1 (the language-model loss needs the model): the
+    attention-output error of pattern c against the all-Full stack,
+        loss(c) = 1/N * sum_l (1 - sim_l(c)),   sim_l(c) = mean per-token cosine of layer l's
+    output under c and under all-Full.  With layers whose inputs do not depend on earlier outputs
+    (the attention-only stack of this build) sim_l(c) = S[l, src(l)], so a Full layer adds 0."""
+    N = len(mask)
+    return sum(1.0 - float(S[l, source_layer(mask, l)]) for l in range(N) if not mask[l]) / N
+
+
+def pattern_loss_forward(layers, full_mask, k_sel, q_pos0, d_v, v_off, sm_scale, O_ref):
+    """The same loss measured the way Alg. 1 measures it: run the whole stack under the pattern
+    (forward_stack) and compare every layer's output with the all-Full run's O_ref (fp64 arrays)."""
+    outs, _, _ = forward_stack(layers, full_mask, k_sel, q_pos0, d_v, v_off, sm_scale)
+    tot = 0.0
+    for O, R in zip(outs, O_ref):
+        a = O.reshape(-1, O.shape[-2] * O.shape[-1])
+        b = R.reshape(a.shape)
+        na, nb = np.linalg.norm(a, axis=1), np.linalg.norm(b, axis=1)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            cs = (a * b).sum(1) / (na * nb)
+        cs = np.where((na == 0) & (nb == 0), 1.0, np.where((na == 0) | (nb == 0), 0.0, cs))
+        tot += 1.0 - cs.mean()
+    return tot / len(layers)
+
+
+def greedy_search(eval_loss, n_layers, n_shared, n_blocks=1):
+    """Alg. 1: start from all-Full; n_shared times, try every remaining candidate layer as Shared,
+    evaluate the loss of the resulting pattern and commit the flip with the lowest loss (ties:
+    the lowest layer).  Layer 0 is never a candidate.  n_blocks > 1 is the pipeline-parallel
+    variant of Sec. 3.2 (Complexity): the layers are cut into n_blocks contiguous blocks of
+    ceil(N / n_blocks), the first layer of a block stays Full, and within one step the blocks are
+    searched one after the other, each committing its own best flip before the next is searched.
+    eval_loss(mask) -> float.  Returns (mask, order of flipped layers, loss after each flip)."""
+    N = n_layers
+    if not (0 <= n_shared <= N - 1) or n_blocks < 1:
+        raise ValueError("need 0 <= n_shared <= N-1 and n_blocks >= 1")
+    size = -(-N // n_blocks)
+    blocks = [list(range(b0, min(b0 + size, N))) for b0 in range(0, N, size)]
+    mask = [True] * N
+    cand = [set(b[1:]) for b in blocks]                 # a block's first layer is fixed Full
+    if n_shared > sum(len(c) for c in cand):
+        raise ValueError("more Shared layers asked for than candidates exist")
+    order, curve = [], []
+    while len(order) < n_shared:
+        for c in cand:
+            if len(order) == n_shared or not c:
+                continue
+            best, arg = None, None
+            for l in sorted(c):
+                trial = list(mask)
+                trial[l] = False
+                v = eval_loss(trial)
+                if best is None or v < best:
+                    best, arg = v, l
+            mask[arg] = False
+            c.remove(arg)
+            order.append(arg)
+            curve.append(best)
+    return mask, order, curve
+
+
 # ---- pattern strings and the layer loop (Fig. 2, Sec. 3 Overview) -------------
 
 def pattern_from_string(s):
