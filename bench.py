@@ -21,7 +21,7 @@ sys.path.insert(0, ROOT)
 
 # HBM bytes per launch of the kernels at the configs[3] per-layer shape, from rocprofv3 FETCH_SIZE +
 # WRITE_SIZE scaled by a plain-copy reference (profiles/attn_score_select_prefill32k_hbm_traffic.txt).
-MEASURED_TRAFFIC_BYTES = {"sparse_attn": 19.33e9 + 1.48e9, "indexer_score": 0.427e9 + 0.543e9,
+MEASURED_TRAFFIC_BYTES = {"sparse_attn": 18.99e9 + 1.07e9, "indexer_score": 0.426e9 + 0.537e9,
                           "topk_select": 0.672e9 + 0.067e9}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
@@ -154,6 +154,7 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--greedy-layers", type=int, default=6)
     ap.add_argument("--no-overlap", action="store_true", help="skip the cross-layer overlap diagnostic arm")
     ap.add_argument("--overlap-layers", type=int, default=48)
     ap.add_argument("--similarity-layers", type=int, default=8)
@@ -375,6 +376,37 @@ def main():
                 "dp_pattern": "".join("F" if m else "S" for m in mask), "dp_total": total, "dp_host_ms": ms_dp}
             del at, o_own, o_b
         del idxs
+
+    # ---------------- greedy layer selection by forward passes (Alg. 1 with the surrogate loss) ----------------
+    if not args.no_overlap and args.greedy_layers >= 2:
+        n_g = args.greedy_layers
+        k_g = n_g // 2
+        log("greedy search arm: %d layers, %d flips" % (n_g, k_g))
+        gcfg = synth.config("c3")
+        at2 = [synth.attn_layer(gcfg, l, device="cuda") for l in range(2)]
+        lay_g = []
+        for l, ixl in enumerate(synth.chain_indexer_layers(gcfg, n_g, device="cuda")):
+            d = dict(ixl)
+            d.update(at2[l % 2])                                  # the big Q/KV inputs are cycled, the indexer inputs are not
+            lay_g.append(d)
+        o_shape = (gcfg["B"], gcfg["Tq"], gcfg["H_q"], gcfg["d_v"])
+        outs_g = [torch.empty(o_shape, dtype=torch.bfloat16, device="cuda") for _ in range(n_g)]
+        arr_g = ic.make_layers(lay_g, gcfg["k_sel"], 0, gcfg["d_v"], gcfg["v_off"], synth.sm_scale(gcfg), outs_g)
+        ws_g = torch.empty(max(int(ic.lib().ic_greedy_search_forward_workspace(arr_g, n_g)), 256), dtype=torch.uint8, device="cuda")
+        cache_g = torch.empty((gcfg["B"], gcfg["Tq"], gcfg["k_sel"]), dtype=torch.int32, device="cuda")
+        ic.forward_stack(arr_g, [True] * n_g, cache_g, ws_g)
+        torch.cuda.synchronize()
+        ref_g = [o.clone() for o in outs_g]
+        t0 = time.perf_counter()
+        gmask, gorder, gcurve = ic.greedy_search_forward(arr_g, k_g, ref_g, cache_g, workspace=ws_g)
+        ms_g = (time.perf_counter() - t0) * 1e3
+        passes = sum(n_g - 1 - s for s in range(k_g))
+        arms["greedy_search"] = {
+            "layers": n_g, "flips": k_g, "forward_passes": passes, "total_ms": ms_g, "ms_per_forward_pass": ms_g / passes,
+            "tokens_per_s_inside_search": passes * gcfg["Tq"] / (ms_g * 1e-3),
+            "order": gorder, "loss_curve": gcurve, "pattern": "".join("F" if m else "S" for m in gmask),
+            "loss": "1/N sum_l (1 - mean per-token cosine of layer l's output under the pattern vs all-Full)"}
+        del lay_g, outs_g, ref_g, at2, arr_g
 
     out = {
         "metric": "prefill & decode tokens/s, 48-layer DSA stack L=32K, 1-in-4 Full vs all-Full",

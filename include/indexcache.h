@@ -229,6 +229,50 @@ ic_status ic_similarity_matrix(const ic_layer *layers, int32_t n_layers, const i
                                void *workspace, size_t workspace_bytes, void *stream);
 ic_status ic_pattern_search_dp(const double *S, int32_t n_layers, int32_t n_full, uint8_t *full_mask, double *total);
 
+/*
+ * Greedy layer selection (paper Alg. 1, Sec. 3.2) with a surrogate loss.
+ *
+ * The algorithm starts from all-Full and, n_shared times, flips to Shared the candidate layer whose
+ * flip gives the lowest EvalLoss (ties: the lowest layer); layer 0 is never a candidate.  n_blocks
+ * > 1 is the pipeline-parallel variant of the same section: contiguous blocks of
+ * ceil(n_layers / n_blocks) layers, a block's first layer stays Full, and within one step the
+ * blocks are searched in order, each committing its own best flip before the next is searched.
+ *
+ * EvalLoss in the paper is the language-model loss on calibration batches, which needs the model.
+ * Its stand-in here is the attention-output error of a pattern against the all-Full stack:
+ *     loss(c) = 1/N sum_l (1 - sim_l(c)),
+ *     sim_l(c) = mean per-token cosine (as ic_cosine_rows) of layer l's output under c and under F^N
+ *
+ * ic_pattern_loss: that loss for one pattern, measured the way Alg. 1 measures it: the whole stack
+ * is run under full_mask (ic_forward_stack: outputs land in layers[l].O, idx_cache is overwritten)
+ * and every layer's output is compared with O_ref[l], the output of the all-Full run.  O_ref: HOST
+ * array of n_layers DEVICE tensors [B,Tq,H_q,d_v] bf16, none of them a layer's own O; loss: device
+ * double, out.  Layers of one attention shape, n_layers <= IC_MAX_OVERLAP_LAYERS.  Asynchronous.
+ *
+ * ic_greedy_search_forward: Alg. 1 driven by ic_pattern_loss, one forward pass of the stack per
+ * candidate (n_layers (n_layers - 1) / 2 passes for a full search with one block).  The host has to
+ * read the candidates' losses to choose, so this call SYNCHRONISES `stream` once per search step.
+ *
+ * ic_pattern_search_greedy (host only): the same search on a similarity matrix S as
+ * ic_similarity_matrix produces it (HOST [n_layers, n_layers] double, j < i read), with
+ * sim_l(c) = S[l][src(l)], which is what the forward passes measure when a layer's inputs do not
+ * depend on earlier layers' outputs (the attention-only stack).
+ *
+ * Outputs (host): full_mask [n_layers]; order [n_shared], nullable: the flipped layers in commit
+ * order; loss_curve [n_shared], nullable: the loss after each commit.
+ * Errors: IC_ERR_NULL, IC_ERR_SHAPE (n_shared > candidates, bad block count, layer shapes),
+ * IC_ERR_PATTERN never (the search keeps layer 0 Full), IC_ERR_WORKSPACE, IC_ERR_HIP.
+ */
+ic_status ic_pattern_search_greedy(const double *S, int32_t n_layers, int32_t n_shared, int32_t n_blocks,
+                                   uint8_t *full_mask, int32_t *order, double *loss_curve);
+size_t ic_pattern_loss_workspace(const ic_layer *layers, int32_t n_layers);
+ic_status ic_pattern_loss(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const void *const *O_ref,
+                          int32_t *idx_cache, double *loss, void *workspace, size_t workspace_bytes, void *stream);
+size_t ic_greedy_search_forward_workspace(const ic_layer *layers, int32_t n_layers);
+ic_status ic_greedy_search_forward(const ic_layer *layers, int32_t n_layers, int32_t n_shared, int32_t n_blocks,
+                                   const void *const *O_ref, int32_t *idx_cache, uint8_t *full_mask, int32_t *order,
+                                   double *loss_curve, void *workspace, size_t workspace_bytes, void *stream);
+
 #define IC_MAX_OVERLAP_LAYERS 128
 #define IC_MAX_OVERLAP_LK (1 << 20)
 size_t ic_topk_overlap_workspace(int32_t n_layers);

@@ -84,6 +84,17 @@ def lib():
         L.ic_similarity_matrix_workspace.argtypes = [C.POINTER(Layer), i32]
         L.ic_similarity_matrix.restype = C.c_int
         L.ic_similarity_matrix.argtypes = [C.POINTER(Layer), i32, C.POINTER(vp), vp, vp, sz, vp]
+        L.ic_pattern_search_greedy.restype = C.c_int
+        L.ic_pattern_search_greedy.argtypes = [C.POINTER(C.c_double), i32, i32, i32, C.c_char_p, C.POINTER(i32), C.POINTER(C.c_double)]
+        L.ic_pattern_loss_workspace.restype = sz
+        L.ic_pattern_loss_workspace.argtypes = [C.POINTER(Layer), i32]
+        L.ic_pattern_loss.restype = C.c_int
+        L.ic_pattern_loss.argtypes = [C.POINTER(Layer), i32, C.c_char_p, C.POINTER(vp), vp, vp, vp, sz, vp]
+        L.ic_greedy_search_forward_workspace.restype = sz
+        L.ic_greedy_search_forward_workspace.argtypes = [C.POINTER(Layer), i32]
+        L.ic_greedy_search_forward.restype = C.c_int
+        L.ic_greedy_search_forward.argtypes = [C.POINTER(Layer), i32, i32, i32, C.POINTER(vp), vp, C.c_char_p, C.POINTER(i32),
+                                               C.POINTER(C.c_double), vp, sz, vp]
         L.ic_pattern_search_dp.restype = C.c_int
         L.ic_pattern_search_dp.argtypes = [C.POINTER(C.c_double), i32, i32, C.c_char_p, C.POINTER(C.c_double)]
         L.ic_topk_overlap_workspace.restype = sz
@@ -391,6 +402,53 @@ def pattern_search_dp(S, n_full):
     total = C.c_double(0.0)
     _check(lib().ic_pattern_search_dp(flat, n, n_full, buf, C.byref(total)))
     return [b != 0 for b in buf.raw[:n]], float(total.value)
+
+
+def pattern_search_greedy(S, n_shared, n_blocks=1):
+    """ic_pattern_search_greedy (host): Alg. 1 on a similarity matrix.  Returns (mask as list of
+    bools, True = Full; flipped layers in commit order; loss after each commit)."""
+    rows = [list(map(float, r)) for r in S]
+    n = len(rows)
+    flat = (C.c_double * (n * n))(*[rows[i][j] for i in range(n) for j in range(n)])
+    buf = C.create_string_buffer(max(n, 1))
+    order = (C.c_int32 * max(n_shared, 1))()
+    curve = (C.c_double * max(n_shared, 1))()
+    _check(lib().ic_pattern_search_greedy(flat, n, n_shared, n_blocks, buf, order, curve))
+    return [b != 0 for b in buf.raw[:n]], list(order[:n_shared]), list(curve[:n_shared])
+
+
+def pattern_loss(layer_arr, full_mask, O_ref, idx_cache, workspace=None, stream=None):
+    """ic_pattern_loss: run the stack under full_mask and compare with the all-Full outputs O_ref
+    (list of device tensors).  Returns the loss as a device float64 scalar tensor."""
+    import torch
+    n = len(layer_arr)
+    mask = bytes(bytearray(int(bool(m)) for m in full_mask))
+    if len(mask) != n or len(O_ref) != n:
+        raise IcError(Status.ERR_SHAPE, "mask / O_ref length differs from the %d layers" % n)
+    if workspace is None:
+        workspace = _workspace(int(lib().ic_pattern_loss_workspace(layer_arr, n)), idx_cache)
+    loss = torch.empty((), dtype=torch.float64, device=idx_cache.device)
+    ptrs = (C.c_void_p * n)(*[t.data_ptr() for t in O_ref])
+    _check(lib().ic_pattern_loss(layer_arr, n, mask, ptrs, _ptr(idx_cache), _ptr(loss), _ptr(workspace), workspace.numel(),
+                                 _stream(stream)))
+    return loss
+
+
+def greedy_search_forward(layer_arr, n_shared, O_ref, idx_cache, n_blocks=1, workspace=None, stream=None):
+    """ic_greedy_search_forward: Alg. 1 with one forward pass of the stack per candidate.
+    Synchronises the stream once per search step.  Returns (mask, order, loss curve)."""
+    n = len(layer_arr)
+    if len(O_ref) != n:
+        raise IcError(Status.ERR_SHAPE, "O_ref length differs from the %d layers" % n)
+    if workspace is None:
+        workspace = _workspace(int(lib().ic_greedy_search_forward_workspace(layer_arr, n)), idx_cache)
+    ptrs = (C.c_void_p * n)(*[t.data_ptr() for t in O_ref])
+    buf = C.create_string_buffer(max(n, 1))
+    order = (C.c_int32 * max(n_shared, 1))()
+    curve = (C.c_double * max(n_shared, 1))()
+    _check(lib().ic_greedy_search_forward(layer_arr, n, n_shared, n_blocks, ptrs, _ptr(idx_cache), buf, order, curve,
+                                          _ptr(workspace), workspace.numel(), _stream(stream)))
+    return [b != 0 for b in buf.raw[:n]], list(order[:n_shared]), list(curve[:n_shared])
 
 
 def debug_indexer_scores(q, k, w, q_pos0, row0, n_rows, q_scale=None, k_scale=None, stream=None):

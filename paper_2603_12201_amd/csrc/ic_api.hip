@@ -600,6 +600,165 @@ ic_status ic_pattern_search_dp(const double *S, int32_t n_layers, int32_t n_full
     return IC_OK;
 }
 
+// ---- greedy layer selection (paper Alg. 1) over a surrogate loss ---------------------------------
+
+extern "C++" {
+namespace {
+
+// Alg. 1 with the blocked variant of Sec. 3.2: `eval` fills losses[i] with the loss of the current
+// pattern with layer cands[i] flipped to Shared as well.  Ties go to the lowest layer.
+template <typename Eval>
+ic_status greedy_core(int N, int K, int P, uint8_t *mask, int32_t *order, double *curve, Eval eval)
+{
+    if (N <= 0 || K < 0 || K > N - 1 || P < 1 || P > N)
+        return fail(IC_ERR_SHAPE, "need 0 <= n_shared <= n_layers-1 and 1 <= n_blocks <= n_layers (n_layers=%d n_shared=%d n_blocks=%d)", N, K, P);
+    const int size = (N + P - 1) / P;
+    int n_cand = 0;
+    for (int b0 = 0; b0 < N; b0 += size) n_cand += (b0 + size < N ? size : N - b0) - 1;   // a block's first layer stays Full
+    if (K > n_cand) return fail(IC_ERR_SHAPE, "n_shared=%d but only %d layers may become Shared with %d blocks", K, n_cand, P);
+    for (int l = 0; l < N; ++l) mask[l] = 1;
+    std::vector<int32_t> cands;
+    std::vector<double> losses;
+    int done = 0;
+    while (done < K) {
+        for (int b0 = 0; b0 < N && done < K; b0 += size) {
+            const int b1 = b0 + size < N ? b0 + size : N;
+            cands.clear();
+            for (int l = b0 + 1; l < b1; ++l)
+                if (mask[l]) cands.push_back(l);
+            if (cands.empty()) continue;
+            losses.assign(cands.size(), 0.0);
+            ic_status s = eval(mask, cands, losses);
+            if (s != IC_OK) return s;
+            size_t arg = 0;
+            for (size_t i = 1; i < cands.size(); ++i)
+                if (losses[i] < losses[arg]) arg = i;
+            mask[cands[arg]] = 0;
+            if (order) order[done] = cands[arg];
+            if (curve) curve[done] = losses[arg];
+            ++done;
+        }
+    }
+    return IC_OK;
+}
+
+size_t pattern_loss_ws(const ic_layer *layers, int32_t n_layers)
+{
+    size_t fw = ic_forward_stack_workspace(layers, n_layers);
+    return align_up(fw) + align_up((size_t)n_layers * sizeof(double)) + kAlign;
+}
+
+ic_status run_pattern_loss(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const void *const *O_ref,
+                           int32_t *idx_cache, double *loss, void *workspace, hipStream_t st)
+{
+    char *ws = (char *)workspace;
+    const size_t fw = align_up(ic_forward_stack_workspace(layers, n_layers));
+    double *sims = (double *)(ws + fw);
+    double *acc = (double *)(ws + fw + align_up((size_t)n_layers * sizeof(double)));
+    ic_status s = ic_forward_stack(layers, n_layers, full_mask, idx_cache, workspace, fw, (void *)st);
+    if (s != IC_OK) return s;
+    const ic_attn_desc *a0 = &layers[0].at;
+    const int64_t n_rows = (int64_t)a0->B * a0->Tq, row_len = (int64_t)a0->H_q * a0->d_v;
+    for (int l = 0; l < n_layers; ++l) {
+        hipError_t e = ic::launch_cosine(layers[l].O, O_ref[l], n_rows, row_len, sims + l, nullptr, acc, st);
+        if (e != hipSuccess) return fail(IC_ERR_HIP, "cosine launch failed: %s", hipGetErrorString(e));
+    }
+    hipError_t e = ic::launch_loss_finish(sims, n_layers, loss, st);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "loss reduction launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
+ic_status check_loss_args(const ic_layer *layers, int32_t n_layers, const void *const *O_ref, const int32_t *idx_cache)
+{
+    ic_status s = check_sim_layers(layers, n_layers);
+    if (s != IC_OK) return s;
+    if (!O_ref || !idx_cache) return fail(IC_ERR_NULL, "O_ref and idx_cache must not be NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!O_ref[l]) return fail(IC_ERR_NULL, "O_ref[%d] is NULL", l);
+        if (O_ref[l] == layers[l].O) return fail(IC_ERR_SHAPE, "O_ref[%d] is the layer's own output buffer", l);
+    }
+    return IC_OK;
+}
+
+} // namespace
+} // extern "C++"
+
+ic_status ic_pattern_search_greedy(const double *S, int32_t n_layers, int32_t n_shared, int32_t n_blocks,
+                                   uint8_t *full_mask, int32_t *order, double *loss_curve)
+{
+    if (!S || !full_mask) return fail(IC_ERR_NULL, "S and full_mask must not be NULL");
+    const int N = n_layers;
+    auto loss_of = [&](const uint8_t *m) {
+        double t = 0.0;
+        int src = 0;
+        for (int l = 0; l < N; ++l) {
+            if (m[l]) src = l;
+            else t += 1.0 - S[(size_t)l * N + src];
+        }
+        return t / N;
+    };
+    return greedy_core(N, n_shared, n_blocks, full_mask, order, loss_curve,
+                       [&](uint8_t *m, const std::vector<int32_t> &cands, std::vector<double> &out) {
+                           for (size_t i = 0; i < cands.size(); ++i) {
+                               m[cands[i]] = 0;
+                               out[i] = loss_of(m);
+                               m[cands[i]] = 1;
+                           }
+                           return IC_OK;
+                       });
+}
+
+size_t ic_pattern_loss_workspace(const ic_layer *layers, int32_t n_layers)
+{
+    if (!layers || n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;
+    return pattern_loss_ws(layers, n_layers);
+}
+
+ic_status ic_pattern_loss(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const void *const *O_ref,
+                          int32_t *idx_cache, double *loss, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ic_status s = check_loss_args(layers, n_layers, O_ref, idx_cache);
+    if (s != IC_OK) return s;
+    if (!full_mask || !loss) return fail(IC_ERR_NULL, "full_mask and loss must not be NULL");
+    s = check_ws(workspace, workspace_bytes, pattern_loss_ws(layers, n_layers));
+    if (s != IC_OK) return s;
+    return run_pattern_loss(layers, n_layers, full_mask, O_ref, idx_cache, loss, workspace, (hipStream_t)stream);
+}
+
+size_t ic_greedy_search_forward_workspace(const ic_layer *layers, int32_t n_layers)
+{
+    if (!layers || n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;
+    return pattern_loss_ws(layers, n_layers) + align_up((size_t)n_layers * sizeof(double));
+}
+
+ic_status ic_greedy_search_forward(const ic_layer *layers, int32_t n_layers, int32_t n_shared, int32_t n_blocks,
+                                   const void *const *O_ref, int32_t *idx_cache, uint8_t *full_mask, int32_t *order,
+                                   double *loss_curve, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ic_status s = check_loss_args(layers, n_layers, O_ref, idx_cache);
+    if (s != IC_OK) return s;
+    if (!full_mask) return fail(IC_ERR_NULL, "full_mask must not be NULL");
+    s = check_ws(workspace, workspace_bytes, ic_greedy_search_forward_workspace(layers, n_layers));
+    if (s != IC_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    double *dev_losses = (double *)((char *)workspace + pattern_loss_ws(layers, n_layers));
+    return greedy_core(n_layers, n_shared, n_blocks, full_mask, order, loss_curve,
+                       [&](uint8_t *m, const std::vector<int32_t> &cands, std::vector<double> &out) {
+                           // one forward pass of the whole stack per candidate, all on the stream;
+                           // then the host needs the losses to choose: one synchronisation per search step
+                           for (size_t i = 0; i < cands.size(); ++i) {
+                               m[cands[i]] = 0;
+                               ic_status r = run_pattern_loss(layers, n_layers, m, O_ref, idx_cache, dev_losses + i, workspace, st);
+                               m[cands[i]] = 1;
+                               if (r != IC_OK) return r;
+                           }
+                           hipError_t e = hipStreamSynchronize(st);
+                           if (e == hipSuccess) e = hipMemcpy(out.data(), dev_losses, cands.size() * sizeof(double), hipMemcpyDeviceToHost);
+                           if (e != hipSuccess) return fail(IC_ERR_HIP, "reading the candidate losses failed: %s", hipGetErrorString(e));
+                           return IC_OK;
+                       });
+}
+
 size_t ic_topk_overlap_workspace(int32_t n_layers)
 {
     if (n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;

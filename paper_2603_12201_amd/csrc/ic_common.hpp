@@ -95,6 +95,7 @@ hipError_t launch_overlap(const int32_t *const *idx_layers, int n_layers, int64_
 hipError_t launch_cosine(const void *A, const void *B, int64_t n_rows, int64_t row_len, double *mean, float *per_row,
                          double *acc, hipStream_t st);
 hipError_t launch_sim_init(double *S, int n, hipStream_t st);
+hipError_t launch_loss_finish(const double *sims, int n, double *loss, hipStream_t st);
 bool score_shape_supported(int dtype, int H_I, int d_I);
 bool attn_shape_supported(int d_qk, int d_v);
 

@@ -4,9 +4,11 @@
 // A workgroup owns one layer i and a block of kQB query rows.  Per query it marks layer i's
 // selected positions in an LDS bitmap of Lk bits, then tests the rows of every layer j >= i against
 // it (the intersection count is symmetric); hits are counted with a wave ballot + popcount and
-// summed per j in LDS; one 64-bit global atomic per (workgroup, j) at the end.  Layer i is the
-// fastest grid dimension, so the workgroups that share a block of query rows run together and the
-// rows of all layers are re-read out of L2, not HBM.
+// summed per j in LDS; one 64-bit global atomic per (workgroup, j) at the end.  The workgroups
+// that share a block of query rows (all layers i) are mapped to one XCD and to neighbouring
+// positions in dispatch order, so the index rows they all read come out of that XCD's L2; with
+// the layers dealt over all eight L2s every pair's rows came from memory (315 GB of fetches for
+// 48 layers at 32K queries) and the kernel ran at the memory rate instead of the LDS rate.
 #include "ic_common.hpp"
 
 namespace ic {
@@ -34,8 +36,13 @@ __global__ __launch_bounds__(256) void overlap_kernel(OverlapArgs a)
     uint32_t *bm = osm;                        // [bm_words]
     uint32_t *cnt = osm + a.bm_words;          // [n_layers] hits per layer j, + [1] members of layer i
     const int tid = threadIdx.x, lane = tid & 63;
-    const int i = (int)(blockIdx.x % (unsigned)a.n_layers);      // layer fastest: see the header comment
-    const int64_t q0 = (int64_t)(blockIdx.x / (unsigned)a.n_layers) * kQB;
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2: id % 8 picks the
+    // query block's residue, so that all layers i of one query block run on the same XCD, next to
+    // each other in dispatch order, and find each other's index rows in that L2.
+    const unsigned xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3;
+    const int i = (int)(rest % (unsigned)a.n_layers);
+    const int64_t q0 = ((int64_t)(rest / (unsigned)a.n_layers) * 8 + xcd) * kQB;
+    if (q0 >= a.nq) return;                    // the grid is padded to a multiple of 8 query blocks
     const int64_t q1 = q0 + kQB < a.nq ? q0 + kQB : a.nq;
 
     auto member = [&](int32_t v) -> bool {
@@ -156,7 +163,7 @@ hipError_t launch_overlap(const int32_t *const *idx_layers, int n_layers, int64_
             if (e != hipSuccess) return e;
             lds_opt_in[vec] = lds;
         }
-        dim3 grid((unsigned)(((nq + kQB - 1) / kQB) * n_layers));
+        dim3 grid((unsigned)(((nq + kQB - 1) / kQB + 7) / 8 * 8 * n_layers));
         if (vec)
             hipLaunchKernelGGL(overlap_kernel<true>, grid, dim3(256), lds, st, a);
         else

@@ -100,6 +100,14 @@ __global__ void cosine_zero_kernel(double *acc) { *acc = 0.0; }
 
 __global__ void cosine_finish_kernel(const double *acc, int64_t n_rows, double *mean) { *mean = *acc / (double)n_rows; }
 
+// loss = 1/n * sum_l (1 - sims[l]): the attention-output error of a pattern against the all-Full stack
+__global__ void loss_finish_kernel(const double *sims, int n, double *loss)
+{
+    double t = 0.0;
+    for (int l = 0; l < n; ++l) t += 1.0 - sims[l];
+    *loss = t / (double)n;
+}
+
 // S starts as the identity: the diagonal is 1 by definition, the upper triangle is not defined (0)
 __global__ void sim_init_kernel(double *S, int n)
 {
@@ -121,6 +129,12 @@ hipError_t launch_cosine(const void *A, const void *B, int64_t n_rows, int64_t r
         hipLaunchKernelGGL(cosine_kernel<false>, dim3((unsigned)n_rows), dim3(256), 0, st, (const unsigned short *)A,
                            (const unsigned short *)B, row_len, per_row, acc);
     hipLaunchKernelGGL(cosine_finish_kernel, dim3(1), dim3(1), 0, st, (const double *)acc, n_rows, mean);
+    return hipGetLastError();
+}
+
+hipError_t launch_loss_finish(const double *sims, int n, double *loss, hipStream_t st)
+{
+    hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(1), 0, st, sims, n, loss);
     return hipGetLastError();
 }
 

@@ -264,3 +264,57 @@ def test_paged_cache_argument_errors(ic):
     assert L.ic_forward_stack_paged(arr, 2, bytes([1, 0]), None, one, one, wss, None) == S.ERR_NULL
     assert L.ic_forward_stack_paged(arr, 2, bytes([1, 0]), C.byref(pc(max_pages=1)), one, one, wss, None) == S.ERR_SHAPE
     assert L.ic_forward_stack_paged(arr, 2, bytes([0, 1]), C.byref(pc()), one, one, wss, None) == S.ERR_PATTERN
+
+
+def test_greedy_search_on_a_similarity_matrix_matches_the_oracle(oracle):
+    """Host-only: Alg. 1 in the library against the oracle's, plain and blocked, random matrices."""
+    import numpy as np
+    import paper_2603_12201_amd as ic
+    rng = np.random.default_rng(11)
+    for n in (2, 5, 9, 16):
+        S = np.tril(rng.random((n, n)), -1) + np.eye(n)
+        f = lambda m: oracle.pattern_loss_from_similarity(S, m)
+        for blocks in (1, 2, 3):
+            if blocks > n:
+                continue
+            size = -(-n // blocks)
+            n_cand = sum(min(size, n - b0) - 1 for b0 in range(0, n, size))
+            for K in sorted({0, min(1, n_cand), n_cand // 2, n_cand}):
+                mask, order, curve = ic.pattern_search_greedy(S, K, blocks)
+                want_mask, want_order, want_curve = oracle.greedy_search(f, n, K, blocks)
+                assert mask == want_mask and order == want_order
+                assert np.allclose(curve, want_curve, rtol=0, atol=1e-13)
+    # the worked example: greedy takes {2, 3}, the optimum is {1, 3}
+    S = np.eye(4)
+    S[1, 0], S[2, 1], S[2, 0], S[3, 2], S[3, 1], S[3, 0] = 0.90, 0.99, 0.20, 0.50, 0.40, 0.30
+    mask, order, curve = ic.pattern_search_greedy(S, 2)
+    assert order == [2, 3] and mask == [True, True, False, False] and curve == pytest.approx([0.0025, 0.1525])
+
+
+def test_greedy_argument_errors_need_no_gpu(ic):
+    L, S = ic.lib(), ic.Status
+    flat = (C.c_double * 16)(*([1.0] * 16))
+    buf = C.create_string_buffer(4)
+    assert L.ic_pattern_search_greedy(None, 4, 1, 1, buf, None, None) == S.ERR_NULL
+    assert L.ic_pattern_search_greedy(flat, 4, 1, 1, None, None, None) == S.ERR_NULL
+    assert L.ic_pattern_search_greedy(flat, 4, 4, 1, buf, None, None) == S.ERR_SHAPE      # layer 0 stays Full
+    assert L.ic_pattern_search_greedy(flat, 4, -1, 1, buf, None, None) == S.ERR_SHAPE
+    assert L.ic_pattern_search_greedy(flat, 4, 1, 0, buf, None, None) == S.ERR_SHAPE
+    assert L.ic_pattern_search_greedy(flat, 4, 1, 5, buf, None, None) == S.ERR_SHAPE
+    assert L.ic_pattern_search_greedy(flat, 4, 3, 2, buf, None, None) == S.ERR_SHAPE      # two blocks: two candidates
+    assert L.ic_pattern_search_greedy(flat, 4, 2, 2, buf, None, None) == S.OK and buf.raw == b"\x01\x00\x01\x00"
+    arr = (ic.Layer * 2)()
+    for l in range(2):
+        arr[l].ix, arr[l].at = _ixd(ic), _atd(ic, k_sel=64)
+        arr[l].q = arr[l].k = arr[l].w = arr[l].Q = arr[l].KV = arr[l].O = 4096
+    ws = L.ic_pattern_loss_workspace(arr, 2)
+    assert ws > 0 and L.ic_greedy_search_forward_workspace(arr, 2) > ws
+    one = C.c_void_p(8192)
+    refs = (C.c_void_p * 2)(8192, 12288)
+    assert L.ic_pattern_loss(arr, 2, bytes([1, 0]), None, one, one, one, ws, None) == S.ERR_NULL
+    assert L.ic_pattern_loss(arr, 2, bytes([1, 0]), refs, one, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_pattern_loss(arr, 2, bytes([1, 0]), refs, one, one, one, 64, None) == S.ERR_WORKSPACE
+    own = (C.c_void_p * 2)(8192, 4096)                                                     # a layer's own O
+    assert L.ic_pattern_loss(arr, 2, bytes([1, 0]), own, one, one, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_greedy_search_forward(arr, 2, 1, 1, refs, one, None, None, None, one, 1 << 30, None) == S.ERR_NULL
+    assert L.ic_greedy_search_forward(arr, 2, 1, 1, refs, one, buf, None, None, one, 64, None) == S.ERR_WORKSPACE
