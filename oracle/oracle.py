@@ -299,6 +299,92 @@ def greedy_search(eval_loss, n_layers, n_shared, n_blocks=1):
     return mask, order, curve
 
 
+# ---- multi-layer distillation loss (Sec. 3.3, Eq. 1 and Prop. 1) -------------------------
+
+def _widen_bf16(bits):
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def indexer_distribution(scores):
+    """q_t = Softmax(I_t) over the finite entries of each row (hidden keys / empty slots hold -inf
+    and get probability 0).  scores [..., n] float64."""
+    sc = np.asarray(scores, dtype=np.float64)
+    m = np.max(np.where(np.isfinite(sc), sc, -np.inf), axis=-1, keepdims=True)
+    m = np.where(np.isfinite(m), m, 0.0)
+    e = np.where(np.isfinite(sc), np.exp(sc - m), 0.0)
+    z = e.sum(-1, keepdims=True)
+    return np.where(z > 0, e / np.where(z > 0, z, 1.0), 0.0)
+
+
+def attn_distribution_dense(Q, KV, sm_scale, q_pos0):
+    """p_t: the attention distribution of a layer aggregated over its heads (Sec. 2.1: the
+    indexer's training target), p_t(s) = 1/H sum_h softmax_s(sm_scale * Q[t,h] . K[s]) over the
+    causally visible keys s <= q_pos0 + t; K[s] = the first d_qk features of KV row s.
+    Returns [B,Tq,Lk] float64 (0 on hidden keys)."""
+    Qf, KVf = _widen_bf16(Q), _widen_bf16(KV)
+    B, Tq, H, d = Qf.shape
+    Lk = KVf.shape[1]
+    P = np.zeros((B, Tq, Lk))
+    for b in range(B):
+        K = KVf[b, :, :d]
+        for t in range(Tq):
+            nv = max(0, min(Lk, q_pos0 + t + 1))
+            if nv == 0:
+                continue
+            z = sm_scale * (Qf[b, t] @ K[:nv].T)                  # [H, nv]
+            z -= z.max(axis=1, keepdims=True)
+            e = np.exp(z)
+            P[b, t, :nv] = (e / e.sum(axis=1, keepdims=True)).mean(axis=0)
+    return P
+
+
+def attn_distribution_selected(Q, KV, idx, sm_scale):
+    """The same aggregated distribution when the layer attends only to the rows named by idx (a
+    Full layer's own T_t, or the T_t a Shared layer inherits): softmax over the selected rows,
+    mean over the heads.  Returns [B,Tq,k_sel] float64 in slot order (0 on empty slots)."""
+    Qf, KVf = _widen_bf16(Q), _widen_bf16(KV)
+    B, Tq, H, d = Qf.shape
+    Lk = KVf.shape[1]
+    P = np.zeros(idx.shape)
+    for b in range(B):
+        for t in range(Tq):
+            slots = np.nonzero((idx[b, t] >= 0) & (idx[b, t] < Lk))[0]
+            if slots.size == 0:
+                continue
+            z = sm_scale * (Qf[b, t] @ KVf[b, idx[b, t, slots], :d].T)   # [H, n]
+            z -= z.max(axis=1, keepdims=True)
+            e = np.exp(z)
+            P[b, t, slots] = (e / e.sum(axis=1, keepdims=True)).mean(axis=0)
+    return P
+
+
+def kl_rows(p, q):
+    """D_KL(p || q) per row = sum_s p(s) log(p(s) / q(s)), with 0 log 0 = 0 (inf if q = 0 < p)."""
+    p, q = np.asarray(p, dtype=np.float64), np.asarray(q, dtype=np.float64)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        t = np.where(p > 0, p * (np.log(p) - np.log(q)), 0.0)
+    return t.sum(-1)
+
+
+def distill_loss_multi(p_list, q):
+    """Eq. 1: sum_j 1/(m+1) sum_t D_KL(p_t^(l+j) || q_t^(l)) for the m+1 layers a Full layer serves
+    (itself and its m Shared followers).  p_list: m+1 arrays [..., n]; q [..., n]."""
+    return sum(kl_rows(p, q).sum() for p in p_list) / len(p_list)
+
+
+def distill_loss_avg(p_list, q):
+    """Eq. 2: the single-target loss against the averaged distribution p_bar = mean_j p^(l+j)."""
+    return kl_rows(sum(np.asarray(p, dtype=np.float64) for p in p_list) / len(p_list), q).sum()
+
+
+def distill_grad_logits(p_list, q):
+    """d/dI of either loss with respect to the indexer's logits (q = Softmax(I)): q_t * (row mass of
+    p_bar) - p_bar_t, i.e. q - p_bar for normalised targets.  What Prop. 1 says is that Eq. 1 and
+    Eq. 2 share it."""
+    pb = sum(np.asarray(p, dtype=np.float64) for p in p_list) / len(p_list)
+    return np.asarray(q, dtype=np.float64) * pb.sum(-1, keepdims=True) - pb
+
+
 # ---- pattern strings and the layer loop (Fig. 2, Sec. 3 Overview) -------------
 
 def pattern_from_string(s):
