@@ -155,6 +155,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--greedy-layers", type=int, default=6)
+    ap.add_argument("--distill-targets", type=int, default=4)
     ap.add_argument("--no-overlap", action="store_true", help="skip the cross-layer overlap diagnostic arm")
     ap.add_argument("--overlap-layers", type=int, default=48)
     ap.add_argument("--similarity-layers", type=int, default=8)
@@ -407,6 +408,35 @@ def main():
             "order": gorder, "loss_curve": gcurve, "pattern": "".join("F" if m else "S" for m in gmask),
             "loss": "1/N sum_l (1 - mean per-token cosine of layer l's output under the pattern vs all-Full)"}
         del lay_g, outs_g, ref_g, at2, arr_g
+
+    # ---------------- forward of the multi-layer distillation loss (Sec. 3.3, Eq. 1 / Eq. 2) ----------------
+    if not args.no_overlap and args.distill_targets >= 1:
+        m1 = args.distill_targets
+        log("distillation arm: one Full layer serving %d layers" % m1)
+        dcfg3 = synth.config("c3")
+        ixd = synth.indexer_layer(dcfg3, 0, device="cuda")
+        idx_d, sel_d = ic.indexer_topk(ixd["q"], ixd["k"], ixd["w"], dcfg3["k_sel"], 0, want_scores=True)
+        del ixd
+        atd = synth.attn_layer(dcfg3, 0, device="cuda")
+        _, lse_d = ic.sparse_attn(atd["Q"], atd["KV"], idx_d, dcfg3["d_v"], dcfg3["v_off"], synth.sm_scale(dcfg3), want_lse=True)
+        ms_probs = time_steps(lambda: ic.attn_probs(atd["Q"], atd["KV"], idx_d, synth.sm_scale(dcfg3), lse_d), 3, 1)
+        probs_d = [ic.attn_probs(atd["Q"], atd["KV"], idx_d, synth.sm_scale(dcfg3), lse_d) for _ in range(m1)]
+        ws_d = torch.empty(int(ic.lib().ic_distill_loss_workspace(dcfg3["Tq"])), dtype=torch.uint8, device="cuda")
+        ms_kl = time_steps(lambda: ic.distill_loss(probs_d, sel_d, workspace=ws_d), 5, 1)
+        lm_d, la_d = ic.distill_loss(probs_d, sel_d, workspace=ws_d)
+        torch.cuda.synchronize()
+        flop_p = 2.0 * dcfg3["H_q"] * dcfg3["k_sel"] * dcfg3["d_qk"] * dcfg3["Tq"]
+        bytes_kl = (m1 + 1) * 4.0 * dcfg3["Tq"] * dcfg3["k_sel"]
+        arms["distill_forward"] = {
+            "served_layers": m1,
+            "attn_probs": {"ms": ms_probs, "bound": "mfma", "achieved": flop_p / (ms_probs * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                           "unit": "TFLOP/s", "frac": flop_p / (ms_probs * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                           "gathered_GBs": dcfg3["Tq"] * dcfg3["k_sel"] * dcfg3["row_elems"] * 2 / (ms_probs * 1e-3) / 1e9},
+            "kl_kernel": {"ms": ms_kl, "bound": "hbm", "achieved": bytes_kl / (ms_kl * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                          "unit": "GB/s", "frac": bytes_kl / (ms_kl * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "loss_multi": float(lm_d), "loss_avg": float(la_d),
+            "note": "identical targets here, so Eq. 1 = Eq. 2; timing only"}
+        del probs_d, atd, idx_d, sel_d
 
     out = {
         "metric": "prefill & decode tokens/s, 48-layer DSA stack L=32K, 1-in-4 Full vs all-Full",

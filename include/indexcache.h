@@ -175,6 +175,40 @@ ic_status ic_sparse_attn_paged(const ic_attn_desc *d, const ic_paged_cache *pc, 
 ic_status ic_forward_stack_paged(const ic_layer *layers, int32_t n_layers, const uint8_t *full_mask, const ic_paged_cache *pc,
                                  int32_t *idx_cache, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Forward of the indexer's distillation loss (paper Sec. 3.3), in the form of the sparse training
+ * phase: both distributions live on the k selected positions of a query.
+ *
+ * ic_attn_probs: the attention distribution of a layer aggregated over its heads (the indexer's
+ * training target, Sec. 2.1) on the rows named by idx,
+ *     probs[b,t,m] = 1/H_q sum_h softmax_m(sm_scale * Q[b,t,h] . K[idx[b,t,m]])     (0 on empty slots)
+ * K = the first d_qk features of a KV row.  lse [B,Tq,H_q] fp32: the log-sum-exps ic_sparse_attn
+ * returns for the same Q, KV, idx (the per-head normalisers); probs [B,Tq,k_sel] fp32, out.
+ * Dense caches only.  Asynchronous.
+ *
+ * ic_distill_loss: for one Full layer's indexer and the n_targets = m+1 layers it serves (itself and
+ * its m Shared followers, all attending to the SAME index tensor):
+ *     q_t = Softmax(sel_scores[t, :]) over the finite entries        (the indexer's distribution on T_t)
+ *     loss_multi = sum_j 1/(m+1) sum_t KL(probs_j[t] || q_t)                               (Eq. 1)
+ *     loss_avg   = sum_t KL(mean_j probs_j[t] || q_t)                                      (Eq. 2)
+ *     grad[t,m]  = q_t[m] * |mean_j probs_j[t]| - mean_j probs_j[t][m]
+ * grad is the derivative of EITHER loss with respect to the indexer's logits (Prop. 1: the two
+ * losses differ by a term without q).  Reading of the sparse-phase restriction: both distributions
+ * are renormalised over the selected set.
+ *   probs       HOST array of n_targets DEVICE tensors [nq, k_sel] fp32 (ic_attn_probs of each layer)
+ *   sel_scores  device [nq, k_sel] fp32 as ic_indexer_topk returns them (-inf on empty slots)
+ *   loss_multi, loss_avg  device doubles, out, each nullable;  grad device [nq, k_sel] fp32, nullable
+ *   workspace   ic_distill_loss_workspace(nq) bytes
+ * 1 <= n_targets <= IC_MAX_DISTILL_TARGETS.  Asynchronous; the sums are taken in a fixed order.
+ */
+#define IC_MAX_DISTILL_TARGETS 16
+ic_status ic_attn_probs(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, const float *lse,
+                        float *probs, void *stream);
+size_t ic_distill_loss_workspace(int64_t nq);
+ic_status ic_distill_loss(const float *const *probs, int32_t n_targets, const float *sel_scores, int64_t nq, int32_t k_sel,
+                          double *loss_multi, double *loss_avg, float *grad, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
 /* Host-only helpers for the pattern string c = c_1..c_N in {F,S}^N (Sec. 3 Overview). */
 ic_status ic_pattern_from_string(const char *fs, uint8_t *full_mask, int32_t n);
 /* Uniform interleave: F at layers l with l % r == 0, "FSSSFSSS.." for r = 4 (Sec. 3.1). */

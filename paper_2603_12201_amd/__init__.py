@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     pattern_from_string, pattern_uniform, topk_overlap,
     cosine_rows, similarity_matrix, pattern_search_dp,
     pattern_search_greedy, pattern_loss, greedy_search_forward,
+    attn_probs, distill_loss,
     paged_cache, indexer_topk_paged, sparse_attn_paged, forward_stack_paged,
     debug_indexer_scores, debug_indexer_launch_count,
     prof_enable, prof_collect, prof_get, prof_reset,

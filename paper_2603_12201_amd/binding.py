@@ -95,6 +95,12 @@ def lib():
         L.ic_greedy_search_forward.restype = C.c_int
         L.ic_greedy_search_forward.argtypes = [C.POINTER(Layer), i32, i32, i32, C.POINTER(vp), vp, C.c_char_p, C.POINTER(i32),
                                                C.POINTER(C.c_double), vp, sz, vp]
+        L.ic_attn_probs.restype = C.c_int
+        L.ic_attn_probs.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp]
+        L.ic_distill_loss_workspace.restype = sz
+        L.ic_distill_loss_workspace.argtypes = [C.c_int64]
+        L.ic_distill_loss.restype = C.c_int
+        L.ic_distill_loss.argtypes = [C.POINTER(vp), i32, vp, C.c_int64, i32, vp, vp, vp, vp, sz, vp]
         L.ic_pattern_search_dp.restype = C.c_int
         L.ic_pattern_search_dp.argtypes = [C.POINTER(C.c_double), i32, i32, C.c_char_p, C.POINTER(C.c_double)]
         L.ic_topk_overlap_workspace.restype = sz
@@ -449,6 +455,39 @@ def greedy_search_forward(layer_arr, n_shared, O_ref, idx_cache, n_blocks=1, wor
     _check(lib().ic_greedy_search_forward(layer_arr, n, n_shared, n_blocks, ptrs, _ptr(idx_cache), buf, order, curve,
                                           _ptr(workspace), workspace.numel(), _stream(stream)))
     return [b != 0 for b in buf.raw[:n]], list(order[:n_shared]), list(curve[:n_shared])
+
+
+def attn_probs(Q, KV, idx, sm_scale, lse, stream=None):
+    """ic_attn_probs: head-aggregated attention probabilities over the selected rows, [B,Tq,k_sel]
+    fp32.  lse: what sparse_attn(..., want_lse=True) returned for the same Q, KV, idx."""
+    import torch
+    _need(lse, "lse", torch.float32, 3)
+    d = attn_desc(Q, KV, idx, 512 if Q.shape[3] == 576 else Q.shape[3], 0, sm_scale)   # the value layout plays no role here
+    probs = torch.empty(tuple(idx.shape), dtype=torch.float32, device=Q.device)
+    _check(lib().ic_attn_probs(C.byref(d), _ptr(Q), _ptr(KV), _ptr(idx), _ptr(lse), _ptr(probs), _stream(stream)))
+    return probs
+
+
+def distill_loss(probs, sel_scores, want_grad=False, workspace=None, stream=None):
+    """ic_distill_loss: probs = list of [B,Tq,k_sel] fp32 targets (the Full layer and the Shared layers
+    it serves), sel_scores = the Full layer's selected indexer scores.  Returns device float64
+    scalars (loss_multi, loss_avg) and, if asked, the gradient with respect to the logits."""
+    import torch
+    _need(sel_scores, "sel_scores", torch.float32, 3)
+    for p in probs:
+        _need(p, "probs", torch.float32, 3)
+        if tuple(p.shape) != tuple(sel_scores.shape):
+            raise IcError(Status.ERR_SHAPE, "probs %s vs sel_scores %s" % (tuple(p.shape), tuple(sel_scores.shape)))
+    nq, k_sel = sel_scores.shape[0] * sel_scores.shape[1], sel_scores.shape[2]
+    if workspace is None:
+        workspace = _workspace(int(lib().ic_distill_loss_workspace(nq)), sel_scores)
+    lm = torch.empty((), dtype=torch.float64, device=sel_scores.device)
+    la = torch.empty((), dtype=torch.float64, device=sel_scores.device)
+    grad = torch.empty_like(sel_scores) if want_grad else None
+    ptrs = (C.c_void_p * len(probs))(*[p.data_ptr() for p in probs])
+    _check(lib().ic_distill_loss(ptrs, len(probs), _ptr(sel_scores), nq, k_sel, _ptr(lm), _ptr(la), _ptr(grad),
+                                 _ptr(workspace), workspace.numel(), _stream(stream)))
+    return (lm, la, grad) if want_grad else (lm, la)
 
 
 def debug_indexer_scores(q, k, w, q_pos0, row0, n_rows, q_scale=None, k_scale=None, stream=None):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libindexcache.so")
-SOURCES = ["ic_api.hip", "ic_indexer_score.hip", "ic_topk_select.hip", "ic_sparse_attn.hip", "ic_overlap.hip", "ic_similarity.hip"]
+SOURCES = ["ic_api.hip", "ic_indexer_score.hip", "ic_topk_select.hip", "ic_sparse_attn.hip", "ic_overlap.hip", "ic_similarity.hip", "ic_distill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -759,6 +759,66 @@ ic_status ic_greedy_search_forward(const ic_layer *layers, int32_t n_layers, int
                        });
 }
 
+// ---- distillation loss forward (paper Sec. 3.3) ---------------------------------------------------
+
+ic_status ic_attn_probs(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, const float *lse,
+                        float *probs, void *stream)
+{
+    ic_status s = check_attn(d);
+    if (s != IC_OK) return s;
+    if (!Q || !KV || !idx || !lse || !probs) return fail(IC_ERR_NULL, "Q, KV, idx, lse and probs must not be NULL");
+    ic::ProbsArgs a;
+    memset(&a, 0, sizeof a);
+    a.Q = Q;
+    a.KV = KV;
+    a.idx = idx;
+    a.lse = lse;
+    a.probs = probs;
+    a.B = d->B;
+    a.Tq = d->Tq;
+    a.Lk = d->Lk;
+    a.H_q = d->H_q;
+    a.row_elems = d->row_elems;
+    a.k_sel = d->k_sel;
+    a.scale_log2e = d->sm_scale * 1.4426950408889634f;
+    hipError_t e = ic::launch_attn_probs(a, d->d_qk, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "attention-probability launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
+size_t ic_distill_loss_workspace(int64_t nq)
+{
+    if (nq <= 0) return kAlign;
+    return 2 * align_up((size_t)nq * sizeof(double));
+}
+
+ic_status ic_distill_loss(const float *const *probs, int32_t n_targets, const float *sel_scores, int64_t nq, int32_t k_sel,
+                          double *loss_multi, double *loss_avg, float *grad, void *workspace, size_t workspace_bytes,
+                          void *stream)
+{
+    if (!probs || !sel_scores) return fail(IC_ERR_NULL, "probs and sel_scores must not be NULL");
+    if (n_targets < 1 || n_targets > IC_MAX_DISTILL_TARGETS)
+        return fail(IC_ERR_SHAPE, "n_targets=%d must be in [1, %d]", n_targets, IC_MAX_DISTILL_TARGETS);
+    if (nq < 0 || nq > INT32_MAX || k_sel <= 0) return fail(IC_ERR_SHAPE, "need 0 <= nq <= 2^31-1 and k_sel > 0");
+    for (int j = 0; j < n_targets; ++j)
+        if (!probs[j]) return fail(IC_ERR_NULL, "probs[%d] is NULL", j);
+    if (!loss_multi && !loss_avg && !grad) return fail(IC_ERR_NULL, "at least one output must be given");
+    ic_status s = check_ws(workspace, workspace_bytes, ic_distill_loss_workspace(nq));
+    if (s != IC_OK) return s;
+    ic::DistillArgs a;
+    memset(&a, 0, sizeof a);
+    for (int j = 0; j < n_targets; ++j) a.probs[j] = probs[j];
+    a.n_targets = n_targets;
+    a.k_sel = k_sel;
+    a.scores = sel_scores;
+    a.row_multi = (double *)workspace;
+    a.row_avg = (double *)((char *)workspace + align_up((size_t)(nq > 0 ? nq : 1) * sizeof(double)));
+    a.grad = grad;
+    hipError_t e = ic::launch_distill(a, nq, loss_multi, loss_avg, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "distillation loss launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
 size_t ic_topk_overlap_workspace(int32_t n_layers)
 {
     if (n_layers <= 0 || n_layers > IC_MAX_OVERLAP_LAYERS) return 0;

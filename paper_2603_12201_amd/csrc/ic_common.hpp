@@ -80,6 +80,39 @@ struct AttnArgs {
     PagedView pv;         // ragged / paged KV cache (KV is then the page pool [n_pages << page_shift, row_elems])
 };
 
+// Head-aggregated attention probabilities over the selected rows (the indexer's training target).
+struct ProbsArgs {
+    const void *Q;        // [B,Tq,H_q,d_qk] bf16
+    const void *KV;       // [B,Lk,row_elems] bf16; K = the first d_qk features of a row
+    const int32_t *idx;   // [B,Tq,k_sel]
+    const float *lse;     // [B,Tq,H_q] natural-log sum-exp of each head over the same rows
+    float *probs;         // [B,Tq,k_sel] out, slot order, 0 on empty slots
+    int32_t B, Tq, Lk, H_q, row_elems, k_sel;
+    float scale_log2e;
+};
+
+// Distillation losses of one Full layer's indexer against the layers it serves.
+struct DistillArgs {
+    const float *probs[IC_MAX_DISTILL_TARGETS];   // m+1 targets, each [nq, k_sel]
+    int32_t n_targets, k_sel;
+    const float *scores;  // [nq, k_sel] indexer logits at the selected positions (-inf on empty slots)
+    double *row_multi;    // [nq] per-row Eq. 1 terms
+    double *row_avg;      // [nq] per-row Eq. 2 terms
+    float *grad;          // [nq, k_sel] or nullptr
+};
+
+// Sum over the 16 lanes of a row (lanes with equal lane / 16) on the data-parallel-primitive path:
+// shifts by 1, 2, 4, 8 lanes inside the row; lanes without a source add zero.  Lane 15 of the row
+// holds the total.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x111, 0xf, 0xf, false));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x112, 0xf, 0xf, false));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x114, 0xf, 0xf, false));
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x118, 0xf, 0xf, false));
+    return x;
+}
+
 // ---- launchers (defined next to their kernels) ----------------------------------------
 
 hipError_t launch_score(const ScoreArgs &a, int dtype, int d_I, int Bc, hipStream_t st);
@@ -96,6 +129,8 @@ hipError_t launch_cosine(const void *A, const void *B, int64_t n_rows, int64_t r
                          double *acc, hipStream_t st);
 hipError_t launch_sim_init(double *S, int n, hipStream_t st);
 hipError_t launch_loss_finish(const double *sims, int n, double *loss, hipStream_t st);
+hipError_t launch_attn_probs(const ProbsArgs &a, int d_qk, hipStream_t st);
+hipError_t launch_distill(const DistillArgs &a, int64_t nq, double *loss_multi, double *loss_avg, hipStream_t st);
 bool score_shape_supported(int dtype, int H_I, int d_I);
 bool attn_shape_supported(int d_qk, int d_v);
 

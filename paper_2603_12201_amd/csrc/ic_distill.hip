@@ -1,0 +1,217 @@
+// Forward of the indexer's distillation loss (paper Sec. 3.3: Eq. 1 multi-layer loss, Eq. 2 loss
+// against the averaged target, Prop. 1), in the form the sparse training phase uses: both
+// distributions live on the k selected positions of a query.
+//
+//   attn_probs_kernel   p_bar_t(s) = 1/H sum_h softmax_s(sm_scale Q[t,h] . K[s]) over the selected
+//                       rows: the layer's attention distribution aggregated over its heads, the
+//                       indexer's training target (Sec. 2.1).  S^T = K Q^T on
+//                       v_mfma_f32_16x16x32_bf16 with Q in registers; the per-head normalisers are
+//                       the log-sum-exps the attention kernel already produced; the head sum is a
+//                       16-lane row reduction.
+//   distill_row_kernel  per query: q = Softmax(I) over the selected scores (in the log domain),
+//                       sum_j 1/(m+1) KL(p_j || q), KL(p_bar || q), and q * |p_bar| - p_bar, the
+//                       gradient with respect to the indexer's logits that both losses share.
+//   distill_sum_kernel  fixed-order sum of the per-row values (one workgroup: deterministic).
+#include "ic_common.hpp"
+
+namespace ic {
+
+namespace {
+
+constexpr int kProbTile = 64;
+
+template <int D_QK>
+__global__ __launch_bounds__(256) void attn_probs_kernel(ProbsArgs a)
+{
+    constexpr int KS = D_QK / 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int64_t qrow = blockIdx.x;
+    const int b = (int)(qrow / a.Tq);
+    const int32_t *idx_row = a.idx + qrow * a.k_sel;
+    const unsigned short *kv_seq = (const unsigned short *)a.KV + (int64_t)b * a.Lk * a.row_elems;
+    float *out = a.probs + qrow * a.k_sel;
+
+    // Q as the B operand (head 16 hb + l16, features 8 g + 32 ks ..), and the heads' log-sum-exps
+    bf16x8 qreg[2][KS];
+    float lse2[2];
+    bool head_ok[2];
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+        const int head = 16 * hb + l16;
+        head_ok[hb] = head < a.H_q;
+        const unsigned short *qp = (const unsigned short *)a.Q + (qrow * a.H_q + (head_ok[hb] ? head : 0)) * D_QK + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 raw = u32x4{0u, 0u, 0u, 0u};
+            if (head_ok[hb]) raw = *(const u32x4 *)(qp + 32 * ks);
+            qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
+        lse2[hb] = head_ok[hb] ? a.lse[qrow * a.H_q + head] * 1.4426950408889634f : INFINITY;
+    }
+    const float inv_h = 1.f / (float)a.H_q;
+
+    const int ntiles = (a.k_sel + kProbTile - 1) / kProbTile;
+#pragma unroll 1
+    for (int it = 0; it < ntiles; ++it) {
+        // the wave's 16 slots; lane (l16, g) feeds row l16 of the A operand
+        const int slot = it * kProbTile + 16 * wave + l16;
+        int32_t v = slot < a.k_sel ? idx_row[slot] : -1;
+        const bool valid = v >= 0 && v < a.Lk;
+        const unsigned rows_ok = (unsigned)(__ballot(valid) & 0xFFFFull);     // bit r: row r of the wave
+        const unsigned short *kp = kv_seq + (int64_t)(valid ? v : 0) * a.row_elems + 8 * g;
+        bf16x8 ka[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) ka[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kp + 32 * ks));
+        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[0][ks], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[1][ks], acc[1], 0, 0, 0);
+        }
+        // lane (head l16, g) holds rows 4 g + i: probabilities of its two heads, summed over the heads
+        float ps[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = (rows_ok >> (4 * g + i)) & 1u;
+            float p = 0.f;
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb)
+                if (ok && head_ok[hb]) p += __builtin_amdgcn_exp2f(acc[hb][i] * a.scale_log2e - lse2[hb]);
+            ps[i] = row16_sum(p);                         // lane l16 == 15: the sum over the 16 head lanes
+        }
+        if (l16 == 15) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int s = it * kProbTile + 16 * wave + 4 * g + i;
+                if (s < a.k_sel) out[s] = ps[i] * inv_h;
+            }
+        }
+    }
+}
+
+// block-wide sum of doubles through LDS (256 threads)
+__device__ __forceinline__ double block_sum(double x, double *red, int tid)
+{
+    red[tid] = x;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) red[tid] += red[tid + off];
+        __syncthreads();
+    }
+    const double r = red[0];
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ float block_max(float x, float *red, int tid)
+{
+    red[tid] = x;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (tid < off) red[tid] = fmaxf(red[tid], red[tid + off]);
+        __syncthreads();
+    }
+    const float r = red[0];
+    __syncthreads();
+    return r;
+}
+
+__global__ __launch_bounds__(256) void distill_row_kernel(DistillArgs a)
+{
+    __shared__ double redd[256];
+    __shared__ float redf[256];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    const float *sc = a.scores + row * a.k_sel;
+    const float w = 1.f / (float)a.n_targets;
+
+    // log q(s) = (I_s - max) - log sum exp(I - max), over the finite entries
+    float mx = -INFINITY;
+    for (int s = tid; s < a.k_sel; s += 256) {
+        const float x = sc[s];
+        if (x > -INFINITY && x < INFINITY) mx = fmaxf(mx, x);
+    }
+    mx = block_max(mx, redf, tid);
+    double z = 0.0;
+    for (int s = tid; s < a.k_sel; s += 256) {
+        const float x = sc[s];
+        if (x > -INFINITY && x < INFINITY) z += (double)expf(x - mx);
+    }
+    z = block_sum(z, redd, tid);
+    const float log_z = z > 0.0 ? (float)log(z) : 0.f;
+
+    // mass of the averaged target (1 for a row with selected entries, 0 for an empty one)
+    double mass = 0.0;
+    for (int s = tid; s < a.k_sel; s += 256) {
+        float pb = 0.f;
+        for (int j = 0; j < a.n_targets; ++j) pb += a.probs[j][row * a.k_sel + s];
+        mass += (double)(pb * w);
+    }
+    mass = block_sum(mass, redd, tid);
+
+    double multi = 0.0, avg = 0.0;
+    for (int s = tid; s < a.k_sel; s += 256) {
+        const float x = sc[s];
+        const bool fin = x > -INFINITY && x < INFINITY;
+        const float lq = fin ? (x - mx) - log_z : -INFINITY;
+        float pb = 0.f;
+        for (int j = 0; j < a.n_targets; ++j) {
+            const float p = a.probs[j][row * a.k_sel + s];
+            pb += p;
+            if (p > 0.f) multi += (double)(w * p * (logf(p) - lq));
+        }
+        pb *= w;
+        if (pb > 0.f) avg += (double)(pb * (logf(pb) - lq));
+        if (a.grad) a.grad[row * a.k_sel + s] = (fin ? expf(lq) : 0.f) * (float)mass - pb;
+    }
+    multi = block_sum(multi, redd, tid);
+    avg = block_sum(avg, redd, tid);
+    if (tid == 0) {
+        a.row_multi[row] = multi;
+        a.row_avg[row] = avg;
+    }
+}
+
+__global__ __launch_bounds__(256) void distill_sum_kernel(const double *row_multi, const double *row_avg, int64_t n,
+                                                          double *loss_multi, double *loss_avg)
+{
+    __shared__ double red[256];
+    const int tid = threadIdx.x;
+    double m = 0.0, v = 0.0;
+    for (int64_t r = tid; r < n; r += 256) {
+        m += row_multi[r];
+        v += row_avg[r];
+    }
+    m = block_sum(m, red, tid);
+    v = block_sum(v, red, tid);
+    if (tid == 0) {
+        if (loss_multi) *loss_multi = m;
+        if (loss_avg) *loss_avg = v;
+    }
+}
+
+} // namespace
+
+hipError_t launch_attn_probs(const ProbsArgs &a, int d_qk, hipStream_t st)
+{
+    const int64_t nq = (int64_t)a.B * a.Tq;
+    if (nq <= 0) return hipSuccess;
+    if (d_qk == 576)
+        hipLaunchKernelGGL(attn_probs_kernel<576>, dim3((unsigned)nq), dim3(256), 0, st, a);
+    else if (d_qk == 64)
+        hipLaunchKernelGGL(attn_probs_kernel<64>, dim3((unsigned)nq), dim3(256), 0, st, a);
+    else
+        return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+hipError_t launch_distill(const DistillArgs &a, int64_t nq, double *loss_multi, double *loss_avg, hipStream_t st)
+{
+    if (nq > 0) hipLaunchKernelGGL(distill_row_kernel, dim3((unsigned)nq), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(distill_sum_kernel, dim3(1), dim3(256), 0, st, (const double *)a.row_multi, (const double *)a.row_avg, nq,
+                       loss_multi, loss_avg);
+    return hipGetLastError();
+}
+
+} // namespace ic

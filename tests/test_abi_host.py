@@ -318,3 +318,24 @@ def test_greedy_argument_errors_need_no_gpu(ic):
     assert L.ic_pattern_loss(arr, 2, bytes([1, 0]), own, one, one, one, ws, None) == S.ERR_SHAPE
     assert L.ic_greedy_search_forward(arr, 2, 1, 1, refs, one, None, None, None, one, 1 << 30, None) == S.ERR_NULL
     assert L.ic_greedy_search_forward(arr, 2, 1, 1, refs, one, buf, None, None, one, 64, None) == S.ERR_WORKSPACE
+
+
+def test_distill_argument_errors_need_no_gpu(ic):
+    L, S = ic.lib(), ic.Status
+    one = C.c_void_p(4096)
+    atd = _atd(ic)
+    assert L.ic_attn_probs(None, one, one, one, one, one, None) == S.ERR_NULL
+    assert L.ic_attn_probs(C.byref(atd), one, one, one, None, one, None) == S.ERR_NULL         # the normalisers are required
+    assert L.ic_attn_probs(C.byref(_atd(ic, d_qk=128)), one, one, one, one, one, None) == S.ERR_UNSUPPORTED
+    ws = L.ic_distill_loss_workspace(1000)
+    assert ws >= 2 * 8000 and L.ic_distill_loss_workspace(0) > 0
+    ptrs = (C.c_void_p * 2)(4096, 8192)
+    assert L.ic_distill_loss(None, 2, one, 1000, 64, one, one, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_distill_loss(ptrs, 2, None, 1000, 64, one, one, None, one, ws, None) == S.ERR_NULL
+    assert L.ic_distill_loss(ptrs, 0, one, 1000, 64, one, one, None, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_distill_loss(ptrs, 17, one, 1000, 64, one, one, None, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_distill_loss(ptrs, 2, one, 1000, 0, one, one, None, one, ws, None) == S.ERR_SHAPE
+    assert L.ic_distill_loss(ptrs, 2, one, 1000, 64, None, None, None, one, ws, None) == S.ERR_NULL   # no output
+    assert L.ic_distill_loss(ptrs, 2, one, 1000, 64, one, one, None, one, 64, None) == S.ERR_WORKSPACE
+    bad = (C.c_void_p * 2)(4096, None)
+    assert L.ic_distill_loss(bad, 2, one, 1000, 64, one, one, None, one, ws, None) == S.ERR_NULL
