@@ -327,6 +327,13 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     const int64_t nq = (int64_t)a.B * a.Tq;
     const bool chain = !SPLIT && ntiles >= 3 && (int64_t)gridDim.x < nq;   // workgroup-uniform
     int64_t qrow = blockIdx.x;
+    if (chain && (gridDim.x & 7u) == 0) {
+        // Workgroup ids are dealt round-robin over the 8 XCDs, each with its own L2.  Give XCD x the
+        // contiguous queries x * grid/8 .. of every round of `grid` queries: neighbouring queries
+        // select largely the same rows, which then meet in one L2.
+        const unsigned per = gridDim.x >> 3;
+        qrow = (int64_t)(blockIdx.x & 7u) * per + (blockIdx.x >> 3);
+    }
     int64_t qnext = chain ? qrow + gridDim.x : nq;        // >= nq: this is the workgroup's last query
 
     // what the gather needs to know about a query: its index row, its cache and its length
