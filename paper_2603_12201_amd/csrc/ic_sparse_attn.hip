@@ -438,7 +438,12 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     // Chained form: Q of the next query goes straight into the accumulation registers while the
     // outputs of the current one are stored.  The compiler does not count these loads, which only
     // makes its own waits conservative; settle_q waits for them and ties every later use to that wait.
+    // Only wave 0 loads (each load touches 16 rows of Q, so four waves loading the same 36 KB keep the
+    // CU's one address unit busy for 2.8 us); it then hands Q to the other waves through the tile
+    // buffer that is free between two queries, in the very lane order the operand has.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto load_q_direct = [&](int64_t q) {
+        if (wave_u != 0) return;
         // the lane's offset into Q is recomputed from the lane id here: kept live across the tile
         // loop it would be spilled, and its reload would wait behind the gathers in flight
         int ln = lane;
@@ -475,16 +480,36 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             }
         }
     };
-    auto settle_q = [&]() {
-        asm volatile("s_waitcnt vmcnt(0)");
+    auto settle_q = [&](unsigned char *qx) {              // qx: 2 * KS KiB of free LDS
+        unsigned char *mine = qx + lane * 16;
+        if (wave_u == 0) {
+            asm volatile("s_waitcnt vmcnt(0)");
 #pragma unroll
-        for (int hb = 0; hb < 2; ++hb)
+            for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                u32x4 raw = __builtin_bit_cast(u32x4, qreg[hb][ks]);
-                asm volatile("" : "+a"(raw));
-                qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
-            }
+                for (int ks = 0; ks < KS; ++ks) {
+                    u32x4 raw = __builtin_bit_cast(u32x4, qreg[hb][ks]);
+                    asm volatile("" : "+a"(raw));
+                    qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+                    *(u32x4 *)(mine + (hb * KS + ks) * 1024) = raw;
+                }
+        }
+        __syncthreads();
+        if (wave_u != 0) {
+            u32x4 raw[2][KS];
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) raw[hb][ks] = *(const u32x4 *)(mine + (hb * KS + ks) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    asm volatile("" : "+a"(raw[hb][ks]));
+                    qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw[hb][ks]);
+                }
+        }
     };
     int g0 = 0;                                           // stream position of the query's tile 0 (buffer parity)
     {
@@ -722,15 +747,37 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
                 a.lse[qrow * a.H_q + l32] =
                     (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
+            // accumulator element i belongs to head 8 (i / 4) + 4 hh + i % 4: the sums of the lane's
+            // 16 heads come straight from the four waves' partials (independent 16-byte reads; a
+            // lane-to-lane shuffle per head would be sixteen dependent trips through the crossbar)
+            f32x4 inv4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 l4 = *(const f32x4 *)(lbuf + 8 * q + 4 * hh);
+#pragma unroll
+                for (int w = 1; w < 4; ++w) l4 += *(const f32x4 *)(lbuf + 32 * w + 8 * q + 4 * hh);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) inv4[q][r] = (l4[r] > 0.f) ? __builtin_amdgcn_rcpf(l4[r]) : 0.f;
+            }
+            const bool all_heads = a.H_q >= 32;               // workgroup-uniform
+            // the lane's offset into O is recomputed from the thread id here: kept live across the
+            // tile loop it is spilled, and its reload waits behind every gather in flight
+            int tx = tid;
+            asm volatile("" : "+v"(tx));
+            const int o_lane = 32 * (tx >> 6) + (tx & 31), o_hh = (tx >> 5) & 1;
+            __bf16 *o_row = (__bf16 *)a.O + qrow * a.H_q * D_V + o_lane;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);   // O row (head) of accumulator element i
-                const float l = __shfl(l_head, hq);
-                if (hq >= a.H_q) continue;
-                const float inv = (l > 0.f) ? 1.f / l : 0.f;
-                __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + 32 * wave + l32;
+                const int hq = 8 * (i >> 2) + 4 * o_hh + (i & 3); // O row (head) of accumulator element i
+                const float inv = inv4[i >> 2][i & 3];
+                __bf16 *po = o_row + hq * D_V;
+                if (all_heads) {
 #pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
+                    for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
+                } else if (hq < a.H_q) {
+#pragma unroll
+                    for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = (__bf16)(oacc[nb][i] * inv);
+                }
             }
         }
     };
@@ -787,7 +834,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
                 l_own[hb] = 0.f;
             }
             m_c = -INFINITY;
-            settle_q();
+            settle_q(tbuf + ((g0 ^ 1) & 1) * TBUFB);      // the drained tile's buffer: nobody touches it before step 0's barrier
         }
     }
 }
