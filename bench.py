@@ -155,6 +155,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--greedy-layers", type=int, default=6)
+    ap.add_argument("--no-fp8", action="store_true")
     ap.add_argument("--distill-targets", type=int, default=4)
     ap.add_argument("--no-overlap", action="store_true", help="skip the cross-layer overlap diagnostic arm")
     ap.add_argument("--overlap-layers", type=int, default=48)
@@ -437,6 +438,26 @@ def main():
             "loss_multi": float(lm_d), "loss_avg": float(la_d),
             "note": "identical targets here, so Eq. 1 = Eq. 2; timing only"}
         del probs_d, atd, idx_d, sel_d
+
+    # ---------------- the FP8 indexer at configs[4] (L = 131072, 64 heads, e4m3 + per-token scales) ----------------
+    if not args.no_fp8:
+        log("fp8 indexer arm (configs[4], one Full layer)")
+        c4 = synth.config("c4")
+        l4 = synth.indexer_layer(c4, 0, device="cuda")
+        from paper_2603_12201_amd import binding as icb
+        ws4 = torch.empty(ic.indexer_topk_workspace(icb.indexer_desc(l4["q"], l4["k"], l4["w"], c4["k_sel"], 0,
+                                                                     l4["q_scale"], l4["k_scale"])), dtype=torch.uint8, device="cuda")
+        idx4 = torch.empty((c4["B"], c4["Tq"], c4["k_sel"]), dtype=torch.int32, device="cuda")
+        run4 = lambda: ic.indexer_topk(l4["q"], l4["k"], l4["w"], c4["k_sel"], 0, q_scale=l4["q_scale"], k_scale=l4["k_scale"],
+                                       idx=idx4, workspace=ws4)
+        ms4 = time_steps(run4, 2, 1)
+        flop4 = 2.0 * c4["H_I"] * c4["d_I"] * (c4["Tq"] * (c4["Tq"] + 1) / 2)
+        arms["indexer_fp8_c4"] = {
+            "L": c4["Tq"], "H_I": c4["H_I"], "ms_indexer_plus_topk": ms4,
+            "tokens_per_s_one_full_layer": c4["Tq"] / (ms4 * 1e-3),
+            "score_flop": flop4, "PFLOPs_incl_topk": flop4 / (ms4 * 1e-3) / 1e15, "peak_PFLOPs": 5.0,
+            "note": "wall time of ic_indexer_topk; per-kernel split in profiles/indexer_fp8_131k_kernel_trace.txt"}
+        del l4, ws4, idx4
 
     out = {
         "metric": "prefill & decode tokens/s, 48-layer DSA stack L=32K, 1-in-4 Full vs all-Full",
