@@ -138,7 +138,7 @@ size_t attn_ws_bytes(const ic_attn_desc *d)
     attn_splits(d, &ns, &sl);
     if (ns <= 1) return 0;
     const size_t nq = (size_t)d->B * d->Tq;
-    return align_up(nq * ns * d->H_q * d->d_v * sizeof(float)) + align_up(nq * ns * d->H_q * 2 * sizeof(float));
+    return align_up(nq * ns * d->H_q * d->d_v * 2) + align_up(nq * ns * d->H_q * 2 * sizeof(float));   // bf16 partial outputs, fp32 (max, sum)
 }
 
 // ragged / paged cache description -> the kernels' view (all-zero when pc is NULL)
@@ -269,8 +269,8 @@ ic_status run_attn(const ic_attn_desc *d, const void *Q, const void *KV, const i
     a.pv = paged_view(pc);
     if (a.n_splits > 1) {
         const size_t nq = (size_t)d->B * d->Tq;
-        a.part_o = (float *)ws;
-        a.part_ml = (float *)((char *)ws + align_up(nq * a.n_splits * d->H_q * d->d_v * sizeof(float)));
+        a.part_o = (__bf16 *)ws;
+        a.part_ml = (float *)((char *)ws + align_up(nq * a.n_splits * d->H_q * d->d_v * 2));
     }
     {
         ProfScope ps(2, st);

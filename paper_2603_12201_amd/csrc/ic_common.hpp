@@ -72,7 +72,7 @@ struct AttnArgs {
     const int32_t *idx;   // [B,Tq,k_sel]
     void *O;              // [B,Tq,H_q,d_v] bf16
     float *lse;           // [B,Tq,H_q] or nullptr
-    float *part_o;        // split partials: [B*Tq, n_splits, H_q, d_v] fp32 (unnormalised)
+    __bf16 *part_o;       // split partials: [B*Tq, n_splits, H_q, d_v] bf16, each normalised by its own row sum
     float *part_ml;       // [B*Tq, n_splits, H_q, 2] fp32 (running max in log2 units, sum)
     int32_t B, Tq, Lk, H_q, v_off, row_elems, k_sel;
     int32_t n_splits, split_len; // key slots per split (multiple of 64)

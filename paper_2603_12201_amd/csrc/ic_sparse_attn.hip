@@ -224,16 +224,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
         const int hq = 16 * mh + hr;
         const float l = __shfl(l_tot, hr);                // the sum lives in the lanes with l16 == hr
         if (hq >= a.H_q) continue;
-        if (split) {
-            float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + DVW * vh;
+        // a split stores its own normalised output (bf16, like the final one); the merge weighs the
+        // splits by their share of the total row sum
+        const float inv = (l > 0.f) ? 1.f / l : 0.f;
+        __bf16 *po = (split ? a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V
+                            : (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V) + DVW * vh;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) po[16 * nb + l16] = oacc[nb][i];
-        } else {
-            const float inv = (l > 0.f) ? 1.f / l : 0.f;
-            __bf16 *po = (__bf16 *)a.O + (qrow * a.H_q + hq) * D_V + DVW * vh;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) po[16 * nb + l16] = (__bf16)(oacc[nb][i] * inv);
-        }
+        for (int nb = 0; nb < NB; ++nb) po[16 * nb + l16] = (__bf16)(oacc[nb][i] * inv);
     }
 }
 
@@ -728,25 +725,20 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         __syncthreads();
         const float l_head = lbuf[l32] + lbuf[32 + l32] + lbuf[64 + l32] + lbuf[96 + l32];   // head l32
         const float m_head = m_c;
-        if constexpr (SPLIT) {
-            // partial of this split: accumulators and row sum in the reference m_head
-            if (wave == 0 && hh == 0 && l32 < a.H_q) {
-                float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + l32) * 2;
-                ml[0] = m_head;
-                ml[1] = l_head;
+        {
+            if constexpr (SPLIT) {
+                // partial of this split: its reference maximum and row sum (the output below is
+                // normalised by that sum; the merge weighs the splits by their share of the total)
+                if (wave == 0 && hh == 0 && l32 < a.H_q) {
+                    float *ml = a.part_ml + ((qrow * a.n_splits + sp) * a.H_q + l32) * 2;
+                    ml[0] = m_head;
+                    ml[1] = l_head;
+                }
+            } else {
+                if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
+                    a.lse[qrow * a.H_q + l32] =
+                        (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
             }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int hq = 8 * (i >> 2) + 4 * hh + (i & 3);
-                if (hq >= a.H_q) continue;
-                float *po = a.part_o + ((qrow * a.n_splits + sp) * a.H_q + hq) * D_V + 32 * wave + l32;
-#pragma unroll
-                for (int nb = 0; nb < NBW; ++nb) po[128 * nb] = oacc[nb][i];
-            }
-        } else {
-            if (wave == 0 && hh == 0 && l32 < a.H_q && a.lse)
-                a.lse[qrow * a.H_q + l32] =
-                    (l_head > 0.f) ? (m_head + __builtin_log2f(l_head)) * 0.6931471805599453f : -INFINITY;
             // accumulator element i belongs to head 8 (i / 4) + 4 hh + i % 4: the sums of the lane's
             // 16 heads come straight from the four waves' partials (independent 16-byte reads; a
             // lane-to-lane shuffle per head would be sixteen dependent trips through the crossbar)
@@ -765,7 +757,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             int tx = tid;
             asm volatile("" : "+v"(tx));
             const int o_lane = 32 * (tx >> 6) + (tx & 31), o_hh = (tx >> 5) & 1;
-            __bf16 *o_row = (__bf16 *)a.O + qrow * a.H_q * D_V + o_lane;
+            __bf16 *o_row = (SPLIT ? a.part_o + (qrow * a.n_splits + sp) * a.H_q * D_V : (__bf16 *)a.O + qrow * a.H_q * D_V) + o_lane;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int hq = 8 * (i >> 2) + 4 * o_hh + (i & 3); // O row (head) of accumulator element i
@@ -839,7 +831,8 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     }
 }
 
-// Combine the per-split partials of one (query, head): O = sum_s O_s 2^(m_s-m) / sum_s l_s 2^(m_s-m).
+// Combine the per-split partials of one (query, head): O = sum_s w_s O_s / sum_s w_s with O_s the split's own
+// normalised output and w_s = l_s 2^(m_s-m) its share of the row sum.
 // One workgroup per (query, head); a thread owns 4 consecutive value columns.
 template <int D_V>
 __global__ __launch_bounds__(D_V / 4) void attn_merge_kernel(AttnArgs a)
@@ -853,13 +846,14 @@ __global__ __launch_bounds__(D_V / 4) void attn_merge_kernel(AttnArgs a)
     for (int s = 0; s < a.n_splits; ++s) m = fmaxf(m, ml[s * ml_stride]);
     float l = 0.f;
     f32x4 o = {0.f, 0.f, 0.f, 0.f};
-    const float *po = a.part_o + ((qrow * a.n_splits) * a.H_q + h) * D_V + v;
+    const __bf16 *po = a.part_o + ((qrow * a.n_splits) * a.H_q + h) * D_V + v;
     for (int s = 0; s < a.n_splits; ++s) {
         const float ms = ml[s * ml_stride], ls = ml[s * ml_stride + 1];
-        const float sc = (ms == -INFINITY) ? 0.f : fast_exp2(ms - m);
-        l += ls * sc;
-        const f32x4 x = *(const f32x4 *)(po + (int64_t)s * a.H_q * D_V);
-        o += x * sc;
+        const float sc = (ms == -INFINITY) ? 0.f : ls * fast_exp2(ms - m);   // the split's share of the row sum
+        l += sc;
+        const s16x4 x = *(const s16x4 *)(po + (int64_t)s * a.H_q * D_V);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] += __uint_as_float((uint32_t)(uint16_t)x[j] << 16) * sc;   // bf16 -> fp32 is a shift
     }
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     __bf16 *out = (__bf16 *)a.O + (qrow * a.H_q + h) * D_V + v;
