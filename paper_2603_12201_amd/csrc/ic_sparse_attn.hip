@@ -388,7 +388,8 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             }
         }
     };
-    load_q(qrow);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    if (wave_u == 0) load_q(qrow);                        // one wave loads Q (see load_q_direct below) and hands it over
     f32x16 oacc[NBW];
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
@@ -438,7 +439,6 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     // Only wave 0 loads (each load touches 16 rows of Q, so four waves loading the same 36 KB keep the
     // CU's one address unit busy for 2.8 us); it then hands Q to the other waves through the tile
     // buffer that is free between two queries, in the very lane order the operand has.
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto load_q_direct = [&](int64_t q) {
         if (wave_u != 0) return;
         // the lane's offset into Q is recomputed from the lane id here: kept live across the tile
@@ -514,6 +514,23 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         ids_n2 = fetch_ids(2);
         gload(d0, 0);
         __builtin_amdgcn_sched_barrier(0);
+        {   // Q from wave 0 to the others through the second tile buffer (unused until step 0 stages tile 1)
+            unsigned char *mine = tbuf + TBUFB + lane * 16;
+            if (wave_u == 0) {
+#pragma unroll
+                for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) *(u32x4 *)(mine + (hb * KS + ks) * 1024) = qraw[hb][ks];
+            }
+            __syncthreads();
+            if (wave_u != 0) {
+#pragma unroll
+                for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) qraw[hb][ks] = *(const u32x4 *)(mine + (hb * KS + ks) * 1024);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
         pin_q();
         vm_cur = ids_mask(d0);
         vm_n1 = ids_mask(d1);
