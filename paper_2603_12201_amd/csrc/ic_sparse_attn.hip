@@ -389,7 +389,6 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         }
     };
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    if (wave_u == 0) load_q(qrow);                        // one wave loads Q (see load_q_direct below) and hands it over
     f32x16 oacc[NBW];
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb)
@@ -512,6 +511,10 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     {
         const Ids d0 = fetch_ids(0), d1 = fetch_ids(1);
         ids_n2 = fetch_ids(2);
+        __builtin_amdgcn_sched_barrier(0);
+        // one wave loads Q (see load_q_direct above) and hands it over; its loads go out behind the
+        // id fetches, so that the ids, and with them the first gather, do not wait for Q
+        if (wave_u == 0) load_q(qrow);
         gload(d0, 0);
         __builtin_amdgcn_sched_barrier(0);
         {   // Q from wave 0 to the others through the second tile buffer (unused until step 0 stages tile 1)
