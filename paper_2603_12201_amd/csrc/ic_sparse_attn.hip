@@ -1,11 +1,16 @@
 // Sparse MQA core attention over the selected KV rows (paper Sec. 2.1: the main attention is
 // computed only over the top-k subset; MLA form, one shared KV row per position).
 //
-// One workgroup (4 waves) per query token and key-slot split; two workgroups fit a CU (75 KB of
-// LDS, <= 256 VGPRs each) so that one computes while the other waits for its gather.  Tiles of
-// 32 selected rows are gathered with 16-byte coalesced loads (each row is contiguous) into a
-// double-buffered LDS tile, row-major.  A wave owns 16 of the 32 heads and half of the value
-// columns, and runs its own online softmax over every row of the tile:
+// Two kernels.  MLA rows whose values are their first features (576 / 512) take the row-slab
+// form further down: one workgroup per CU, 64-row tiles, walking a chain of queries when there are
+// more queries than CUs, or one (query, split) each when there are fewer (decode).  Every other
+// supported layout takes the small-tile form described here.
+//
+// Small-tile form: one workgroup (4 waves) per query token and key-slot split; two workgroups
+// fit a CU (75 KB of LDS, <= 256 VGPRs each) so that one computes while the other waits for its
+// gather.  Tiles of 32 selected rows are gathered with 16-byte coalesced loads (each row is
+// contiguous) into a double-buffered LDS tile, row-major.  A wave owns 16 of the 32 heads and half
+// of the value columns, and runs its own online softmax over every row of the tile:
 //   S^T = K Q^T   v_mfma_f32_16x16x32_bf16, A = tile rows (16-byte LDS reads), B = Q (registers)
 //   P   = exp2(S^T * scale*log2e - m)   in the result layout: a lane owns one head, 8 keys
 //   O  += P V     same MFMA; P is already an A operand (its contraction slots are whatever keys
@@ -13,8 +18,11 @@
 //                 transpose read ds_read_b64_tr_b16, which hands a lane one value column of four
 //                 consecutive tile rows.  No transposed copy of V is ever made.
 // The two waves of a head group compute the same S^T (cheap next to the gather) and therefore
-// the same softmax statistics, so no exchange between waves is ever needed.  With several
-// splits per query the unnormalised partials go to the workspace and a small kernel merges them.
+// the same softmax statistics, so no exchange between waves is ever needed.
+//
+// Splits (both forms): a split stores its own normalised output in bf16 together with its
+// reference maximum and row sum; attn_merge_kernel weighs the splits by their share of the total
+// row sum.
 #include "ic_common.hpp"
 #include <type_traits>
 
@@ -235,9 +243,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 }
 
 // ---- row-slab form (576/512 MLA rows) --------------------------------------------------
-// One workgroup (4 waves, one per SIMD, the whole register file) per query, for launches with
-// enough queries to fill the chip; tiles of 64 selected rows, two tiles resident in LDS.  Wave w owns rows 16w..16w+15 of a tile
-// in the producer role and value columns 32w + 128nb + (0..31) in the consumer role:
+// One workgroup (4 waves, one per SIMD, the whole register file) per CU; tiles of 64 selected
+// rows, two tiles resident in LDS.  Wave w owns rows 16w..16w+15 of a tile in the producer role
+// and value columns 32w + 128nb + (0..31) in the consumer role:
 //   gather    eight lanes fetch one 128-byte line of a row (the access shape the vector memory
 //             path serves fastest), 18 loads per lane and tile, refilled in place one tile ahead
 //   stage     the wave stores its own 16 rows to the LDS tile (after the barrier of the previous
@@ -251,6 +259,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 //             steps are exactly the four waves' row groups; V comes out of the same row-major
 //             tile through the LDS transpose read, once per element.
 // Row sums stay with the producers in their own reference and are combined once at the end.
+// The consumer role lags the producer role by one tile (a step = produce tile it, consume tile
+// it-1), so the previous tile's operand reads run under the softmax arithmetic and the staging
+// stores under the PV MFMAs.
+// Between two queries of a chain: the last two steps already gather and stage the next query's
+// first tiles; one wave loads the next Q straight into the accumulation registers while the
+// outputs are stored and hands it to the other waves through the tile buffer that is idle at
+// that moment (see the driver at the end of the kernel).
 constexpr int kSlabTile = 64;
 constexpr float kLazyLog2 = 8.f;
 

@@ -9,8 +9,15 @@
 //            single read of the row from HBM; rows of up to `cache_elems` keys stay in LDS
 //   pass 2,3 12 + 8 bits; only entries that match the prefix found so far touch the histogram,
 //            so these are read-mostly sweeps over the cached row
-//   emit     wave scan of per-thread counts (greater/equal packed in one word) + a scan of the
-//            wave totals; a thread owns 4 consecutive positions in every sweep
+//   emit     a thread owns 4 consecutive positions in every sweep.  When every entry equal to the
+//            k-th key is selected (the usual case: known from the last histogram) "selected" is
+//            the single test key >= tau: per-thread counts of two sweeps packed in one word, one
+//            wave scan per word on the DPP path, one scan over the (sweep, wave) cells, two
+//            barriers in all.  When ties are cut at the boundary: per-sweep scans of packed
+//            greater / equal counts.
+// Three forms by row length: keys cached in LDS (<= 32768), keys in registers (<= 65536, the
+// decode shape, with the first-digit histogram spread over 8 counters per bin), and a streaming
+// form that re-reads the row on every sweep (longer rows).
 #include "ic_common.hpp"
 
 namespace ic {
