@@ -11,16 +11,24 @@
 // loop; key tiles (64 keys) are staged through LDS, double buffered, one barrier per tile,
 // and shared by the four waves of the workgroup (each wave owns TPW tokens).
 //
-// Occupancy.  A wave cannot overlap its own MFMAs with its own VALU epilogue (both issue through
-// the same port), and the epilogue costs about as many cycles as the MFMAs.  Two workgroups per
-// CU (two waves per SIMD, <= 256 registers each) let one wave's epilogue run under the other's
-// MFMAs; that caps a wave at 3 tokens (96 q + 48 w registers), which still reuses every B
-// operand read from LDS three times (LDS return bandwidth, ~64 B/clk/CU, is the next limit).
+// Schedule.  A wave's work is a stream of units (32 keys x one token x one head tile): a chain of
+// KS MFMAs into a fresh accumulator, then 16 max/fma pairs on the result.  The chain of unit c + 1
+// is issued one MFMA at a time between the epilogue steps of unit c (a scheduling barrier after each
+// MFMA + its share of the epilogue pins that order), and the stream runs on across key tiles: the
+// first chain of the next tile is issued under the last epilogue of this one.  For that the tile
+// hand-over sits in the middle of a tile -- after the wave's last LDS read of the tile the other
+// buffer is refilled, and the barrier that publishes it comes two units later, just before the first
+// read of the next tile.  Tiles on the causal diagonal or at a ragged end take a plain, checked path.
+// Two workgroups per CU (two waves per SIMD, <= 256 registers each) cover what bubbles remain (LDS
+// read latency at the start of a subtile, the barrier); that caps a wave at 3 tokens (96 q + 48 w
+// registers), which still reuses every B operand read from LDS three times.
 //
 // The kernel writes scores of the query rows in flight into a strip (rows x Lk fp32); it
 // never holds more rows than the caller's workspace allows.  Keys hidden by the causal mask
 // are not written.
 #include "ic_common.hpp"
+
+#include <type_traits>
 
 namespace ic {
 
@@ -78,12 +86,19 @@ template <int RB, int LPT, int ROWB, int NT>
 __device__ __forceinline__ void tile_lstore(const u32x4 (&pre)[LPT], unsigned char *buf, int tid)
 {
     constexpr int CPR = RB / 16;
+    static_assert(NT % CPR == 0, "a thread keeps its chunk column over the tile");
+    unsigned char *p = buf + (tid / CPR) * ROWB + (tid % CPR) * 16;
 #pragma unroll
-    for (int r = 0; r < LPT; ++r) {
-        const int c = tid + NT * r;
-        const int row = c / CPR, col = c % CPR;
-        *(u32x4 *)(buf + row * ROWB + col * 16) = pre[r];
-    }
+    for (int r = 0; r < LPT; ++r) *(u32x4 *)(p + r * (NT / CPR) * ROWB) = pre[r];
+}
+
+// The same load for a tile whose 64 rows all exist: one lane offset, constant strides.
+template <int LPT, int NT>
+__device__ __forceinline__ void tile_gload_full(u32x4 (&pre)[LPT], const unsigned char *tile, int tid)
+{
+    const unsigned off = (unsigned)tid * 16u;
+#pragma unroll
+    for (int r = 0; r < LPT; ++r) pre[r] = *(const u32x4 *)(tile + r * NT * 16 + off);
 }
 
 // ReLU on the bit pattern: a non-positive float (including -0) is a non-positive integer.
@@ -190,114 +205,212 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     // Combine the two half-wave partial sums of a token pair (or of one token with itself) and
     // store 32 scores per row.  permlane32_swap(x, y) returns {[x.lo, y.lo], [x.hi, y.hi]}: their
     // sum is token A's total in lanes 0-31 and token B's in lanes 32-63.
-    auto emit = [&](float pa, float pb, bool pair, int j, int s0, bool interior) {
+    auto emit = [&](float pa, float pb, bool pair, int j, int s0, int r32_x, int half_x) {
         const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(pa), __float_as_uint(pb), false, false);
         float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-        const int t = t_w0 + j + half;
-        const int s = s0 + r32;
-        const bool lane_on = pair || half == 0;
+        const int t = t_w0 + j + half_x;
+        const int s = s0 + r32_x;
+        const bool lane_on = pair || half_x == 0;
         if (FP8) {
             // positive per-token scales commute with the ReLU gate: I = sq[t] sk[s] sum_j w_j ReLU(q8_j . k8)
-            const float sq = (pair && half) ? sqr[(j + 1) % TPW] : sqr[j];
+            const float sq = (pair && half_x) ? sqr[(j + 1) % TPW] : sqr[j];
             v *= sq * ksc[min(s, Lk_b - 1)];
         }
-        if (lane_on && (interior || (t < i_end && s < Lk_b && (int64_t)s <= q_pos0 + t))) {
+        if (lane_on && t < i_end && s < Lk_b && (int64_t)s <= q_pos0 + t) {
             const int64_t srow = (int64_t)blockIdx.z * a.Ri + (t - a.i0);
             a.strip[srow * a.ld + s] = v;
         }
     };
 
-    for (int it0 = 0; it0 < ntiles; it0 += PD) {
+    if constexpr (STREAM) {
+        for (int it0 = 0; it0 < ntiles; it0 += PD) {
 #pragma unroll
-      for (int ph = 0; ph < PD; ++ph) {
-        const int it = it0 + ph;
-        if (it >= ntiles) break;                            // workgroup-uniform
-        const int kt = kc0 + it * TILE;
-        const int buf = it & 1;
-        if (it + PD < ntiles) tile_gload<RB, LPT, NT>(pre[ph], tile_ptr(kt + PD * TILE), Lk_b - (kt + PD * TILE), tid);
-
-        // Interior tile: all 64 keys are visible to every token of this wave and every token is a
-        // real row, so nothing needs masking and the whole tile is one straight-line block.
-        const bool interior = (t_w0 + TPW <= i_end) && (kt + TILE <= Lk_b) &&
-                              ((int64_t)(kt + TILE - 1) <= q_pos0 + t_w0);
-        if (interior && !STREAM) {
-            // Software pipeline over the units (key subtile, token, head tile): the MFMA chain of unit
-            // c+1 is issued before the ReLU/weight/sum epilogue of unit c, so the matrix pipe works
-            // under this wave's own VALU epilogue as well as under the other wave's.
-            Op kb[KS];                                      // B operands of the subtile being multiplied
-            auto load_kb = [&](int sub) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    kb[ks] = F::load(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 2 + half) * OPB]);
-            };
-            constexpr int NCH = 2 * TPW * HT;
-            f32x16 acc[2];
-            float part[TPW];
-            auto chain = [&](int c) -> f32x16 {
-                const int x = c / HT, ht = c % HT, j = x % TPW;
-                if (c % (TPW * HT) == 0) load_kb(x / TPW);  // first unit of a subtile
-                f32x16 r;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) r[i] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    r = F::mma(qa[j][ht][ks], kb[ks], r);
-                return r;
-            };
-            acc[0] = chain(0);
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                if (c + 1 < NCH) acc[(c + 1) & 1] = chain(c + 1);
-                const int x = c / HT, ht = c % HT, sub = x / TPW, j = x % TPW;
-                float s_acc = (ht == 0) ? 0.f : part[j];
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    s_acc = fmaf(relu(acc[c & 1][i]), wr[j][ht][i], s_acc);
-                part[j] = s_acc;
-                if (ht == HT - 1) {
-                    if (j & 1) emit(part[j - 1], part[j], true, j - 1, kt + sub * 32, true);
-                    else if (j == TPW - 1) emit(part[j], part[j], false, j, kt + sub * 32, true);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                const int s0 = kt + sub * 32;
-                if (s0 >= wave_vis) continue;               // wave-uniform: hidden from all its tokens
-                if (STREAM && (sub != (wave & 1) || (it & 1) != (wave >> 1))) continue;   // another wave's turn
+          for (int ph = 0; ph < PD; ++ph) {
+            const int it = it0 + ph;
+            if (it >= ntiles) break;                        // workgroup-uniform
+            const int kt = kc0 + it * TILE;
+            const int buf = it & 1;
+            if (it + PD < ntiles) tile_gload<RB, LPT, NT>(pre[ph], tile_ptr(kt + PD * TILE), Lk_b - (kt + PD * TILE), tid);
+            const int sub = wave & 1;                       // this wave's subtile; tiles alternate between wave pairs
+            const int s0 = kt + sub * 32;
+            if (s0 < wave_vis && (it & 1) == (wave >> 1)) {
                 Op kb[KS];
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
                     kb[ks] = F::load(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 2 + half) * OPB]);
-                float part[TPW];
+                float s_acc = 0.f;
+#pragma unroll
+                for (int ht = 0; ht < HT; ++ht) {
+                    f32x16 acc;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        acc = F::mma(qa[0][ht][ks], kb[ks], acc);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        s_acc = fmaf(relu(acc[i]), wr[0][ht][i], s_acc);
+                }
+                emit(s_acc, s_acc, false, 0, s0, r32, half);
+            }
+            if (it + 1 < ntiles) tile_lstore<RB, LPT, ROWB, NT>(pre[(ph + 1) % PD], &lds[buf ^ 1][0], tid);
+            __syncthreads();
+          }
+        }
+    } else {
+        static_assert(STREAM || PD == 1, "the tiled form keeps one key tile in flight");
+        static_assert(16 % KS == 0, "epilogue elements per MFMA step");
+        constexpr int NCH = 2 * TPW * HT;                   // units (key subtile, token, head tile) per key tile
+        constexpr int HALF = TPW * HT;                      // units per key subtile
+        constexpr int EPC = 16 / KS;                        // epilogue elements that ride under one MFMA
+
+        // Leading tiles in which all 64 keys are visible to every token of this wave and every token is
+        // a real row: nothing needs masking there.  The remaining tiles (the causal diagonal, a ragged
+        // end) take the checked path.
+        int n_int = 0;
+        if (t_w0 + TPW <= i_end) {
+            const int64_t lim = min((int64_t)Lk_b, q_pos0 + t_w0 + 1);
+            const int64_t n = (lim - kc0) / TILE;
+            n_int = (int)(n < 0 ? 0 : (n > ntiles ? ntiles : n));
+        }
+
+        // Hand-over of a tile: once every LDS read of tile `it` has been issued by this wave, the other
+        // buffer (last read for tile it - 1, before the previous barrier) takes tile it + 1 and the
+        // registers take tile it + 2.  The barrier that publishes the buffer follows later in the tile,
+        // before the first read of tile it + 1, so the four waves rarely wait for one another.
+        auto stage = [&](int it, int tid_x, auto steady_c) {
+            if (decltype(steady_c)::value) {
+                // tile it + 1 follows for certain and tile it + 2, if there is one, has all its 64 rows;
+                // past the end the load repeats tile it + 1 instead of being skipped, which keeps the
+                // steady-state loop body free of branches
+                tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[(it + 1) & 1][0], tid_x);
+                const int kn = kc0 + (it + 2 < ntiles ? it + 2 : it + 1) * TILE;
+                tile_gload_full<LPT, NT>(pre[0], tile_ptr(kn), tid_x);
+            } else {
+                if (it + 1 < ntiles) tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[(it + 1) & 1][0], tid_x);
+                if (it + 2 < ntiles) {
+                    const int kn = kc0 + (it + 2) * TILE;
+                    tile_gload<RB, LPT, NT>(pre[0], tile_ptr(kn), Lk_b - kn, tid_x);
+                }
+            }
+        };
+        if (ntiles > 1) tile_gload<RB, LPT, NT>(pre[0], tile_ptr(kc0 + TILE), Lk_b - (kc0 + TILE), tid);
+
+        // Unmasked store of two 32-score runs: lanes 0-31 write token ja at keys sa.., lanes 32-63 token
+        // jb at keys sb.. (pa / pb: the half-wave partial sums of those two runs).
+        float *const srow0 = a.strip + ((int64_t)blockIdx.z * a.Ri + (t_w0 - a.i0)) * a.ld + r32;
+        auto emit_full = [&](float pa, float pb, int ja, int sa, int jb, int sb) {
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(pa), __float_as_uint(pb), false, false);
+            float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+            const int j = half ? jb : ja, s = half ? sb : sa;
+            if (FP8) v *= (half ? sqr[jb] : sqr[ja]) * ksc[s + r32];
+            srow0[(int64_t)j * a.ld + s] = v;
+        };
+
+        Op kb[KS];
+        f32x16 acc[2];
+        float part[TPW];
+        float held = 0.f;                                   // odd TPW: the last token's sum over subtile 0
+        auto load_kb = [&](int buf, int sub) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kb[ks] = F::load(&lds[buf][(sub * 32 + r32) * ROWB + (ks * 2 + half) * OPB]);
+        };
+        auto mma_step = [&](int u, int ks) {                // MFMA ks of unit u's chain
+            const int x = u / HT, ht = u % HT, j = x % TPW;
+            f32x16 c0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c0[i] = 0.f;
+            acc[u & 1] = F::mma(qa[j][ht][ks], kb[ks], ks == 0 ? c0 : acc[u & 1]);
+        };
+        // One interior tile, software pipelined over its units and into the next tile: the MFMA chain of
+        // unit c + 1 is issued one instruction at a time between the ReLU/weight/sum steps of unit c, so
+        // the matrix pipe never waits for this wave's VALU work.  On entry the chain of unit 0 is in
+        // flight and kb holds subtile 0; NEXT: another interior tile follows.
+        auto tile_body = [&](const int it, const int tid_x, auto next_c) {
+            constexpr bool NEXT = decltype(next_c)::value;
+            const int kt = kc0 + it * TILE, buf = it & 1;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const int x = c / HT, ht = c % HT, sub = x / TPW, j = x % TPW;
+                if (c + 1 == HALF) load_kb(buf, 1);
+                if (c + 1 == NCH && NEXT) load_kb(buf ^ 1, 0);
+                float s_acc = (ht == 0) ? 0.f : part[j];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    if (c + 1 < NCH || NEXT) mma_step((c + 1) % NCH, ks);
+#pragma unroll
+                    for (int i = ks * EPC; i < (ks + 1) * EPC; ++i)
+                        s_acc = fmaf(relu(acc[c & 1][i]), wr[j][ht][i], s_acc);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                part[j] = s_acc;
+                if (ht == HT - 1) {
+                    if (j & 1) emit_full(part[j - 1], part[j], j - 1, kt + sub * 32, j, kt + sub * 32);
+                    else if (j == TPW - 1) {
+                        if (sub == 0) held = part[j];
+                        else emit_full(held, part[j], j, kt, j, kt + 32);
+                    }
+                }
+                if (c + 1 == HALF) stage(it, tid_x, next_c);
+                if (c + 2 == NCH) __syncthreads();
+            }
+        };
+
+        int it = 0;
+        if (n_int > 0) {
+            load_kb(0, 0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) mma_step(0, ks);
+        }
+        // steady state: the next tile is interior too and the one after it is not a ragged last tile
+        const int n_steady = min(n_int - 1, kc0 + ntiles * TILE <= Lk_b ? ntiles : ntiles - 3);
+        for (; it < n_steady; ++it) tile_body(it, tid, std::true_type{});
+        // What the remaining tiles need of the lane's position is rebuilt from the thread id behind a
+        // compiler barrier, so that none of it occupies registers during the steady-state loop.
+        int tid_c = tid;
+        asm volatile("" : "+v"(tid_c));
+        if (it < n_int) {
+            tile_body(it, tid_c, std::false_type{});
+            ++it;
+        }
+        const int r32_c = tid_c & 31, half_c = (tid_c >> 5) & 1;
+        for (; it < ntiles; ++it) {
+            const int kt = kc0 + it * TILE, buf = it & 1;
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int s0 = kt + sub * 32;
+                if (s0 >= wave_vis) continue;               // wave-uniform: hidden from all its tokens
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    kb[ks] = F::load(&lds[buf][(sub * 32 + r32_c) * ROWB + (ks * 2 + half_c) * OPB]);
+                float ps[TPW];
 #pragma unroll
                 for (int j = 0; j < TPW; ++j) {
                     float s_acc = 0.f;
 #pragma unroll
                     for (int ht = 0; ht < HT; ++ht) {
-                        f32x16 acc;
+                        f32x16 r;
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                        for (int i = 0; i < 16; ++i) r[i] = 0.f;
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks)
-                            acc = F::mma(qa[j][ht][ks], kb[ks], acc);
+                            r = F::mma(qa[j][ht][ks], kb[ks], r);
 #pragma unroll
                         for (int i = 0; i < 16; ++i)
-                            s_acc = fmaf(relu(acc[i]), wr[j][ht][i], s_acc);
+                            s_acc = fmaf(relu(r[i]), wr[j][ht][i], s_acc);
                     }
-                    part[j] = s_acc;
+                    ps[j] = s_acc;
                 }
 #pragma unroll
                 for (int j = 0; j < TPW; j += 2) {
                     const bool pair = j + 1 < TPW;
-                    emit(part[j], pair ? part[j + 1] : part[j], pair, j, s0, false);
+                    emit(ps[j], pair ? ps[j + 1] : ps[j], pair, j, s0, r32_c, half_c);
                 }
             }
+            stage(it, tid_c, std::false_type{});
+            __syncthreads();
         }
-
-        if (it + 1 < ntiles) tile_lstore<RB, LPT, ROWB, NT>(pre[(ph + 1) % PD], &lds[buf ^ 1][0], tid);
-        __syncthreads();
-      }
     }
 }
 
