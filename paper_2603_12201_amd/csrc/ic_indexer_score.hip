@@ -13,8 +13,9 @@
 //
 // Schedule.  A wave's work is a stream of units (32 keys x one token x one head tile): a chain of
 // KS MFMAs into a fresh accumulator, then 16 max/fma pairs on the result.  The chain of unit c + 1
-// is issued one MFMA at a time between the epilogue steps of unit c (a scheduling barrier after each
-// MFMA + its share of the epilogue pins that order), and the stream runs on across key tiles: the
+// is issued one MFMA at a time between the epilogue steps of unit c, one step ahead so that it ends
+// before the epilogue that reads it begins (a scheduling barrier after each MFMA + its share of the
+// epilogue pins that order), and the stream runs on across key tiles: the
 // first chain of the next tile is issued under the last epilogue of this one.  For that the tile
 // hand-over sits in the middle of a tile -- after the wave's last LDS read of the tile the other
 // buffer is refilled, and the barrier that publishes it comes two units later, just before the first
@@ -22,6 +23,8 @@
 // Two workgroups per CU (two waves per SIMD, <= 256 registers each) cover what bubbles remain (LDS
 // read latency at the start of a subtile, the barrier); that caps a wave at 3 tokens (96 q + 48 w
 // registers), which still reuses every B operand read from LDS three times.
+// fp8 halves the MFMA time per unit but not the 32 VALU operations of its epilogue, so that form is
+// bound by VALU issue at about half of the fp8 matrix peak.
 //
 // The kernel writes scores of the query rows in flight into a strip (rows x Lk fp32); it
 // never holds more rows than the caller's workspace allows.  Keys hidden by the causal mask
@@ -130,6 +133,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     constexpr int LPT = (TILE * CPR + NT - 1) / NT;     // 16-byte loads per thread per tile
     static_assert(TILE * CPR % NT == 0, "tile chunks must divide evenly over the threads");
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][TILE * ROWB];
+    __shared__ float lds_ks[2][TILE];                       // fp8: the key scales of the two tiles
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r32 = lane & 31, half = lane >> 5;
@@ -200,6 +204,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
     for (int d = 1; d < PD; ++d)
         if (d < ntiles) tile_gload<RB, LPT, NT>(pre[d], tile_ptr(kc0 + d * TILE), Lk_b - (kc0 + d * TILE), tid);
     tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[0][0], tid);
+    if (FP8 && !STREAM) lds_ks[0][lane] = ksc[min(kc0 + lane, Lk_b - 1)];
     __syncthreads();
 
     // Combine the two half-wave partial sums of a token pair (or of one token with itself) and
@@ -263,6 +268,7 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         constexpr int NCH = 2 * TPW * HT;                   // units (key subtile, token, head tile) per key tile
         constexpr int HALF = TPW * HT;                      // units per key subtile
         constexpr int EPC = 16 / KS;                        // epilogue elements that ride under one MFMA
+        constexpr int LEAD = 1;
 
         // Leading tiles in which all 64 keys are visible to every token of this wave and every token is
         // a real row: nothing needs masking there.  The remaining tiles (the causal diagonal, a ragged
@@ -278,13 +284,17 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         // buffer (last read for tile it - 1, before the previous barrier) takes tile it + 1 and the
         // registers take tile it + 2.  The barrier that publishes the buffer follows later in the tile,
         // before the first read of tile it + 1, so the four waves rarely wait for one another.
+        float pre_s = 1.f;                                  // fp8: a key scale of the tile in flight
+        if (FP8 && ntiles > 1) pre_s = ksc[min(kc0 + TILE + lane, Lk_b - 1)];
         auto stage = [&](int it, int tid_x, auto steady_c) {
             if (decltype(steady_c)::value) {
                 // tile it + 1 follows for certain and tile it + 2, if there is one, has all its 64 rows;
                 // past the end the load repeats tile it + 1 instead of being skipped, which keeps the
                 // steady-state loop body free of branches
                 tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[(it + 1) & 1][0], tid_x);
+                if (FP8) lds_ks[(it + 1) & 1][tid_x & 63] = pre_s;
                 const int kn = kc0 + (it + 2 < ntiles ? it + 2 : it + 1) * TILE;
+                if (FP8) pre_s = ksc[kn + (tid_x & 63)];
                 tile_gload_full<LPT, NT>(pre[0], tile_ptr(kn), tid_x);
             } else {
                 if (it + 1 < ntiles) tile_lstore<RB, LPT, ROWB, NT>(pre[0], &lds[(it + 1) & 1][0], tid_x);
@@ -299,11 +309,18 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         // Unmasked store of two 32-score runs: lanes 0-31 write token ja at keys sa.., lanes 32-63 token
         // jb at keys sb.. (pa / pb: the half-wave partial sums of those two runs).
         float *const srow0 = a.strip + ((int64_t)blockIdx.z * a.Ri + (t_w0 - a.i0)) * a.ld + r32;
-        auto emit_full = [&](float pa, float pb, int ja, int sa, int jb, int sb) {
+        // fp8: the 64 key scales of a tile travel with the tile (register -> lds_ks at the hand-over, every
+        // wave writing the same values) and are read back at the start of the tile; the query scales of a
+        // lane's two possible rows are folded into one value per emit
+        static_assert(TPW <= 4, "two emits per key subtile at most");
+        float ks0 = 1.f, ks1 = 1.f;
+        const float sq_l0 = (half && TPW > 1) ? sqr[1 % TPW] : sqr[0];
+        const float sq_l1 = (half && TPW > 3) ? sqr[3 % TPW] : sqr[2 % TPW];
+        auto emit_full = [&](float pa, float pb, int ja, int suba, int jb, int subb, int kt, float sc) {
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(pa), __float_as_uint(pb), false, false);
             float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-            const int j = half ? jb : ja, s = half ? sb : sa;
-            if (FP8) v *= (half ? sqr[jb] : sqr[ja]) * ksc[s + r32];
+            const int j = half ? jb : ja, s = kt + 32 * (half ? subb : suba);
+            if (FP8) v *= sc;
             srow0[(int64_t)j * a.ld + s] = v;
         };
 
@@ -333,12 +350,24 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
                 const int x = c / HT, ht = c % HT, sub = x / TPW, j = x % TPW;
+                if (FP8 && c == 0) {
+                    ks0 = lds_ks[buf][r32];
+                    ks1 = lds_ks[buf][32 + r32];
+                }
                 if (c + 1 == HALF) load_kb(buf, 1);
                 if (c + 1 == NCH && NEXT) load_kb(buf ^ 1, 0);
                 float s_acc = (ht == 0) ? 0.f : part[j];
+                // MFMA ks + LEAD of the next chain goes out with epilogue step ks: the chain ends LEAD steps
+                // before the epilogue that reads its result begins
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    if (c + 1 < NCH || NEXT) mma_step((c + 1) % NCH, ks);
+                    if (c + 1 < NCH || NEXT) {
+                        if (ks == 0) {
+#pragma unroll
+                            for (int m = 0; m < LEAD; ++m) mma_step((c + 1) % NCH, m);
+                        }
+                        if (ks + LEAD < KS) mma_step((c + 1) % NCH, ks + LEAD);
+                    }
 #pragma unroll
                     for (int i = ks * EPC; i < (ks + 1) * EPC; ++i)
                         s_acc = fmaf(relu(acc[c & 1][i]), wr[j][ht][i], s_acc);
@@ -346,10 +375,11 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
                 }
                 part[j] = s_acc;
                 if (ht == HT - 1) {
-                    if (j & 1) emit_full(part[j - 1], part[j], j - 1, kt + sub * 32, j, kt + sub * 32);
+                    const float sq = (j / 2 == 0) ? sq_l0 : sq_l1;
+                    if (j & 1) emit_full(part[j - 1], part[j], j - 1, sub, j, sub, kt, sq * (sub ? ks1 : ks0));
                     else if (j == TPW - 1) {
                         if (sub == 0) held = part[j];
-                        else emit_full(held, part[j], j, kt, j, kt + 32);
+                        else emit_full(held, part[j], j, 0, j, 1, kt, sq * (half ? ks1 : ks0));
                     }
                 }
                 if (c + 1 == HALF) stage(it, tid_x, next_c);
