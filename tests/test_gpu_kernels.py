@@ -45,6 +45,14 @@ SCORE_CASES = [
     (1, 20, 90, 64, 128, 70, False),     # 64 heads (two head tiles)
     (1, 24, 24, 7, 64, 0, False),        # head count that is not a multiple of anything
     (1, 9, 50, 32, 128, 10, False),      # Lk caps the visible range (q_pos0 + i >= Lk)
+    # long rows: the key loop runs its steady state (unmasked tiles, pipelined across tiles) before
+    # the diagonal; ragged and whole last tiles, every kernel shape
+    (1, 30, 1000, 32, 128, 970, True),
+    (1, 30, 1024, 32, 128, 994, False),
+    (2, 26, 900, 64, 128, 874, True),
+    (1, 30, 777, 32, 64, 747, False),
+    (1, 26, 840, 64, 64, 814, True),
+    (1, 200, 200, 32, 128, 0, False),    # causal square: every wave has a different number of unmasked tiles
 ]
 
 
@@ -65,6 +73,9 @@ FP8_CASES = [
     (2, 30, 200, 32, 170),
     (2, 1, 300, 64, 299),      # decode form
     (1, 40, 40, 20, 0),        # ragged head count
+    (1, 30, 1000, 32, 970),    # long rows: steady-state key loop, ragged last tile
+    (2, 26, 905, 64, 879),
+    (1, 150, 150, 64, 0),
 ]
 
 
