@@ -67,6 +67,32 @@ def test_indexer_scores(ic, oracle, case):
     parity.check_scores(got.cpu().numpy(), want)
 
 
+def _sweep_cases(n, seed):
+    """Seeded random shapes around the tile (64 keys) and block (8 / 12 tokens) boundaries of the score kernel."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        H, d = [(32, 128), (64, 128), (32, 64), (64, 64), (17, 128), (40, 64)][int(rng.integers(0, 6))]
+        B = int(rng.integers(1, 3))
+        Tq = int(rng.integers(1, 60))
+        extra = int(rng.choice([0, 1, 63, 64, 65, 127, 128, 200, 513, 1000]))
+        Lk = Tq + extra
+        p0 = int(rng.choice([Lk - Tq, max(0, Lk - Tq - 7), Lk]))     # aligned to the end, short of it, past it
+        out.append((B, Tq, Lk, H, d, p0, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("case", _sweep_cases(24, 20260312))
+def test_indexer_scores_shape_sweep(ic, oracle, case):
+    B, Tq, Lk, H, d, p0, signed = case
+    say("scores sweep B=%d Tq=%d Lk=%d H=%d d=%d q_pos0=%d signed=%s" % case)
+    q, k, w = _mk_indexer(900 + Tq + Lk, B, Tq, Lk, H, d, signed)
+    got = ic.debug_indexer_scores(q.cuda(), k.cuda(), w.cuda(), p0, 0, Tq)
+    torch.cuda.synchronize()
+    want = oracle.indexer_scores(synth.bits(q), synth.bits(k), synth.bits(w), p0)
+    parity.check_scores(got.cpu().numpy(), want)
+
+
 FP8_CASES = [
     # B, Tq, Lk, H, q_pos0
     (1, 70, 70, 64, 0),        # configs[4] head count: two head tiles
