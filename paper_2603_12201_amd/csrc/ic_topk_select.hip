@@ -8,7 +8,9 @@
 //   pass 1   12-bit digit (sign, exponent, 3 mantissa bits) over the whole row, fused with the
 //            single read of the row from HBM; rows of up to `cache_elems` keys stay in LDS
 //   pass 2,3 12 + 8 bits; only entries that match the prefix found so far touch the histogram,
-//            so these are read-mostly sweeps over the cached row
+//            so these are read-mostly sweeps over the cached row.  The sweeps stop as soon as the
+//            boundary bin holds exactly the entries still needed (with distinct scores: after
+//            pass 2), because then every entry with key >= prefix is selected
 //   emit     a thread owns 4 consecutive positions in every sweep.  When every entry equal to the
 //            k-th key is selected (the usual case: known from the last histogram) "selected" is
 //            the single test key >= tau: per-thread counts of two sweeps packed in one word, one
@@ -56,7 +58,7 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t x)
 }
 
 // Workgroup-wide descending scan over `nbins` counters: finds the digit d with
-// count(bins > d) < need <= count(bins >= d) and writes {d, need - count(bins > d)} to bc.
+// count(bins > d) < need <= count(bins >= d) and writes {d, need - count(bins > d), count(bin d)} to bc.
 // Every thread owns BPT consecutive bins, highest bins first.  A bin is the sum of R adjacent
 // counters (R > 1: the histogram was spread over R copies against same-address collisions).
 template <int NT, int BPT, int R = 1>
@@ -103,6 +105,7 @@ __device__ __forceinline__ void find_digit(const uint32_t *cnt, uint32_t need, u
             if (run < need && need <= run + c[j]) {
                 bc[0] = (uint32_t)(top - j);
                 bc[1] = need - run;
+                bc[2] = c[j];
             }
             run += c[j];
         }
@@ -194,11 +197,16 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     find_digit<NT, kBins1 / NT>(hist1, (uint32_t)a.k_sel, wsum, bc, tid, lane, wave);
     uint32_t prefix = bc[0] << 20, prefix_mask = 0xFFF00000u;
     uint32_t need = bc[1];
+    // Once the boundary bin holds exactly as many entries as are still needed, all of them are
+    // selected and the remaining digits do not matter: "selected" is key >= prefix (rest zero).
+    // With distinct scores that happens after the second digit, which saves the third sweep.
+    bool all_sel = bc[2] == need;              // workgroup-uniform
+    uint32_t total_eq = bc[2];
     __syncthreads();
 
     // ---- passes 2 and 3: bits [19:8] and [7:0] of the entries that match the prefix so far ----
 #pragma unroll 1
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = 0; pass < 2 && !all_sel; ++pass) {
         const int shift = pass == 0 ? 8 : 0;
         const uint32_t dmask = pass == 0 ? 4095u : 255u;
         for (int e = tid; e < kBins1; e += NT) hist1[e] = 0;
@@ -215,10 +223,14 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
         prefix |= bc[0] << shift;
         prefix_mask |= dmask << shift;
         need = bc[1];
+        total_eq = bc[2];
+        all_sel = total_eq == need;
         __syncthreads();
     }
-    const uint32_t tau = prefix;               // key of the k-th largest score
-    const uint32_t need_eq = need;             // how many entries equal to tau are selected
+    // tau: key of the k-th largest score, or (all_sel) a lower bound of it that no unselected entry
+    // reaches.  need_eq: how many of the total_eq entries equal to tau are selected.
+    const uint32_t tau = prefix;
+    const uint32_t need_eq = need;
 
     // ---- ordered emit, common case: the row is cached, has at most kFastChunks sweeps, and every
     // entry equal to tau is selected (the k-th score is unique, or all of its ties fit).  Then
@@ -227,9 +239,8 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     // pair, one scan over the (chunk, wave) cells, two barriers in all. ----
     constexpr int kFastChunks = 8;
     const int nchunks = (nv + 4 * NT - 1) / (4 * NT);
-    const uint32_t total_eq = hist1[tau & 255u];       // the last histogram is still in place
-    if (cached && nchunks <= kFastChunks && total_eq == need_eq) {
-        uint32_t *cellsum = hist1 + 256;               // [kFastChunks / 2][NW]  (beyond the 256 live bins)
+    if (cached && nchunks <= kFastChunks && all_sel) {
+        uint32_t *cellsum = hist1;                     // [kFastChunks / 2][NW]  (the histogram is dead: its barrier is behind us)
         uint32_t *cellbase = cellsum + kFastChunks / 2 * NW;   // [kFastChunks * NW]
         uint32_t cw[kFastChunks / 2], inc[kFastChunks / 2];
 #pragma unroll
@@ -247,7 +258,7 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
             cw[j] = n2[0] | (n2[1] << 16);
             inc[j] = wave_incl_scan(cw[j]);
         }
-        if (lane == 63) {                              // (the cells lie beyond the 256 bins still being read)
+        if (lane == 63) {
 #pragma unroll
             for (int j = 0; j < kFastChunks / 2; ++j) cellsum[j * NW + wave] = inc[j];
         }
@@ -298,8 +309,8 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (p + e < nv) {
-                gm |= (k4[e] > tau ? 1u : 0u) << e;
-                em |= (k4[e] == tau ? 1u : 0u) << e;
+                gm |= ((all_sel ? k4[e] >= tau : k4[e] > tau) ? 1u : 0u) << e;
+                em |= ((!all_sel && k4[e] == tau) ? 1u : 0u) << e;
             }
         }
         const uint32_t mine = ((uint32_t)__popc(em) << 16) | (uint32_t)__popc(gm);
@@ -416,6 +427,7 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
 
     // ---- three digit passes: 12 + 12 + 8 bits, most significant first ----
     uint32_t prefix, prefix_mask, need;
+    bool all_sel;                              // workgroup-uniform
     {
         for (int e = tid; e < kBins1 * kSpread / 4; e += NT) ((u32x4 *)hist)[e] = u32x4{0u, 0u, 0u, 0u};
         __syncthreads();
@@ -429,10 +441,12 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
         prefix = bc[0] << 20;
         prefix_mask = 4095u << 20;
         need = bc[1];
+        all_sel = bc[2] == need;
         __syncthreads();
     }
+    // (as in select_kernel: the sweeps stop once every entry left in the boundary bin is selected)
 #pragma unroll 1
-    for (int pass = 1; pass < 3; ++pass) {
+    for (int pass = 1; pass < 3 && !all_sel; ++pass) {
         const int shift = pass == 1 ? 8 : 0;
         const uint32_t dmask = pass == 2 ? 255u : 4095u;
         for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
@@ -447,9 +461,10 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
         prefix |= bc[0] << shift;
         prefix_mask |= dmask << shift;
         need = bc[1];
+        all_sel = bc[2] == need;
         __syncthreads();
     }
-    const uint32_t tau = prefix;               // key of the k-th largest score
+    const uint32_t tau = prefix;               // key of the k-th largest score (all_sel: a lower bound no unselected entry reaches)
     const uint32_t need_eq = need;             // how many entries equal to tau are selected
 
     int tid_e = tid;
@@ -460,8 +475,7 @@ __global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
     // slot of an entry is the number of selected entries ahead of it in position order, i.e.
     // (chunk, wave, lane, element).  One packed wave scan per chunk pair, one scan over the 256
     // (chunk, wave) cells, two barriers in all. ----
-    const uint32_t total_eq = hist[tau & 255u];        // the last histogram is still in place
-    if (total_eq == need_eq) {
+    if (all_sel) {
         uint32_t cw[NCH / 2], inc[NCH / 2];
 #pragma unroll
         for (int j = 0; j < NCH / 2; ++j) {

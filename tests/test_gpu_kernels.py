@@ -240,6 +240,27 @@ def test_topk_ties_cut_at_the_boundary_on_long_rows(ic, oracle, Lk):
         assert want.size == ks and np.array_equal(idx[0, i], want)
 
 
+@pytest.mark.parametrize("Lk", [3000, 9000, 40000, 70000])
+def test_topk_boundary_bin_fully_selected(ic, oracle, Lk):
+    # exactly k winners, all inside one bin of the first radix digit ([64, 72): sixteen bf16 values),
+    # everything else far below: the digit sweeps may stop after the first one, and "selected" becomes
+    # key >= the bin's lower edge, in every select variant (by row length)
+    say("topk winners fill the boundary bin, Lk=%d" % Lk)
+    B, Tq, H, d, ks = 1, 3, 1, 64, 256
+    g = torch.Generator().manual_seed(Lk + 1)
+    p0 = Lk - Tq
+    vals = torch.randint(0, 32, (Lk,), generator=g).float() / 4.0            # losers: [0, 8)
+    win = torch.randperm(p0, generator=g)[:ks]                                # winners visible to every row
+    vals[win] = 64.0 + torch.randint(0, 16, (ks,), generator=g).float() / 2.0
+    q = torch.zeros((B, Tq, H, d)); q[..., 3] = 1.0
+    k = torch.zeros((B, Lk, d)); k[0, :, 3] = vals
+    w = torch.ones((B, Tq, H))
+    idx = ic.indexer_topk(q.bfloat16().cuda(), k.bfloat16().cuda(), w.cuda(), ks, p0).cpu().numpy()
+    want = np.sort(win.numpy())
+    for i in range(Tq):
+        assert np.array_equal(idx[0, i], want)
+
+
 def test_topk_monotone_scores(ic, oracle):
     # one head, one-hot q, keys increasing along that coordinate: scores increase with position,
     # so the last k visible positions win (the adversarial order for a streaming filter)
