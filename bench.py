@@ -21,8 +21,8 @@ sys.path.insert(0, ROOT)
 
 # HBM bytes per launch of the kernels at the configs[3] per-layer shape, from rocprofv3 FETCH_SIZE +
 # WRITE_SIZE scaled by a plain-copy reference (profiles/attn_score_select_prefill32k_hbm_traffic.txt).
-MEASURED_TRAFFIC_BYTES = {"sparse_attn": 18.99e9 + 1.07e9, "indexer_score": 0.426e9 + 0.537e9,
-                          "topk_select": 0.672e9 + 0.067e9}
+MEASURED_TRAFFIC_BYTES = {"sparse_attn": 18.88e9 + 1.07e9, "indexer_score": 0.452e9 + 0.566e9,
+                          "topk_select": 0.672e9 + 0.068e9}
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 KERNELS = ["indexer_score", "topk_select", "sparse_attn", "attn_merge"]
