@@ -280,12 +280,12 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
             n_int = (int)(n < 0 ? 0 : (n > ntiles ? ntiles : n));
         }
 
+        float pre_s = 1.f;                                  // fp8: a key scale of the tile in flight
+        if (FP8 && ntiles > 1) pre_s = ksc[min(kc0 + TILE + lane, Lk_b - 1)];
         // Hand-over of a tile: once every LDS read of tile `it` has been issued by this wave, the other
         // buffer (last read for tile it - 1, before the previous barrier) takes tile it + 1 and the
         // registers take tile it + 2.  The barrier that publishes the buffer follows later in the tile,
         // before the first read of tile it + 1, so the four waves rarely wait for one another.
-        float pre_s = 1.f;                                  // fp8: a key scale of the tile in flight
-        if (FP8 && ntiles > 1) pre_s = ksc[min(kc0 + TILE + lane, Lk_b - 1)];
         auto stage = [&](int it, int tid_x, auto steady_c) {
             if (decltype(steady_c)::value) {
                 // tile it + 1 follows for certain and tile it + 2, if there is one, has all its 64 rows;
@@ -306,16 +306,18 @@ __global__ __launch_bounds__(64 * NW, MINB) void score_kernel(ScoreArgs a)
         };
         if (ntiles > 1) tile_gload<RB, LPT, NT>(pre[0], tile_ptr(kc0 + TILE), Lk_b - (kc0 + TILE), tid);
 
-        // Unmasked store of two 32-score runs: lanes 0-31 write token ja at keys sa.., lanes 32-63 token
-        // jb at keys sb.. (pa / pb: the half-wave partial sums of those two runs).
-        float *const srow0 = a.strip + ((int64_t)blockIdx.z * a.Ri + (t_w0 - a.i0)) * a.ld + r32;
         // fp8: the 64 key scales of a tile travel with the tile (register -> lds_ks at the hand-over, every
-        // wave writing the same values) and are read back at the start of the tile; the query scales of a
-        // lane's two possible rows are folded into one value per emit
+        // wave writing the same values) and are read back at the start of the tile (ks0 / ks1: the lane's
+        // key in either subtile); the query scales of a lane's two possible rows are folded into one
+        // value per emit (sq_l0: tokens 0 / 1, sq_l1: tokens 2 / 3)
         static_assert(TPW <= 4, "two emits per key subtile at most");
         float ks0 = 1.f, ks1 = 1.f;
         const float sq_l0 = (half && TPW > 1) ? sqr[1 % TPW] : sqr[0];
         const float sq_l1 = (half && TPW > 3) ? sqr[3 % TPW] : sqr[2 % TPW];
+        // Unmasked store of two 32-score runs of tile kt: lanes 0-31 write token ja at the keys of subtile
+        // suba, lanes 32-63 token jb at those of subtile subb (pa / pb: the half-wave partial sums of the
+        // two runs; sc: the lane's fp8 scale product).
+        float *const srow0 = a.strip + ((int64_t)blockIdx.z * a.Ri + (t_w0 - a.i0)) * a.ld + r32;
         auto emit_full = [&](float pa, float pb, int ja, int suba, int jb, int subb, int kt, float sc) {
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(pa), __float_as_uint(pb), false, false);
             float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
