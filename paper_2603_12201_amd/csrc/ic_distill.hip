@@ -5,9 +5,10 @@
 //   attn_probs_kernel   p_bar_t(s) = 1/H sum_h softmax_s(sm_scale Q[t,h] . K[s]) over the selected
 //                       rows: the layer's attention distribution aggregated over its heads, the
 //                       indexer's training target (Sec. 2.1).  S^T = K Q^T on
-//                       v_mfma_f32_16x16x32_bf16 with Q in registers; the per-head normalisers are
-//                       the log-sum-exps the attention kernel already produced; the head sum is a
-//                       16-lane row reduction.
+//                       v_mfma_f32_16x16x32_bf16 with Q in registers and the gathered rows turned
+//                       into the A-operand layout through a per-wave LDS tile; the per-head
+//                       normalisers are the log-sum-exps the attention kernel already produced;
+//                       the head sum is a 16-lane row reduction.
 //   distill_row_kernel  per query: q = Softmax(I) over the selected scores (in the log domain),
 //                       sum_j 1/(m+1) KL(p_j || q), KL(p_bar || q), and q * |p_bar| - p_bar, the
 //                       gradient with respect to the indexer's logits that both losses share.
@@ -18,19 +19,44 @@ namespace ic {
 
 namespace {
 
-constexpr int kProbTile = 64;
+constexpr int kProbRows = 16;                 // selected rows per wave and step
 
-template <int D_QK>
-__global__ __launch_bounds__(256) void attn_probs_kernel(ProbsArgs a)
+// XOR swizzle of the 16-byte slot inside a 128-byte window of an LDS row (rows are unpadded, so
+// without it the 16 rows of an A-operand read would start in the same bank)
+__device__ __forceinline__ int slot_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+// Validity of a wave's 16 rows from the two ballots over the gather lanes (lane 8r' + piece holds
+// row r' of the first / second eight rows): bit r of the result is row r.
+__device__ __forceinline__ unsigned rows_mask(unsigned long long ba, unsigned long long bb)
 {
-    constexpr int KS = D_QK / 32;
+    const unsigned long long ones = 0x0101010101010101ull, pack = 0x0102040810204080ull;
+    const unsigned lo = (unsigned)(((ba & ones) * pack) >> 56);
+    const unsigned hi = (unsigned)(((bb & ones) * pack) >> 56);
+    return lo | (hi << 8);
+}
+
+// One workgroup per query, every wave on its own: wave w takes the selected rows 16 w .. 16 w + 15,
+// then 64 further on.  Eight lanes fetch one 128-byte line of a row (the gather shape the memory
+// system serves fastest); the 16 rows turn into the A-operand layout (lane = row, 8 features) through
+// the wave's private 16-row LDS tile: LDS executes a wave's accesses in order, so the stores of the
+// next rows simply follow the reads of the current ones and the workgroup never meets at a barrier.
+// The next 16 rows are in flight while the current ones are multiplied.
+template <int D_QK>
+__global__ __launch_bounds__(256, 2) void attn_probs_kernel(ProbsArgs a)
+{
+    constexpr int KS = D_QK / 32;             // contraction steps = 16-byte chunks per gather lane
+    constexpr int ROWB = D_QK * 2;            // bytes per LDS row
+    static_assert(ROWB % 128 == 0 && KS % 2 == 0, "a row is a whole number of 128-byte windows");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [4 waves][16 rows][ROWB]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
+    const int gr = lane >> 3, gp = lane & 7;  // gather role: row (and row + 8), 16-byte piece of the window
     const int64_t qrow = blockIdx.x;
     const int b = (int)(qrow / a.Tq);
     const int32_t *idx_row = a.idx + qrow * a.k_sel;
     const unsigned short *kv_seq = (const unsigned short *)a.KV + (int64_t)b * a.Lk * a.row_elems;
     float *out = a.probs + qrow * a.k_sel;
+    unsigned char *tb = smem + wave * kProbRows * ROWB;
 
     // Q as the B operand (head 16 hb + l16, features 8 g + 32 ks ..), and the heads' log-sum-exps
     bf16x8 qreg[2][KS];
@@ -51,23 +77,58 @@ __global__ __launch_bounds__(256) void attn_probs_kernel(ProbsArgs a)
     }
     const float inv_h = 1.f / (float)a.H_q;
 
-    const int ntiles = (a.k_sel + kProbTile - 1) / kProbTile;
-#pragma unroll 1
-    for (int it = 0; it < ntiles; ++it) {
-        // the wave's 16 slots; lane (l16, g) feeds row l16 of the A operand
-        const int slot = it * kProbTile + 16 * wave + l16;
-        int32_t v = slot < a.k_sel ? idx_row[slot] : -1;
-        const bool valid = v >= 0 && v < a.Lk;
-        const unsigned rows_ok = (unsigned)(__ballot(valid) & 0xFFFFull);     // bit r: row r of the wave
-        const unsigned short *kp = kv_seq + (int64_t)(valid ? v : 0) * a.row_elems + 8 * g;
-        bf16x8 ka[KS];
+    // LDS offsets of the lane in its two roles
+    const int st_off = gr * ROWB + ((gp ^ slot_swz(gr)) << 4);            // + 8 rows for odd chunks
+    const int ka_row = l16 * ROWB;
+    const int ka_e = ka_row + ((g ^ slot_swz(l16)) << 4);                 // even contraction steps
+    const int ka_o = ka_row + (((4 + g) ^ slot_swz(l16)) << 4);           // odd ones
+
+    struct Ids { int32_t lo, hi; };           // validated ids of rows gr and gr + 8 of a group, -1: empty slot
+    auto fetch_ids = [&](int grp) -> Ids {
+        const int s_lo = kProbRows * grp + gr, s_hi = s_lo + 8;
+        const int32_t v_lo = idx_row[min(s_lo, a.k_sel - 1)], v_hi = idx_row[min(s_hi, a.k_sel - 1)];
+        Ids r;
+        r.lo = ((int)(s_lo < a.k_sel) & (int)(v_lo >= 0) & (int)(v_lo < a.Lk)) ? v_lo : -1;
+        r.hi = ((int)(s_hi < a.k_sel) & (int)(v_hi >= 0) & (int)(v_hi < a.Lk)) ? v_hi : -1;
+        return r;
+    };
+    // loads are unconditional (an empty slot reads row 0 and is masked later): the wait counters stay positional
+    u32x4 cur[KS];
+    auto gather = [&](const Ids &d) {
+        const unsigned short *pl = kv_seq + (int64_t)(d.lo < 0 ? 0 : d.lo) * a.row_elems + 8 * gp;
+        const unsigned short *ph = kv_seq + (int64_t)(d.hi < 0 ? 0 : d.hi) * a.row_elems + 8 * gp;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) ka[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kp + 32 * ks));
-        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        for (int ks = 0; ks < KS; ++ks) cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
+    };
+
+    const int ngroups = (a.k_sel + kProbRows - 1) / kProbRows;
+    Ids d_cur = fetch_ids(wave), d_nxt = fetch_ids(wave + 4);
+    gather(d_cur);
+#pragma unroll 1
+    for (int grp = wave; grp < ngroups; grp += 4) {                       // wave-uniform
+        const unsigned rows_ok = rows_mask(__ballot(d_cur.lo >= 0), __ballot(d_cur.hi >= 0));
+        const Ids d_n2 = fetch_ids(grp + 8);
+        // the rows of this group go to the tile, their registers take the next group
+        {
+            const unsigned short *pl = kv_seq + (int64_t)(d_nxt.lo < 0 ? 0 : d_nxt.lo) * a.row_elems + 8 * gp;
+            const unsigned short *ph = kv_seq + (int64_t)(d_nxt.hi < 0 ? 0 : d_nxt.hi) * a.row_elems + 8 * gp;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                *(u32x4 *)(tb + st_off + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
+                cur[ks] = *(const u32x4 *)(((ks & 1) ? ph : pl) + 64 * (ks >> 1));
+            }
+        }
+        // S^T for 16 rows x 32 heads: two accumulation chains per head block
+        f32x4 s4[2][2];
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int par = 0; par < 2; ++par) s4[hb][par] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[0][ks], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qreg[1][ks], acc[1], 0, 0, 0);
+            const bf16x8 ka = *(const bf16x8 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1));
+            s4[0][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[0][ks], s4[0][ks & 1], 0, 0, 0);
+            s4[1][ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qreg[1][ks], s4[1][ks & 1], 0, 0, 0);
         }
         // lane (head l16, g) holds rows 4 g + i: probabilities of its two heads, summed over the heads
         float ps[4];
@@ -77,16 +138,19 @@ __global__ __launch_bounds__(256) void attn_probs_kernel(ProbsArgs a)
             float p = 0.f;
 #pragma unroll
             for (int hb = 0; hb < 2; ++hb)
-                if (ok && head_ok[hb]) p += __builtin_amdgcn_exp2f(acc[hb][i] * a.scale_log2e - lse2[hb]);
+                if (ok && head_ok[hb])
+                    p += __builtin_amdgcn_exp2f((s4[hb][0][i] + s4[hb][1][i]) * a.scale_log2e - lse2[hb]);
             ps[i] = row16_sum(p);                         // lane l16 == 15: the sum over the 16 head lanes
         }
         if (l16 == 15) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int s = it * kProbTile + 16 * wave + 4 * g + i;
+                const int s = kProbRows * grp + 4 * g + i;
                 if (s < a.k_sel) out[s] = ps[i] * inv_h;
             }
         }
+        d_cur = d_nxt;
+        d_nxt = d_n2;
     }
 }
 
@@ -197,12 +261,17 @@ hipError_t launch_attn_probs(const ProbsArgs &a, int d_qk, hipStream_t st)
 {
     const int64_t nq = (int64_t)a.B * a.Tq;
     if (nq <= 0) return hipSuccess;
-    if (d_qk == 576)
-        hipLaunchKernelGGL(attn_probs_kernel<576>, dim3((unsigned)nq), dim3(256), 0, st, a);
-    else if (d_qk == 64)
-        hipLaunchKernelGGL(attn_probs_kernel<64>, dim3((unsigned)nq), dim3(256), 0, st, a);
-    else
+    if (d_qk == 576) {
+        constexpr int lds = 4 * kProbRows * 576 * 2;      // above the default limit of dynamic LDS: opt in once
+        static hipError_t attr = hipFuncSetAttribute((const void *)attn_probs_kernel<576>,
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(attn_probs_kernel<576>, dim3((unsigned)nq), dim3(256), lds, st, a);
+    } else if (d_qk == 64) {
+        hipLaunchKernelGGL(attn_probs_kernel<64>, dim3((unsigned)nq), dim3(256), 4 * kProbRows * 64 * 2, st, a);
+    } else {
         return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
