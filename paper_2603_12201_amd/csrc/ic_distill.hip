@@ -9,7 +9,8 @@
 //                       into the A-operand layout through a per-wave LDS tile; the per-head
 //                       normalisers are the log-sum-exps the attention kernel already produced;
 //                       the head sum is a 16-lane row reduction.
-//   distill_row_kernel  per query: q = Softmax(I) over the selected scores (in the log domain),
+//   distill_row_kernel  (and its register-resident form for k <= 2048, which reads every input once)
+//                       per query: q = Softmax(I) over the selected scores (in the log domain),
 //                       sum_j 1/(m+1) KL(p_j || q), KL(p_bar || q), and q * |p_bar| - p_bar, the
 //                       gradient with respect to the indexer's logits that both losses share.
 //   distill_sum_kernel  fixed-order sum of the per-row values (one workgroup: deterministic).
@@ -154,29 +155,26 @@ __global__ __launch_bounds__(256, 2) void attn_probs_kernel(ProbsArgs a)
     }
 }
 
-// block-wide sum of doubles through LDS (256 threads)
+// Block-wide reductions (256 threads): a butterfly inside each wave, then the four wave results
+// through LDS.  The sum runs in a fixed order, so a row's value does not depend on timing.
 __device__ __forceinline__ double block_sum(double x, double *red, int tid)
 {
-    red[tid] = x;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+    if ((tid & 63) == 0) red[tid >> 6] = x;
     __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if (tid < off) red[tid] += red[tid + off];
-        __syncthreads();
-    }
-    const double r = red[0];
+    const double r = (red[0] + red[1]) + (red[2] + red[3]);
     __syncthreads();
     return r;
 }
 
 __device__ __forceinline__ float block_max(float x, float *red, int tid)
 {
-    red[tid] = x;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+    if ((tid & 63) == 0) red[tid >> 6] = x;
     __syncthreads();
-    for (int off = 128; off > 0; off >>= 1) {
-        if (tid < off) red[tid] = fmaxf(red[tid], red[tid + off]);
-        __syncthreads();
-    }
-    const float r = red[0];
+    const float r = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     __syncthreads();
     return r;
 }
@@ -237,6 +235,80 @@ __global__ __launch_bounds__(256) void distill_row_kernel(DistillArgs a)
     }
 }
 
+// The same per-row values for rows of up to 256 * EPT selected positions, every input read exactly
+// once: the thread keeps its EPT logits (as log q) and the running sum of the targets in registers;
+// the targets are visited one after the other, each adding its own term of Eq. 1.
+template <int EPT>
+__global__ __launch_bounds__(256) void distill_row_reg_kernel(DistillArgs a)
+{
+    __shared__ double redd[4];
+    __shared__ float redf[4];
+    const int tid = threadIdx.x;
+    const int64_t row = blockIdx.x;
+    const float *sc = a.scores + row * a.k_sel;
+    const float w = 1.f / (float)a.n_targets;
+
+    float lq[EPT];                             // logits, then log q
+    bool fin[EPT];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        const int s = tid + 256 * e;
+        lq[e] = s < a.k_sel ? sc[s] : -INFINITY;
+        fin[e] = lq[e] > -INFINITY && lq[e] < INFINITY;
+        if (fin[e]) mx = fmaxf(mx, lq[e]);
+    }
+    mx = block_max(mx, redf, tid);
+    double z = 0.0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+        if (fin[e]) z += (double)expf(lq[e] - mx);
+    z = block_sum(z, redd, tid);
+    const float log_z = z > 0.0 ? (float)log(z) : 0.f;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) lq[e] = fin[e] ? (lq[e] - mx) - log_z : -INFINITY;
+
+    float pb[EPT];
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) pb[e] = 0.f;
+    double multi = 0.0;
+    for (int j = 0; j < a.n_targets; ++j) {
+        const float *pj = a.probs[j] + row * a.k_sel;
+        float p[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int s = tid + 256 * e;
+            p[e] = s < a.k_sel ? pj[s] : 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            pb[e] += p[e];
+            if (p[e] > 0.f) multi += (double)(w * p[e] * (logf(p[e]) - lq[e]));
+        }
+    }
+    double avg = 0.0, mass = 0.0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+        mass += (double)(pb[e] * w);           // 1 for a row with selected entries, 0 for an empty one
+        pb[e] *= w;
+        if (pb[e] > 0.f) avg += (double)(pb[e] * (logf(pb[e]) - lq[e]));
+    }
+    mass = block_sum(mass, redd, tid);
+    if (a.grad) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const int s = tid + 256 * e;
+            if (s < a.k_sel) a.grad[row * a.k_sel + s] = (fin[e] ? expf(lq[e]) : 0.f) * (float)mass - pb[e];
+        }
+    }
+    multi = block_sum(multi, redd, tid);
+    avg = block_sum(avg, redd, tid);
+    if (tid == 0) {
+        a.row_multi[row] = multi;
+        a.row_avg[row] = avg;
+    }
+}
+
 __global__ __launch_bounds__(256) void distill_sum_kernel(const double *row_multi, const double *row_avg, int64_t n,
                                                           double *loss_multi, double *loss_avg)
 {
@@ -277,7 +349,12 @@ hipError_t launch_attn_probs(const ProbsArgs &a, int d_qk, hipStream_t st)
 
 hipError_t launch_distill(const DistillArgs &a, int64_t nq, double *loss_multi, double *loss_avg, hipStream_t st)
 {
-    if (nq > 0) hipLaunchKernelGGL(distill_row_kernel, dim3((unsigned)nq), dim3(256), 0, st, a);
+    if (nq > 0) {
+        if (a.k_sel <= 256 * 8)
+            hipLaunchKernelGGL(distill_row_reg_kernel<8>, dim3((unsigned)nq), dim3(256), 0, st, a);
+        else
+            hipLaunchKernelGGL(distill_row_kernel, dim3((unsigned)nq), dim3(256), 0, st, a);
+    }
     hipLaunchKernelGGL(distill_sum_kernel, dim3(1), dim3(256), 0, st, (const double *)a.row_multi, (const double *)a.row_avg, nq,
                        loss_multi, loss_avg);
     return hipGetLastError();

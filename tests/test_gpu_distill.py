@@ -109,3 +109,31 @@ def test_distill_loss_and_proposition_1(ic, oracle):
     # one served layer: Eq. 1 = Eq. 2 = the single-layer DSA loss
     l1, a1 = ic.distill_loss(probs[:1], sel)
     assert float(l1) == pytest.approx(float(a1), rel=1e-6) and float(l1) == pytest.approx(oracle.kl_rows(ps[0], q).sum(), rel=1e-2)
+
+
+@pytest.mark.parametrize("k_sel", [700, 2048, 3000])
+def test_distill_loss_row_lengths(ic, oracle, k_sel):
+    """ic_distill_loss on given distributions: the register-resident row kernel (k <= 2048, ragged and
+    full) and the re-reading one (longer rows), with empty slots and one empty row."""
+    say("distillation loss on synthetic distributions, k=%d" % k_sel)
+    nq, m1 = 37, 3
+    rng = np.random.default_rng(k_sel)
+    logits = rng.normal(size=(1, nq, k_sel)).astype(np.float32) * 2.0
+    empty = rng.random((1, nq, k_sel)) < 0.1
+    empty[0, 5] = True                                       # a row with nothing selected
+    logits[empty] = -np.inf
+    ps = []
+    for j in range(m1):
+        e = rng.random((1, nq, k_sel)) ** 4
+        e[empty] = 0.0
+        s = e.sum(-1, keepdims=True)
+        ps.append(np.where(s > 0, e / np.where(s > 0, s, 1.0), 0.0).astype(np.float32))
+    lm, la, grad = ic.distill_loss([torch.from_numpy(p).cuda() for p in ps], torch.from_numpy(logits).cuda(), want_grad=True)
+    torch.cuda.synchronize()
+    q = oracle.indexer_distribution(logits.astype(np.float64))
+    p64 = [p.astype(np.float64) for p in ps]
+    want_m, want_a = oracle.distill_loss_multi(p64, q), oracle.distill_loss_avg(p64, q)
+    assert float(lm) == pytest.approx(want_m, rel=1e-5) and float(la) == pytest.approx(want_a, rel=1e-5)
+    g = grad.cpu().numpy()
+    assert np.abs(g - oracle.distill_grad_logits(p64, q)).max() <= 1e-5
+    assert np.all(g[0, 5] == 0)
