@@ -339,3 +339,14 @@ def test_distill_argument_errors_need_no_gpu(ic):
     assert L.ic_distill_loss(ptrs, 2, one, 1000, 64, one, one, None, one, 64, None) == S.ERR_WORKSPACE
     bad = (C.c_void_p * 2)(4096, None)
     assert L.ic_distill_loss(bad, 2, one, 1000, 64, one, one, None, one, ws, None) == S.ERR_NULL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build is for one GPU: the bench says so and exits instead of pretending to scale."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
