@@ -42,6 +42,7 @@ PROB_CASES = [
     (2, 9, 200, 20, 576, 640, 100, 150, True),       # ragged heads, padded rows, ragged last tile, holes
     (1, 50, 50, 4, 64, 128, 16, 0, False),           # tiny-config shape, short causal rows
     (1, 6, 500, 32, 576, 576, 300, 494, True),
+    (1, 4, 5000, 32, 576, 576, 2048, 4996, True),   # the workload's k: 32 steps per wave
 ]
 
 
