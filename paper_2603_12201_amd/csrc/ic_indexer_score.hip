@@ -494,7 +494,7 @@ hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipSt
     // several times; the streaming variant wants exactly one resident round (3 per CU).
     const int64_t want_wgs = few_rows ? 768 : 2048;
     int64_t kc = (max_vis * a.n_qblocks * Bc / want_wgs + 63) / 64 * 64;
-    kc = kc < 512 ? 512 : (kc > 4096 ? 4096 : kc);
+    kc = kc < 512 ? 512 : (kc > 8192 ? 8192 : kc);
     a.KC = (int)kc;
     const bool fp8 = dtype == IC_FP8_E4M3;
     if (!fp8) {
