@@ -447,9 +447,12 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
                 qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
             }
     };
-    // Chained form: Q of the next query goes straight into the accumulation registers while the
-    // outputs of the current one are stored.  The compiler does not count these loads, which only
-    // makes its own waits conservative; settle_q waits for them and ties every later use to that wait.
+    // Chained form: Q of the next query is loaded while the outputs of the current one are stored.  Its
+    // only use is pinned to the accumulation registers (settle_q), so the loads target those registers
+    // directly and take no vector registers; they are issued before the epilogue and waited for in
+    // settle_q.  (With fewer than 32 heads the loads sit under a lane mask; there they are inline loads
+    // the compiler does not count, which only makes its own waits conservative, and settle_q's explicit
+    // wait ties every later use to them.)
     // Only wave 0 loads (each load touches 16 rows of Q, so four waves loading the same 36 KB keep the
     // CU's one address unit busy for 2.8 us); it then hands Q to the other waves through the tile
     // buffer that is free between two queries, in the very lane order the operand has.
@@ -467,9 +470,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     const unsigned short *src = q0 + (16 * hb + hd) * D_QK + 32 * ks;
-                    u32x4 raw;
-                    asm volatile("global_load_dwordx4 %0, %1, off" : "=a"(raw) : "v"(src));
-                    qreg[hb][ks] = __builtin_bit_cast(bf16x8, raw);
+                    qreg[hb][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)src);
                 }
         } else {
 #pragma unroll
