@@ -50,16 +50,16 @@ struct ProfScope {
         if (g_prof_recs.size() >= kProfPool) return;
         if (hipEventCreate(&e0) != hipSuccess) return;
         if (hipEventCreate(&e1) != hipSuccess) {
-            hipEventDestroy(e0);
+            (void)hipEventDestroy(e0);
             return;
         }
         live = true;
-        hipEventRecord(e0, st);
+        (void)hipEventRecord(e0, st);
     }
     ~ProfScope()
     {
         if (!live) return;
-        hipEventRecord(e1, st);
+        (void)hipEventRecord(e1, st);
         std::lock_guard<std::mutex> lk(g_prof_mu);
         g_prof_recs.push_back(ProfRec{e0, e1, which});
     }
@@ -337,6 +337,7 @@ static ic_status check_stack(const ic_layer *layers, int32_t n, const uint8_t *f
     if (full_mask) {
         if (!full_mask[0]) return fail(IC_ERR_PATTERN, "the first layer must be Full: there are no indices to reuse yet");
     }
+    int32_t idx_lk = 0;                        // key range the cached indices were drawn from (the last Full layer's)
     for (int l = 0; l < n; ++l) {
         const ic_layer *L = &layers[l];
         const bool full = !full_mask || full_mask[l];
@@ -349,6 +350,12 @@ static ic_status check_stack(const ic_layer *layers, int32_t n, const uint8_t *f
             if (!L->q || !L->k || !L->w) return fail(IC_ERR_NULL, "Full layer %d: q, k and w must not be NULL", l);
             if (L->ix.B != L->at.B || L->ix.Tq != L->at.Tq || L->ix.k_sel != L->at.k_sel)
                 return fail(IC_ERR_SHAPE, "layer %d: indexer and attention disagree on B, Tq or k_sel", l);
+            if (L->ix.Lk != L->at.Lk)
+                return fail(IC_ERR_SHAPE, "layer %d: indexer scores %d keys but the KV cache holds %d rows", l, L->ix.Lk, L->at.Lk);
+            idx_lk = L->ix.Lk;
+        } else if (L->at.Lk < idx_lk) {
+            // a Shared layer reads positions selected among idx_lk keys: its own cache must hold them all
+            return fail(IC_ERR_SHAPE, "Shared layer %d: its KV cache holds %d rows, the inherited indices cover %d", l, L->at.Lk, idx_lk);
         }
         if (L->at.B != layers[0].at.B || L->at.Tq != layers[0].at.Tq || L->at.k_sel != layers[0].at.k_sel)
             return fail(IC_ERR_SHAPE, "layer %d: all layers must share B, Tq and k_sel (one index buffer)", l);
@@ -901,8 +908,8 @@ ic_status ic_prof_collect(void)
         } else {
             rc = fail(IC_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
         }
-        hipEventDestroy(r.e0);
-        hipEventDestroy(r.e1);
+        (void)hipEventDestroy(r.e0);
+        (void)hipEventDestroy(r.e1);
     }
     g_prof_recs.clear();
     return rc;

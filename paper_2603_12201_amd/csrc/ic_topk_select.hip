@@ -298,9 +298,12 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
     }
 
     // ---- ordered emit, general case: slot = #greater before + min(#equal before, need_eq) ----
-    // A thread owns 4 consecutive positions; counts of greater / equal entries travel packed in
-    // one word (equal << 16 | greater) through a wave scan and a 16-entry scan of the wave totals.
-    uint32_t run = 0;                                  // packed counts of all previous chunks
+    // A thread owns 4 consecutive positions; the counts of greater / equal entries of ONE chunk
+    // (at most 4 * NT of each) travel packed in one word (equal << 16 | greater) through a wave scan
+    // and a 16-entry scan of the wave totals.  The totals over all previous chunks are kept in two
+    // full words: a row longer than 65535 keys may tie with the k-th score in more than 65535 places.
+    static_assert(4 * NT < 65536, "per-chunk counts must fit 16 bits");
+    uint32_t run_g = 0, run_e = 0;                     // greater / equal entries of all previous chunks
 #pragma unroll 1
     for (int c = 0; c < nchunks; ++c) {
         const int p = c * 4 * NT + 4 * tid;
@@ -331,8 +334,8 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
         }
         const uint32_t waves_before = wave == 0 ? 0u : __shfl(ws, wave - 1);
         const uint32_t chunk_total = __shfl(ws, NW - 1);
-        uint32_t before = run + waves_before + incl - mine;
-        uint32_t g_before = before & 0xFFFFu, e_before = before >> 16;
+        const uint32_t before = waves_before + incl - mine;   // inside this chunk: both fields < 65536
+        uint32_t g_before = run_g + (before & 0xFFFFu), e_before = run_e + (before >> 16);
         if ((gm | em) != 0u) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -348,7 +351,8 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
                 e_before += q ? 1u : 0u;
             }
         }
-        run += chunk_total;
+        run_g += chunk_total & 0xFFFFu;
+        run_e += chunk_total >> 16;
     }
 }
 

@@ -141,6 +141,16 @@ def test_forward_stack_argument_errors(ic):
     arr[1].at.k_sel = 32                                             # one index buffer: k_sel must agree
     assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, ws, None) == S.ERR_SHAPE
     arr[1].at.k_sel = 64
+    arr[0].ix.Lk = 8192                                              # indexer scores keys the KV cache does not hold
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, ws, None) == S.ERR_SHAPE
+    assert b"KV cache" in L.ic_last_error()
+    arr[0].ix.Lk = 4096
+    arr[1].at.Lk = 2048                                              # a Shared layer's cache is shorter than the inherited indices
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, ws, None) == S.ERR_SHAPE
+    assert b"Shared layer 1" in L.ic_last_error()
+    arr[1].at.Lk = 8192                                              # a longer one is fine: it gets past the shape checks
+    assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, 16, None) == S.ERR_WORKSPACE
+    arr[1].at.Lk = 4096
     arr[1].q = None                                                  # a Shared layer may omit q,k,w ...
     arr[0].q = None                                                  # ... a Full layer may not
     assert L.ic_forward_stack(arr, 2, bytes([1, 0]), p, p, ws, None) == S.ERR_NULL

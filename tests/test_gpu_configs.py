@@ -117,9 +117,15 @@ def test_all_full_mask_and_irregular_patterns(ic, oracle):
 
 
 def _sample_rows(Tq, k_sel, n, seed):
+    """n query rows: an even stride over the whole range plus the rows where something changes (the first
+    rows, the rows around k_sel where the select starts to cut, the first and last query each workgroup
+    of the chained attention kernel walks (rounds of 256 queries), the last rows) and a few random ones."""
     rng = np.random.default_rng(seed)
-    fixed = [0, 1, k_sel - 2, k_sel - 1, k_sel, k_sel + 1, Tq // 2, Tq - 2, Tq - 1]
+    fixed = [0, 1, k_sel - 2, k_sel - 1, k_sel, k_sel + 1, 255, 256, 257, Tq // 2, Tq - 257, Tq - 256, Tq - 255,
+             Tq - 2, Tq - 1]
     rows = set(r for r in fixed if 0 <= r < Tq)
+    stride = max(1, Tq // max(1, n - len(rows) - 8))
+    rows.update(range(stride // 2, Tq, stride))
     while len(rows) < n:
         rows.add(int(rng.integers(0, Tq)))
     return sorted(rows)
@@ -159,9 +165,9 @@ def test_indexer_topk_prefill_16k_sampled(ic, oracle):
     assert bool(((idx <= pos) | ~valid).all())
     d = idx[..., 1:] - idx[..., :-1]
     assert bool(((d > 0) | ~valid[..., 1:]).all())
-    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 20, 1)
+    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 256, 1)
     kinds = _check_indexer_rows(ic, oracle, cfg, lay, idx, sel, rows)
-    say("rows %s kinds %s" % (rows, kinds))
+    say("%d rows, kinds %s" % (len(rows), kinds))
 
 
 def test_decode_step_sampled(ic, oracle):
@@ -193,9 +199,15 @@ def test_prefill_32k_layer_sampled(ic, oracle):
     lay = synth.stack_layers(cfg, device="cuda", n_layers=1)[0]
     mask = [True]
     outs, idx_cache, n_idx = _run_stack(ic, cfg, [lay], mask)
-    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 14, 3)
-    kinds = _check_indexer_rows(ic, oracle, cfg, lay, idx_cache, None, rows)
-    say("rows %s kinds %s" % (rows, kinds))
+    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 256, 3)
+    # the selected scores come from the indexer entry point called on its own; its indices must be the
+    # ones the stack cached
+    idx1, sel1 = ic.indexer_topk(lay["q"], lay["k"], lay["w"], cfg["k_sel"], 0, want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(idx1, idx_cache)
+    kinds = _check_indexer_rows(ic, oracle, cfg, lay, idx_cache, sel1, rows)
+    del idx1, sel1
+    say("%d rows, kinds %s" % (len(rows), kinds))
     Qb, KVb = synth.bits(lay["Q"]), synth.bits(lay["KV"])
     idx_rows = np.ascontiguousarray(idx_cache[:, rows].cpu().numpy())
     want, _ = oracle.sparse_attn(Qb, KVb, idx_rows, cfg["d_v"], cfg["v_off"], synth.sm_scale(cfg), rows=rows,
@@ -212,9 +224,9 @@ def test_fp8_long_context_layer_sampled(ic, oracle):
     torch.cuda.synchronize()
     outs, idx_cache, n_idx = _run_stack(ic, cfg, [lay], [True])
     assert n_idx == 1
-    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 12, 5)
+    rows = _sample_rows(cfg["Tq"], cfg["k_sel"], 256, 5)
     kinds = _check_indexer_rows(ic, oracle, cfg, lay, idx_cache, None, rows)
-    say("rows %s kinds %s" % (rows, kinds))
+    say("%d rows, kinds %s" % (len(rows), kinds))
     Qb, KVb = synth.bits(lay["Q"][:, rows]), synth.bits(lay["KV"])
     idx_rows = np.ascontiguousarray(idx_cache[:, rows].cpu().numpy())
     # Q rows were gathered: address them as rows 0..n-1 of a compact Q

@@ -240,6 +240,37 @@ def test_topk_ties_cut_at_the_boundary_on_long_rows(ic, oracle, Lk):
         assert want.size == ks and np.array_equal(idx[0, i], want)
 
 
+@pytest.mark.parametrize("Lk", [70000, 140000])
+def test_topk_tie_class_beyond_65535_entries(ic, oracle, Lk):
+    # rows longer than 65536 keys take the select form that streams the row: there the tie class of the
+    # k-th score can hold more than 65535 entries.  (a) every score equal (w = 0): the k lowest positions
+    # win; (b) 100 larger scores spread over the row, everything else one tie class: the 100 plus the
+    # first k - 100 positions of the class, in position order
+    say("topk tie class beyond 65535 entries, Lk=%d" % Lk)
+    B, Tq, H, d, ks = 1, 2, 1, 64, 256
+    p0 = Lk - Tq
+    q = torch.zeros((B, Tq, H, d)); q[..., 3] = 1.0
+    g = torch.Generator().manual_seed(Lk + 7)
+    vals = torch.full((Lk,), 7.0)
+    big = torch.randperm(p0, generator=g)[:100]
+    vals[big] = 9.0
+    k = torch.zeros((B, Lk, d)); k[0, :, 3] = vals
+    w = torch.ones((B, Tq, H))
+    zero_w = torch.zeros((B, Tq, H))
+    idx0 = ic.indexer_topk(q.bfloat16().cuda(), k.bfloat16().cuda(), zero_w.cuda(), ks, p0).cpu().numpy()
+    for i in range(Tq):
+        assert np.array_equal(idx0[0, i], np.arange(ks)), "all-equal row: the k lowest positions must win"
+    idx = ic.indexer_topk(q.bfloat16().cuda(), k.bfloat16().cuda(), w.cuda(), ks, p0).cpu().numpy()
+    sc = oracle.indexer_scores(synth.bits(q.bfloat16()), synth.bits(k.bfloat16()), synth.bits(w), p0)
+    v = vals.numpy()
+    for i in range(Tq):
+        nv = p0 + i + 1
+        assert parity.check_idx_row(idx[0, i], sc[0, i], nv, ks, oracle) == "tie"
+        sevens = np.nonzero(v[:nv] == 7.0)[0][:ks - 100]
+        want = np.sort(np.concatenate([np.sort(big.numpy()), sevens]))
+        assert np.array_equal(idx[0, i], want)
+
+
 @pytest.mark.parametrize("Lk", [3000, 9000, 40000, 70000])
 def test_topk_boundary_bin_fully_selected(ic, oracle, Lk):
     # exactly k winners, all inside one bin of the first radix digit ([64, 72): sixteen bf16 values),
