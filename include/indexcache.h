@@ -331,6 +331,24 @@ ic_status ic_debug_indexer_scores(const ic_indexer_desc *desc, const void *q, co
 uint64_t ic_debug_indexer_launch_count(void);
 
 /*
+ * Calibration (a measurement aid for the roofline figures of Sec. 4.3-style throughput reports, not part of
+ * the method): what the chip sustains on the patterns the hot path is made of, launched on `stream` through
+ * this library so that a benchmark can time them beside the real kernels.
+ *   IC_CALIB_READ       read n bytes from src (n a multiple of 16); dst: >= 4 * wgs bytes, rarely written
+ *   IC_CALIB_COPY       copy n bytes from src to dst
+ *   IC_CALIB_GATHER     read n rows of row_bytes (1152 or 256) from the table src [table_rows, row_bytes],
+ *                       row numbers in idx [n] int32 (device; values outside the table are clamped), eight
+ *                       lanes per 128-byte line as the attention kernels do; dst as for READ
+ *   IC_CALIB_MFMA_BF16  n back-to-back rounds of four v_mfma_f32_32x32x16_bf16 per wave (4 waves per
+ *   IC_CALIB_MFMA_FP8   workgroup), or of four 32x32x64 e4m3 instructions; dst: >= 1024 * wgs bytes
+ * wgs = workgroups of 256 threads to launch (1 .. 2^20).  All pointers are device pointers owned by the
+ * caller; nothing is allocated.  Errors: IC_ERR_NULL, IC_ERR_SHAPE, IC_ERR_UNSUPPORTED (row_bytes), IC_ERR_HIP.
+ */
+enum { IC_CALIB_READ = 0, IC_CALIB_COPY = 1, IC_CALIB_GATHER = 2, IC_CALIB_MFMA_BF16 = 3, IC_CALIB_MFMA_FP8 = 4 };
+ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows,
+                       int32_t row_bytes, int32_t wgs, void *stream);
+
+/*
  * Per-kernel timing with HIP events recorded on the launch stream (a measuring aid; off by
  * default).  ic_prof_enable(1) starts recording an event pair around every kernel launch
  * (bounded pool of 8192 pairs; launches beyond it are not recorded), ic_prof_enable(0) stops.

@@ -16,5 +16,6 @@ from .binding import (  # noqa: F401
     paged_cache, indexer_topk_paged, sparse_attn_paged, forward_stack_paged,
     debug_indexer_scores, debug_indexer_launch_count,
     prof_enable, prof_collect, prof_get, prof_reset,
+    calibrate, CALIB_READ, CALIB_COPY, CALIB_GATHER, CALIB_MFMA_BF16, CALIB_MFMA_FP8,
     IndexerDesc, AttnDesc, Layer, PagedCache,
 )

@@ -63,6 +63,8 @@ def lib():
         L.ic_sparse_attn_workspace.argtypes = [C.POINTER(AttnDesc)]
         L.ic_sparse_attn.restype = C.c_int
         L.ic_sparse_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.ic_calibrate.restype = C.c_int
+        L.ic_calibrate.argtypes = [i32, vp, vp, vp, C.c_int64, C.c_int64, i32, i32, vp]
         L.ic_forward_stack_workspace.restype = sz
         L.ic_forward_stack_workspace.argtypes = [C.POINTER(Layer), i32]
         L.ic_forward_stack.restype = C.c_int
@@ -231,6 +233,15 @@ def sparse_attn(Q, KV, idx, d_v, v_off, sm_scale, want_lse=False, workspace=None
     _check(lib().ic_sparse_attn(C.byref(d), _ptr(Q), _ptr(KV), _ptr(idx), _ptr(O), _ptr(lse),
                                 _ptr(workspace), workspace.numel(), _stream(stream)))
     return (O, lse) if want_lse else O
+
+
+CALIB_READ, CALIB_COPY, CALIB_GATHER, CALIB_MFMA_BF16, CALIB_MFMA_FP8 = range(5)
+
+
+def calibrate(kind, src, dst, idx=None, n=0, table_rows=0, row_bytes=0, wgs=2048, stream=None):
+    """ic_calibrate: one launch of a calibration kernel on the current stream (see indexcache.h)."""
+    _check(lib().ic_calibrate(kind, _ptr(src), _ptr(dst), _ptr(idx), int(n), int(table_rows), int(row_bytes), int(wgs),
+                              _stream(stream)))
 
 
 def paged_cache(seq_lens=None, page_table=None, page_size=0):

@@ -888,6 +888,28 @@ ic_status ic_debug_indexer_scores(const ic_indexer_desc *d, const void *q, const
 
 uint64_t ic_debug_indexer_launch_count(void) { return g_indexer_launches.load(); }
 
+ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows,
+                       int32_t row_bytes, int32_t wgs, void *stream)
+{
+    if (kind < IC_CALIB_READ || kind > IC_CALIB_MFMA_FP8) return fail(IC_ERR_SHAPE, "unknown calibration kind %d", kind);
+    if (!dst) return fail(IC_ERR_NULL, "dst must not be NULL");
+    if (wgs < 1 || wgs > (1 << 20)) return fail(IC_ERR_SHAPE, "wgs=%d outside [1, 2^20]", wgs);
+    if (n < 0) return fail(IC_ERR_SHAPE, "n must not be negative");
+    if (kind == IC_CALIB_READ || kind == IC_CALIB_COPY) {
+        if (!src) return fail(IC_ERR_NULL, "src must not be NULL");
+        if (n % 16 != 0) return fail(IC_ERR_SHAPE, "n=%lld bytes is not a multiple of 16", (long long)n);
+    } else if (kind == IC_CALIB_GATHER) {
+        if (!src || !idx) return fail(IC_ERR_NULL, "src and idx must not be NULL");
+        if (table_rows < 1) return fail(IC_ERR_SHAPE, "table_rows must be positive");
+        if (row_bytes != 1152 && row_bytes != 256) return fail(IC_ERR_UNSUPPORTED, "row_bytes=%d (1152 or 256)", row_bytes);
+    } else if (n > INT32_MAX) {
+        return fail(IC_ERR_SHAPE, "too many rounds");
+    }
+    hipError_t e = ic::launch_calib(kind, src, dst, idx, n, table_rows, row_bytes, wgs, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "calibration launch failed: %s", hipGetErrorString(e));
+    return IC_OK;
+}
+
 void ic_prof_enable(int32_t on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -131,6 +131,8 @@ hipError_t launch_sim_init(double *S, int n, hipStream_t st);
 hipError_t launch_loss_finish(const double *sims, int n, double *loss, hipStream_t st);
 hipError_t launch_attn_probs(const ProbsArgs &a, int d_qk, hipStream_t st);
 hipError_t launch_distill(const DistillArgs &a, int64_t nq, double *loss_multi, double *loss_avg, hipStream_t st);
+hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows, int row_bytes,
+                        int wgs, hipStream_t st);
 bool score_shape_supported(int dtype, int H_I, int d_I);
 bool attn_shape_supported(int d_qk, int d_v);
 
