@@ -112,6 +112,23 @@ size_t ic_sparse_attn_workspace(const ic_attn_desc *desc);
 ic_status ic_sparse_attn(const ic_attn_desc *desc, const void *Q, const void *KV, const int32_t *idx,
                          void *O, float *lse, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * ic_sparse_attn for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same computation and the same kernels, with the
+ * split-attention partials in a scratch array that is part of the library's code object instead of a
+ * caller workspace.  Nothing is allocated or freed, by the library or any routine it calls.
+ *   - The scratch holds IC_STATIC_SCRATCH_BYTES per GPU for the life of the process.  A descriptor
+ *     whose ic_sparse_attn_workspace() exceeds it is rejected with IC_ERR_WORKSPACE before any launch.
+ *   - The device the stream belongs to must be the current device of the calling thread.
+ *   - Every call on one GPU shares that GPU's scratch: calls that overlap in time on one GPU (other
+ *     streams, other threads) race.  Calls on one stream are ordered and safe.  The kernels overwrite
+ *     every partial they later read, so nothing needs clearing between calls.
+ * Arguments, results and error behaviour are otherwise those of ic_sparse_attn.
+ */
+#define IC_STATIC_SCRATCH_BYTES (16u << 20)
+ic_status ic_sparse_attn_static(const ic_attn_desc *desc, const void *Q, const void *KV, const int32_t *idx,
+                                void *O, float *lse, void *stream);
+
 /* One attention layer of the stack: its indexer problem and its attention problem. */
 typedef struct ic_layer {
     ic_indexer_desc ix;

@@ -7,7 +7,7 @@ PyTorch is used for device memory and streams only.
 """
 from .binding import (  # noqa: F401
     IcError, Status, lib, lib_path, last_error,
-    indexer_topk, indexer_topk_workspace, sparse_attn, sparse_attn_workspace,
+    indexer_topk, indexer_topk_workspace, sparse_attn, sparse_attn_workspace, sparse_attn_static, STATIC_SCRATCH_BYTES,
     forward_stack, forward_stack_workspace, make_layers,
     pattern_from_string, pattern_uniform, topk_overlap,
     cosine_rows, similarity_matrix, pattern_search_dp,

@@ -65,6 +65,8 @@ def lib():
         L.ic_sparse_attn.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp, sz, vp]
         L.ic_calibrate.restype = C.c_int
         L.ic_calibrate.argtypes = [i32, vp, vp, vp, C.c_int64, C.c_int64, i32, i32, vp]
+        L.ic_sparse_attn_static.restype = C.c_int
+        L.ic_sparse_attn_static.argtypes = [C.POINTER(AttnDesc), vp, vp, vp, vp, vp, vp]
         L.ic_forward_stack_workspace.restype = sz
         L.ic_forward_stack_workspace.argtypes = [C.POINTER(Layer), i32]
         L.ic_forward_stack.restype = C.c_int
@@ -242,6 +244,17 @@ def calibrate(kind, src, dst, idx=None, n=0, table_rows=0, row_bytes=0, wgs=2048
     """ic_calibrate: one launch of a calibration kernel on the current stream (see indexcache.h)."""
     _check(lib().ic_calibrate(kind, _ptr(src), _ptr(dst), _ptr(idx), int(n), int(table_rows), int(row_bytes), int(wgs),
                               _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def sparse_attn_static(Q, KV, idx, d_v, v_off, sm_scale, out, lse=None, stream=None):
+    """ic_sparse_attn_static: ic_sparse_attn with the split partials in the library's own static scratch.
+    Allocates nothing: the caller passes `out` [B,Tq,H_q,d_v] bf16 (and `lse` [B,Tq,H_q] fp32 if wanted)."""
+    d = attn_desc(Q, KV, idx, d_v, v_off, sm_scale)
+    _check(lib().ic_sparse_attn_static(C.byref(d), _ptr(Q), _ptr(KV), _ptr(idx), _ptr(out), _ptr(lse), _stream(stream)))
+    return out
 
 
 def paged_cache(seq_lens=None, page_table=None, page_size=0):

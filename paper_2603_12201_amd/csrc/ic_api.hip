@@ -10,6 +10,10 @@
 
 #include "ic_common.hpp"
 
+// Scratch for ic_sparse_attn_static: part of the code object, one copy per GPU at its own address.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[IC_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -328,6 +332,49 @@ ic_status ic_sparse_attn(const ic_attn_desc *d, const void *Q, const void *KV, c
     s = check_ws(workspace, workspace_bytes, attn_ws_bytes(d));
     if (s != IC_OK) return s;
     return run_attn(d, Q, KV, idx, O, lse, workspace, (hipStream_t)stream);
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current GPU's copy of `scratch`, looked up once per device.
+ic_status static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(IC_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(IC_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(IC_ERR_HIP, "address of the static scratch on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return IC_OK;
+}
+} // namespace
+
+ic_status ic_sparse_attn_static(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, void *O,
+                                float *lse, void *stream)
+{
+    ic_status s = check_attn(d);
+    if (s != IC_OK) return s;
+    if (!Q || !KV || !idx || !O) return fail(IC_ERR_NULL, "Q, KV, idx and O must not be NULL");
+    const size_t need = attn_ws_bytes(d);
+    if (need > (size_t)IC_STATIC_SCRATCH_BYTES)
+        return fail(IC_ERR_WORKSPACE, "this shape needs %zu bytes of split-attention scratch, the static scratch holds %zu",
+                    need, (size_t)IC_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (need > 0) {
+        s = static_scratch(&ws);
+        if (s != IC_OK) return s;
+    }
+    return run_attn(d, Q, KV, idx, O, lse, ws, (hipStream_t)stream);
 }
 
 static ic_status check_stack(const ic_layer *layers, int32_t n, const uint8_t *full_mask)
