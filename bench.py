@@ -19,12 +19,10 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the kernels at the configs[3] per-layer shape, from rocprofv3 FETCH_SIZE +
-# WRITE_SIZE scaled by a plain-copy reference (profiles/attn_score_select_prefill32k_hbm_traffic.txt).
-MEASURED_TRAFFIC_BYTES = {"sparse_attn": 18.88e9 + 1.07e9, "indexer_score": 0.452e9 + 0.566e9,
-                          "topk_select": 0.672e9 + 0.068e9}
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+MFMA_FP8_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 MFMA, published
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
 KERNELS = ["indexer_score", "topk_select", "sparse_attn", "attn_merge"]
 
 
@@ -54,15 +52,50 @@ def time_steps(fn, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def event_ms(fn, reps=5, warmup=1):
+    """Average duration of fn's device work in ms, between two events on torch's current stream (the
+    stream the binding hands to the library)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def measured_traffic():
+    """HBM bytes per launch from the tracked rocprofv3 counter summary (lines 'traffic <kernel> <workload>
+    fetch_bytes=<f> write_bytes=<w>'); the file names the runs the figures come from."""
+    out = {"source": os.path.relpath(TRAFFIC_FILE, ROOT)}
+    try:
+        for line in open(TRAFFIC_FILE):
+            t = line.split()
+            if len(t) >= 5 and t[0] == "traffic":
+                kv = dict(x.split("=") for x in t[3:] if "=" in x)
+                out[(t[1], t[2])] = float(kv["fetch_bytes"]) + float(kv["write_bytes"])
+    except OSError:
+        out["source"] = None
+    return out
+
+
 def prof_snapshot(ic):
     ic.prof_collect()
     return {name: ic.prof_get(i) for i, name in enumerate(KERNELS)}
 
 
 class Stack:
-    """Device-resident layer tensors + the host layer array for ic_forward_stack."""
+    """Device-resident layer tensors + the host layer array for ic_forward_stack.  Every layer has its own
+    indexer inputs and its own KV cache; Q is distinct for the first `distinct_q` layers and cycled after
+    that (all layers by default; the long-context workload aliases it because 48 x 4.8 GB of Q and as much
+    of O do not fit beside the rest, and Q does not influence the indices).  Every layer writes its output to one
+    shared buffer (a layer's output is consumed at once in a model)."""
 
-    def __init__(self, ic, synth, cfg, n_layers, share_q_every):
+    def __init__(self, ic, synth, cfg, n_layers, distinct_q):
         import torch
         self.cfg, self.ic = cfg, ic
         B, Tq = cfg["B"], cfg["Tq"]
@@ -70,11 +103,11 @@ class Stack:
         self.layers = []
         for l in range(n_layers):
             d = synth.indexer_layer(cfg, l, device="cuda")
-            if l < share_q_every:
+            if l < distinct_q:
                 d.update(synth.attn_layer(cfg, l, device="cuda"))
-            else:   # cycle the big attention inputs (they do not influence the indices)
-                src = self.layers[l % share_q_every]
-                d["Q"], d["KV"] = src["Q"], src["KV"]
+            else:
+                d.update(synth.attn_layer(cfg, l, device="cuda", parts=("KV",)))
+                d["Q"] = self.layers[l % distinct_q]["Q"]
             self.layers.append(d)
             if l % 8 == 7:
                 torch.cuda.synchronize()
@@ -90,6 +123,50 @@ class Stack:
         self.ic.forward_stack(self.arr, mask, self.idx_cache, self.ws)
 
 
+def profile_pass(ic, stack, mask):
+    """Per-kernel durations of ONE step, from HIP events the library records around its launches on the
+    caller's stream.  A pass of its own, outside every timed region."""
+    import torch
+    ic.prof_reset()
+    torch.cuda.synchronize()
+    ic.prof_enable(True)
+    stack.step(mask)
+    torch.cuda.synchronize()
+    ic.prof_enable(False)
+    return prof_snapshot(ic)
+
+
+def kernel_table(alg, prof, n_full, n_layers, traffic, workload, fp8):
+    """Per-layer time and roofline position of the three kernels of a prefill step."""
+    t_score = prof["indexer_score"][1] / n_full
+    t_select = prof["topk_select"][1] / n_full
+    t_attn = prof["sparse_attn"][1] / n_layers
+    mfma_peak_ix = MFMA_FP8_PEAK_TFLOPS if fp8 else MFMA_BF16_PEAK_TFLOPS
+    k = {
+        "indexer_score": {"bound": "mfma", "ms_per_layer": t_score, "achieved": alg["indexer_flop"] / (t_score * 1e-3) / 1e12,
+                          "peak": mfma_peak_ix, "unit": "TFLOP/s", "launches_per_layer": prof["indexer_score"][0] / n_full},
+        "topk_select": {"bound": "hbm", "ms_per_layer": t_select, "achieved": alg["select_bytes"] / (t_select * 1e-3) / 1e9,
+                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "launches_per_layer": prof["topk_select"][0] / n_full},
+        # score and select together, priced as the one fused kernel they stand for: its flops against the MFMA peak
+        "indexer_plus_topk": {"bound": "mfma", "ms_per_layer": t_score + t_select,
+                              "achieved": alg["indexer_flop"] / ((t_score + t_select) * 1e-3) / 1e12, "peak": mfma_peak_ix,
+                              "unit": "TFLOP/s"},
+        # the gather is served out of L2 / Infinity Cache (a layer's KV is 38-151 MB, every row is fetched by
+        # many queries), so its arithmetic intensity against compulsory bytes is far above the ridge:
+        # the binding roofline is the MFMA rate of its flops
+        "sparse_attn": {"bound": "mfma", "ms_per_layer": t_attn, "achieved": alg["attn_flop"] / (t_attn * 1e-3) / 1e12,
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "launches_per_layer": prof["sparse_attn"][0] / n_layers,
+                        "gathered_GBs": alg["attn_bytes"] / (t_attn * 1e-3) / 1e9,
+                        "compulsory_bytes": alg["attn_unique_bytes"]},
+    }
+    for name, v in k.items():
+        v["frac"] = v["achieved"] / v["peak"]
+        t = traffic.get((name, workload))
+        if t is not None:
+            v["traffic"] = t
+    return k
+
+
 def algorithmic(cfg):
     """Algorithmic work of ONE layer's kernels: flops per causal pair, bytes per key / score / query token."""
     B, Tq, Lk, p0 = cfg["B"], cfg["Tq"], cfg["Lk"], cfg["q_pos0"]
@@ -102,6 +179,9 @@ def algorithmic(cfg):
         "attn_bytes": float(B) * Tq * (min(cfg["k_sel"], Lk) * cfg["row_elems"] * 2
                                        + cfg["H_q"] * cfg["d_qk"] * 2 + cfg["H_q"] * cfg["d_v"] * 2),
         "attn_flop": 2.0 * B * Tq * cfg["H_q"] * min(cfg["k_sel"], Lk) * (cfg["d_qk"] + cfg["d_v"]),
+        # what a layer must move at least: its KV once, Q, O and the index tensor
+        "attn_unique_bytes": float(B) * (Lk * cfg["row_elems"] * 2 + Tq * (cfg["H_q"] * (cfg["d_qk"] + cfg["d_v"]) * 2
+                                                                         + cfg["k_sel"] * 4)),
     }
 
 
@@ -143,21 +223,74 @@ def cpu_baseline(synth, cfg, layer_gpu, n_full, n_layers, budget_s=15.0):
     }
 
 
+def calibration(ic, synth, idx_prefill, kv_rows):
+    """What the chip sustains on the hot path's access and issue patterns, through the library's own
+    calibration kernels: the second denominator beside the published peaks."""
+    import torch
+    out = {}
+    scratch = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    n = 2 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    ms = event_ms(lambda: ic.calibrate(ic.CALIB_READ, src, scratch, n=n, wgs=4096))
+    out["stream_read"] = {"bytes": n, "ms": ms, "GBs": n / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    dst = torch.empty(n // 2, dtype=torch.uint8, device="cuda")
+    ms = event_ms(lambda: ic.calibrate(ic.CALIB_COPY, src, dst, n=n // 2, wgs=4096))
+    out["copy"] = {"bytes_read_plus_written": n, "ms": ms, "GBs": n / (ms * 1e-3) / 1e9}
+    del dst
+    # decode indexer: one pass over the index-key cache of configs[2] (32 x 65536 keys x 256 B)
+    nk = 32 * 65536 * 256
+    ms = event_ms(lambda: ic.calibrate(ic.CALIB_READ, src, scratch, n=nk, wgs=2048), reps=20, warmup=3)
+    out["decode_key_stream"] = {"bytes": nk, "us": ms * 1e3, "GBs": nk / (ms * 1e-3) / 1e9,
+                                "frac_of_hbm_peak": nk / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del src
+    # decode attention: 32 sequences x 2048 random rows of 1152 B out of a 2.4 GB cache (configs[2])
+    g = torch.Generator().manual_seed(77)
+    table = torch.empty((32 * 65536, 1152), dtype=torch.uint8, device="cuda").fill_(3)
+    rows = (torch.randint(0, 65536, (32, 2048), generator=g) + 65536 * torch.arange(32)[:, None]).to(torch.int32).cuda()
+    ms = event_ms(lambda: ic.calibrate(ic.CALIB_GATHER, table, scratch, idx=rows, n=rows.numel(), table_rows=table.shape[0],
+                                       row_bytes=1152, wgs=2048), reps=20, warmup=3)
+    gb = rows.numel() * 1152
+    out["decode_row_gather"] = {"bytes": gb, "us": ms * 1e3, "GBs": gb / (ms * 1e-3) / 1e9,
+                                "frac_of_hbm_peak": gb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                "note": "no compute attached, every row in flight at once"}
+    # prefill attention: the rows one L=32768 layer really selects, out of its 37.7 MB cache
+    if idx_prefill is not None:
+        flat = idx_prefill.reshape(-1)
+        ms = event_ms(lambda: ic.calibrate(ic.CALIB_GATHER, table, scratch, idx=flat, n=flat.numel(), table_rows=kv_rows,
+                                           row_bytes=1152, wgs=8192), reps=2, warmup=1)
+        gb = flat.numel() * 1152
+        out["prefill_row_gather"] = {"bytes": gb, "ms": ms, "GBs": gb / (ms * 1e-3) / 1e9,
+                                     "note": "served out of L2 / Infinity Cache; no compute attached"}
+    del table, rows
+    for kind, name, flop, peak in ((ic.CALIB_MFMA_BF16, "mfma_bf16", 2.0 * 32 * 32 * 16, MFMA_BF16_PEAK_TFLOPS),
+                                   (ic.CALIB_MFMA_FP8, "mfma_fp8", 2.0 * 32 * 32 * 64, MFMA_FP8_PEAK_TFLOPS)):
+        rounds, wgs = 20000, 512
+        ms = event_ms(lambda: ic.calibrate(kind, None, scratch, n=rounds, wgs=wgs), reps=3, warmup=1)
+        tf = flop * 4 * rounds * 4 * wgs / (ms * 1e-3) / 1e12
+        out[name] = {"TFLOPs": tf, "frac_of_published_peak": tf / peak, "waves_per_simd": 2,
+                     "note": "constant operands; under random operands the shader clock settles lower"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--layers", type=int, default=48, help="layers of the prefill stack (48 = the metric's workload)")
-    ap.add_argument("--distinct-attn-inputs", type=int, default=4,
-                    help="distinct per-layer Q/KV buffers to generate; later layers cycle through them")
+    ap.add_argument("--distinct-attn-inputs", type=int, default=48,
+                    help="layers with a Q tensor of their own (every layer has its own KV and indexer inputs); "
+                         "later layers cycle through those Q")
     ap.add_argument("--decode-steps", type=int, default=20)
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-calibrate", action="store_true", help="skip the calibration arm (stream, copy, gather, MFMA rounds)")
     ap.add_argument("--greedy-layers", type=int, default=6)
-    ap.add_argument("--no-fp8", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the configs[4] long-context fp8 stack arm")
+    ap.add_argument("--fp8-layers", type=int, default=48)
+    ap.add_argument("--fp8-distinct-q", type=int, default=2)
     ap.add_argument("--distill-targets", type=int, default=4)
-    ap.add_argument("--no-overlap", action="store_true", help="skip the cross-layer overlap diagnostic arm")
+    ap.add_argument("--no-overlap", action="store_true", help="skip the diagnostic arms (overlap, similarity, greedy, distillation)")
     ap.add_argument("--overlap-layers", type=int, default=48)
     ap.add_argument("--similarity-layers", type=int, default=8)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -177,6 +310,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    t_start = time.perf_counter()
+    traffic = measured_traffic()
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -194,69 +329,54 @@ def main():
     stack = Stack(ic, synth, cfg, n_layers, max(1, min(args.distinct_attn_inputs, n_layers)))
     alg = algorithmic(cfg)
     tokens = cfg["B"] * cfg["Tq"]
+    n_full = sum(mask_14)
 
+    # the timed regions carry no event records; the per-kernel split comes from a pass of its own
     log("prefill 1-in-4 arm")
-    ic.prof_reset()
-    for _ in range(args.warmup):
-        stack.step(mask_14)
-    torch.cuda.synchronize()
-    ic.prof_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        stack.step(mask_14)
-    torch.cuda.synchronize()
-    ms_14 = (time.perf_counter() - t0) * 1e3 / args.steps
-    ic.prof_enable(False)
-    prof_14 = prof_snapshot(ic)
-
+    ms_14 = time_steps(lambda: stack.step(mask_14), args.steps, args.warmup)
     log("prefill all-Full arm")
     ms_all = time_steps(lambda: stack.step(mask_all), max(1, args.steps - 1), 1)
+    log("per-kernel pass")
+    prof_14 = profile_pass(ic, stack, mask_14)
+    workload = "prefill32k" if cfg["Tq"] == 32768 else "other"
+    kernels = kernel_table(alg, prof_14, n_full, n_layers, traffic, workload, fp8=False)
 
-    def per_launch(prof, name):
-        n, ms = prof[name]
-        return (ms / n) if n else None
-
-    # per-layer kernel time (one layer = all its launches of that class)
-    n_full = sum(mask_14)
-    t_score = prof_14["indexer_score"][1] / (args.steps * n_full)
-    t_select = prof_14["topk_select"][1] / (args.steps * n_full)
-    t_attn = prof_14["sparse_attn"][1] / (args.steps * n_layers)
-    kernels = {
-        "indexer_score": {"bound": "mfma", "ms_per_layer": t_score,
-                          "achieved": alg["indexer_flop"] / (t_score * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
-                          "unit": "TFLOP/s", "launches_per_layer": prof_14["indexer_score"][0] / (args.steps * n_full)},
-        "topk_select": {"bound": "hbm", "ms_per_layer": t_select,
-                        "achieved": alg["select_bytes"] / (t_select * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "launches_per_layer": prof_14["topk_select"][0] / (args.steps * n_full)},
-        "sparse_attn": {"bound": "hbm", "ms_per_layer": t_attn,
-                        "achieved": alg["attn_bytes"] / (t_attn * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "launches_per_layer": prof_14["sparse_attn"][0] / (args.steps * n_layers),
-                        "mfma_tflops": alg["attn_flop"] / (t_attn * 1e-3) / 1e12},
-    }
-    for k in kernels.values():
-        k["frac"] = k["achieved"] / k["peak"]
     # dominant kernel of the timed step = largest share of the step's time
-    share = {"indexer_score": t_score * n_full, "topk_select": t_select * n_full, "sparse_attn": t_attn * n_layers}
+    share = {"indexer_score": kernels["indexer_score"]["ms_per_layer"] * n_full,
+             "topk_select": kernels["topk_select"]["ms_per_layer"] * n_full,
+             "sparse_attn": kernels["sparse_attn"]["ms_per_layer"] * n_layers}
     dom = max(share, key=share.get)
-    roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
-                "peak": kernels[dom]["peak"], "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"],
-                "traffic": MEASURED_TRAFFIC_BYTES.get(dom) if cfg["Tq"] == 32768 else None,
-                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE+WRITE_SIZE, scaled; see profiles/)",
-                "avg_launch_ms": per_launch(prof_14, dom),
+    kd = kernels[dom]
+    roofline = {"kernel": dom, "bound": kd["bound"], "achieved": kd["achieved"], "peak": kd["peak"], "unit": kd["unit"],
+                "frac": kd["frac"], "traffic": kd.get("traffic"),
+                "traffic_unit": "HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a plain copy",
+                "traffic_source": traffic.get("source"),
+                "avg_launch_ms": kd["ms_per_layer"] / kd["launches_per_layer"],
+                "timing": "HIP events around every launch of one 1-in-4 step, a pass of its own after the timed region",
                 "share_of_step": share[dom] / sum(share.values())}
     if dom == "sparse_attn":
-        # the gathered rows of neighbouring queries are re-used out of L2 / Infinity Cache (unique KV is
-        # 37.7 MB), so the algorithmic gather rate may exceed the HBM peak; the kernel's own bounds are
-        # the MFMA rate of its flops and the LDS data path every gathered byte crosses
-        roofline["mfma_frac"] = kernels[dom]["mfma_tflops"] / MFMA_BF16_PEAK_TFLOPS
-        roofline["note"] = ("achieved = algorithmic gathered bytes / time; HBM traffic (field traffic) is 4x smaller "
-                            "because selected rows are re-used out of L2, so frac can exceed 1")
+        roofline["gathered_GBs"] = kd["gathered_GBs"]
+        roofline["compulsory_bytes"] = kd["compulsory_bytes"]
+        roofline["note"] = ("algorithmic flops per launch (2 * H_q * k * (d_qk + d_v) per query token) against the bf16 MFMA peak; "
+                            "the gathered rows (gathered_GBs, algorithmic) come out of L2 / Infinity Cache, the HBM side "
+                            "moves only `traffic`")
 
     arms = {
         "prefill_1in4": {"ms_per_step": ms_14, "tokens_per_s": tokens / (ms_14 * 1e-3), "full_layers": n_full},
         "prefill_all_full": {"ms_per_step": ms_all, "tokens_per_s": tokens / (ms_all * 1e-3), "full_layers": n_layers},
         "prefill_speedup_1in4_vs_all_full": ms_all / ms_14,
     }
+
+    if not args.no_calibrate:
+        log("calibration arm")
+        stack.step([True] + [False] * (n_layers - 1))           # idx_cache = layer 0's selection
+        torch.cuda.synchronize()
+        arms["calibration"] = calibration(ic, synth, stack.idx_cache if cfg["Tq"] == 32768 else None, cfg["Lk"])
+        cal = arms["calibration"]
+        if "prefill_row_gather" in cal:
+            kernels["sparse_attn"]["gather_only_ms"] = cal["prefill_row_gather"]["ms"]
+        kernels["sparse_attn"]["frac_of_measured_mfma"] = kernels["sparse_attn"]["achieved"] / cal["mfma_bf16"]["TFLOPs"]
+        kernels["indexer_score"]["frac_of_measured_mfma"] = kernels["indexer_score"]["achieved"] / cal["mfma_bf16"]["TFLOPs"]
 
     cpu = None
     if not args.no_cpu:
@@ -303,6 +423,13 @@ def main():
                                            "frac": dalg["attn_bytes"] / (d_att * 1e-3) / 1e9 / HBM_PEAK_GBS},
             },
         })
+        if "calibration" in arms:
+            # the same bytes with no compute attached, through the library's calibration kernels
+            dk, cal = arms["decode_kernels"], arms["calibration"]
+            dk["indexer_plus_topk"]["stream_only_ms"] = cal["decode_key_stream"]["us"] * 1e-3
+            dk["indexer_plus_topk"]["frac_of_stream_only"] = cal["decode_key_stream"]["us"] * 1e-3 / d_idx
+            dk["sparse_attn_plus_merge"]["gather_only_ms"] = cal["decode_row_gather"]["us"] * 1e-3
+            dk["sparse_attn_plus_merge"]["frac_of_gather_only"] = cal["decode_row_gather"]["us"] * 1e-3 / d_att
         # the same caches read through a page table (64-position pages in random physical order),
         # first with every sequence at full length, then with a seeded mix of lengths in [Lk/2, Lk]
         log("paged decode arm")
@@ -442,25 +569,31 @@ def main():
             "note": "identical targets here, so Eq. 1 = Eq. 2; timing only"}
         del probs_d, atd, idx_d, sel_d
 
-    # ---------------- the FP8 indexer at configs[4] (L = 131072, 64 heads, e4m3 + per-token scales) ----------------
+    # ---------------- configs[4]: the long-context fp8 stack (L = 131072, 64 fp8 indexer heads, 48 layers, 12 Full) ----------------
     if not args.no_fp8:
-        log("fp8 indexer arm (configs[4], one Full layer)")
-        c4 = synth.config("c4")
-        l4 = synth.indexer_layer(c4, 0, device="cuda")
-        from paper_2603_12201_amd import binding as icb
-        ws4 = torch.empty(ic.indexer_topk_workspace(icb.indexer_desc(l4["q"], l4["k"], l4["w"], c4["k_sel"], 0,
-                                                                     l4["q_scale"], l4["k_scale"])), dtype=torch.uint8, device="cuda")
-        idx4 = torch.empty((c4["B"], c4["Tq"], c4["k_sel"]), dtype=torch.int32, device="cuda")
-        run4 = lambda: ic.indexer_topk(l4["q"], l4["k"], l4["w"], c4["k_sel"], 0, q_scale=l4["q_scale"], k_scale=l4["k_scale"],
-                                       idx=idx4, workspace=ws4)
-        ms4 = time_steps(run4, 2, 1)
-        flop4 = 2.0 * c4["H_I"] * c4["d_I"] * (c4["Tq"] * (c4["Tq"] + 1) / 2)
-        arms["indexer_fp8_c4"] = {
-            "L": c4["Tq"], "H_I": c4["H_I"], "ms_indexer_plus_topk": ms4,
-            "tokens_per_s_one_full_layer": c4["Tq"] / (ms4 * 1e-3),
-            "score_flop": flop4, "PFLOPs_incl_topk": flop4 / (ms4 * 1e-3) / 1e15, "peak_PFLOPs": 5.0,
-            "note": "wall time of ic_indexer_topk; per-kernel split in profiles/indexer_fp8_131k_kernel_trace.txt"}
-        del l4, ws4, idx4
+        torch.cuda.empty_cache()
+        c4 = synth.config("c4", n_layers=args.fp8_layers)
+        n4 = args.fp8_layers
+        log("configs[4] stack: %d layers at L = %d (fp8 indexer)" % (n4, c4["Tq"]))
+        s4 = Stack(ic, synth, c4, n4, max(1, min(args.fp8_distinct_q, n4)))
+        m4_14 = ic.pattern_uniform(n4, 4)
+        m4_all = [True] * n4
+        alg4 = algorithmic(c4)
+        ms4_14 = time_steps(lambda: s4.step(m4_14), 1, 1)
+        ms4_all = time_steps(lambda: s4.step(m4_all), 1, 0)
+        prof4 = profile_pass(ic, s4, m4_14)
+        k4 = kernel_table(alg4, prof4, sum(m4_14), n4, traffic, "prefill131k_fp8", fp8=True)
+        arms["prefill_fp8_131k"] = {
+            "workload": "configs[4]: 1 sequence, L=131072, %d layers, H_I=64 d_I=128 e4m3 q/k with per-token scales, k=2048, "
+                        "MQA 32 heads, KV row 576 bf16; every layer has its own KV and indexer inputs, Q cycles over %d tensors "
+                        "and O is one buffer (48 x 4.8 GB of Q and 4.3 GB of O per layer do not fit beside the rest)"
+                        % (n4, min(args.fp8_distinct_q, n4)),
+            "prefill_1in4": {"ms_per_step": ms4_14, "tokens_per_s": c4["Tq"] / (ms4_14 * 1e-3), "full_layers": sum(m4_14), "steps": 1},
+            "prefill_all_full": {"ms_per_step": ms4_all, "tokens_per_s": c4["Tq"] / (ms4_all * 1e-3), "full_layers": n4, "steps": 1},
+            "prefill_speedup_1in4_vs_all_full": ms4_all / ms4_14,
+            "kernels": k4,
+        }
+        del s4
 
     out = {
         "metric": "prefill & decode tokens/s, 48-layer DSA stack L=32K, 1-in-4 Full vs all-Full",
@@ -470,13 +603,14 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[3]: 48-layer attention-only DSA stack prefill, 1 sequence, L=32768, "
                                "H_I=32 d_I=128 k=2048, MQA 32 heads, KV row 576 bf16, 1-in-4 Full (value); "
-                               "all-Full and decode (configs[2]) in arms",
+                               "all-Full, decode (configs[2]) and the fp8 long-context stack (configs[4]) in arms",
                    "layers": n_layers, "pattern": "FSSS x%d" % (n_layers // 4), "L": cfg["Tq"], "k_sel": cfg["k_sel"],
-                   "distinct_attn_inputs": min(args.distinct_attn_inputs, n_layers)},
+                   "distinct_q_tensors": min(args.distinct_attn_inputs, n_layers), "distinct_kv_and_indexer_inputs": n_layers},
         "roofline": roofline,
         "kernels": kernels,
         "arms": arms,
         "cpu_baseline": cpu,
+        "bench_wall_s": time.perf_counter() - t_start,
     }
     print(json.dumps(out), flush=True)
 

@@ -125,15 +125,19 @@ def chain_indexer_layers(cfg, n_layers, device="cpu", rho=0.8):
                "k": k.to(torch.bfloat16).contiguous(), "w": w.contiguous()}
 
 
-def attn_layer(cfg, layer, device="cpu"):
-    """Q [B,Tq,H_q,d_qk] bf16 and KV [B,Lk,row_elems] bf16."""
+def attn_layer(cfg, layer, device="cpu", parts=("Q", "KV")):
+    """Q [B,Tq,H_q,d_qk] bf16 and KV [B,Lk,row_elems] bf16 (each has its own random stream, so either can
+    be drawn alone with `parts`)."""
     B, Tq, Lk = cfg["B"], cfg["Tq"], cfg["Lk"]
     seed = cfg["seed"]
-    Q = torch.randn((B, Tq, cfg["H_q"], cfg["d_qk"]), generator=_gen(seed, layer, "Q", device),
-                    device=device, dtype=torch.bfloat16)
-    KV = torch.randn((B, Lk, cfg["row_elems"]), generator=_gen(seed, layer, "KV", device),
-                     device=device, dtype=torch.bfloat16)
-    return {"Q": Q.contiguous(), "KV": KV.contiguous()}
+    out = {}
+    if "Q" in parts:
+        out["Q"] = torch.randn((B, Tq, cfg["H_q"], cfg["d_qk"]), generator=_gen(seed, layer, "Q", device),
+                               device=device, dtype=torch.bfloat16).contiguous()
+    if "KV" in parts:
+        out["KV"] = torch.randn((B, Lk, cfg["row_elems"]), generator=_gen(seed, layer, "KV", device),
+                                device=device, dtype=torch.bfloat16).contiguous()
+    return out
 
 
 def stack_layers(cfg, device="cpu", n_layers=None):
