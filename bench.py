@@ -75,9 +75,12 @@ def measured_traffic():
     try:
         for line in open(TRAFFIC_FILE):
             t = line.split()
-            if len(t) >= 5 and t[0] == "traffic":
+            if len(t) >= 5 and line.startswith("traffic "):
                 kv = dict(x.split("=") for x in t[3:] if "=" in x)
-                out[(t[1], t[2])] = float(kv["fetch_bytes"]) + float(kv["write_bytes"])
+                try:
+                    out[(t[1], t[2])] = float(kv["fetch_bytes"]) + float(kv["write_bytes"])
+                except (KeyError, ValueError):
+                    pass
     except OSError:
         out["source"] = None
     return out

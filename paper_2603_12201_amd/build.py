@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libindexcache.so")
-SOURCES = ["ic_api.hip", "ic_indexer_score.hip", "ic_topk_select.hip", "ic_sparse_attn.hip",
+SOURCES = ["ic_api.hip", "ic_indexer_score.hip", "ic_topk_select.hip", "ic_sparse_attn.hip", "ic_attn_prefill.hip",
            "ic_overlap.hip", "ic_similarity.hip", "ic_distill.hip", "ic_calibrate.hip"]
 HEADERS = [os.path.join(CSRC, "ic_common.hpp"), os.path.join(ROOT, "include", "indexcache.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -34,9 +34,9 @@ def _run(cmd, verbose):
         raise subprocess.CalledProcessError(p.returncode, cmd)
 
 
-def build(verbose: bool = False, extra=(), incremental: bool = False, out: str = OUT, jobs: int = 8) -> str:
+def compile_objects(verbose: bool = False, extra=(), incremental: bool = False, tag: str = "", jobs: int = 8):
+    """Compile every source to _build/<source><tag>.o (in parallel); returns the object paths."""
     os.makedirs(OBJ, exist_ok=True)
-    tag = "" if out == OUT else "." + os.path.basename(out)
     newest_hdr = max(os.path.getmtime(h) for h in HEADERS)
     work = []
     objs = []
@@ -49,6 +49,11 @@ def build(verbose: bool = False, extra=(), incremental: bool = False, out: str =
             work.append(["hipcc"] + FLAGS + list(extra) + ["-c", src, "-o", obj])
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(work) or 1))) as ex:
         list(ex.map(lambda c: _run(c, verbose), work))
+    return objs
+
+
+def build(verbose: bool = False, extra=(), incremental: bool = False, out: str = OUT, jobs: int = 8) -> str:
+    objs = compile_objects(verbose, extra, incremental, "" if out == OUT else "." + os.path.basename(out), jobs)
     _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC"] + list(extra) + objs + ["-o", out], verbose)
     return out
 
