@@ -231,8 +231,21 @@ __global__ __launch_bounds__(512, 1) void attn_prefill_kernel(AttnArgs a)
         for (int r = 0; r < 9; ++r) gather_piece(c, r);
     };
 
+    // V operands of tile j (published) for the P V that follows the next barrier
+    auto vfetch = [&](int j) {
+        const unsigned char *tbV = smem + kOffV + ((g0 + j) & 1) * kVBuf;
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                vq[jj][nb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tbV + t_v[0][nb] + 16 * jj * kVRow));
+                vq[jj][nb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tbV + t_v[1][nb] + 16 * jj * kVRow));
+            }
+    };
+
     // S^T, V fetch and softmax of tile j (already in LDS and published); idv = the lane's row id for validity
-    auto produce = [&](int j, int idv, const Gather *gc) {
+    auto produce = [&](int j, int idv, const Gather *gc, bool with_v) {
         const int par = (g0 + j) & 1;
         const unsigned char *tbV = smem + kOffV + par * kVBuf;
         const unsigned char *tbR = smem + kOffR + par * kRBuf;
@@ -257,31 +270,28 @@ __global__ __launch_bounds__(512, 1) void attn_prefill_kernel(AttnArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                vq[jj][nb][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tbV + t_v[0][nb] + 16 * jj * kVRow));
-                vq[jj][nb][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tbV + t_v[1][nb] + 16 * jj * kVRow));
-            }
+        if (with_v) vfetch(j);
 
         float z[4], mx = -INFINITY;
+        const bool all_rows = vm == 0xFFFFu;              // wave-uniform: no empty slot among the wave's 16 rows
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const bool ok = (vm >> (4 * g + i)) & 1u;
-            z[i] = ok ? (s4[0][i] + s4[1][i]) * a.scale_log2e : -INFINITY;
+            z[i] = (s4[0][i] + s4[1][i]) * a.scale_log2e;
+            if (!all_rows) z[i] = ((vm >> (4 * g + i)) & 1u) ? z[i] : -INFINITY;
             mx = fmaxf(mx, z[i]);
         }
         mx = xmax16_32(mx);
-        // lazy reference: keep the common reference until this tile exceeds it by more than 2^kLazyLog2
-        const float m_new = (mx > m_all + kLazyLog2) ? mx : m_all;       // m_all >= m_ref always
+        // lazy reference: keep the common reference until this tile exceeds it by more than 2^kLazyLog2.  m_all may
+        // lag one tile behind (the waves that produce before they consume): the consumer side never lowers its reference.
+        const float m_base = fmaxf(m_all, m_ref);         // a wave never lowers its own reference either
+        const float m_new = (mx > m_base + kLazyLog2) ? mx : m_base;
         const float resc = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref - m_new);
         float psum = 0.f;
         s16x4 pk;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float p = (z[i] == -INFINITY) ? 0.f : fast_exp2(z[i] - m_new);
+            float p = fast_exp2(z[i] - m_new);            // z = -inf gives 0 unless m_new is -inf too
+            if (!all_rows) p = (z[i] == -INFINITY) ? 0.f : p;
             psum += p;
             pk[i] = __builtin_bit_cast(short, (__bf16)p);
         }
@@ -300,36 +310,43 @@ __global__ __launch_bounds__(512, 1) void attn_prefill_kernel(AttnArgs a)
         bf16x8 pa[4];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) pa[jj] = *(const bf16x8 *)(pp + (16 * jj + 8 * hh) * 2);
-        const float m_new_c = fmaxf(fmaxf(mjc[0], mjc[1]), fmaxf(mjc[2], mjc[3]));
-        // the producer role needs the new common reference of head 16hb + l16, which lives in another 16-lane group
-        const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m_new_c), __float_as_uint(m_new_c), false, false);
-        m_all = __uint_as_float(hb ? sw[1] : sw[0]);
-        const float alpha = (m_new_c == -INFINITY) ? 1.f : fast_exp2(m_c - m_new_c);
-        m_c = m_new_c;
-        float fj[4];
-        bool any_f = false;
+        // common case: all four row-block waves kept the common reference: nothing to rescale
+        const bool same = (mjc[0] == m_c) & (mjc[1] == m_c) & (mjc[2] == m_c) & (mjc[3] == m_c);
+        if (__ballot(!same) != 0ull) {
+            // the reference never goes down (a producer's reference may lag one tile behind the common one)
+            const float m_new_c = fmaxf(m_c, fmaxf(fmaxf(mjc[0], mjc[1]), fmaxf(mjc[2], mjc[3])));
+            const float alpha = (m_new_c == -INFINITY) ? 1.f : fast_exp2(m_c - m_new_c);
+            m_c = m_new_c;
+            float fj[4];
+            bool any_f = false;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            fj[jj] = (m_new_c == -INFINITY) ? 1.f : fast_exp2(mjc[jj] - m_new_c);
-            any_f |= (fj[jj] != 1.f);
+            for (int jj = 0; jj < 4; ++jj) {
+                fj[jj] = (m_new_c == -INFINITY) ? 1.f : fast_exp2(mjc[jj] - m_new_c);
+                any_f |= (fj[jj] != 1.f);
+            }
+            if (__ballot(alpha != 1.f) != 0ull) {
+                // rescale factors of the 16 heads a lane accumulates, through a per-wave LDS row (LDS serves a wave in order)
+                float *ab = abuf + w * 32;
+                if (hh == 0) ab[l32] = alpha;
+                f32x4 ar[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ar[q] = *(const f32x4 *)(ab + 8 * q + 4 * hh);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[nb][i] *= ar[i >> 2][i & 3];
+            }
+            if (__ballot(any_f) != 0ull) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) pa[jj][e] = (__bf16)((float)pa[jj][e] * fj[jj]);
+            }
         }
-        if (__ballot(alpha != 1.f) != 0ull) {
-            // rescale factors of the 16 heads a lane accumulates, through a per-wave LDS row (LDS serves a wave in order)
-            float *ab = abuf + w * 32;
-            if (hh == 0) ab[l32] = alpha;
-            f32x4 ar[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) ar[q] = *(const f32x4 *)(ab + 8 * q + 4 * hh);
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[nb][i] *= ar[i >> 2][i & 3];
-        }
-        if (__ballot(any_f) != 0ull) {
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pa[jj][e] = (__bf16)((float)pa[jj][e] * fj[jj]);
+        // the producer role needs the common reference of head 16hb + l16, which lives in another 16-lane group
+        {
+            const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m_c), __float_as_uint(m_c), false, false);
+            m_all = __uint_as_float(hb ? sw[1] : sw[0]);
         }
         typedef __attribute__((ext_vector_type(8))) short s16x8;
 #pragma unroll
@@ -403,7 +420,7 @@ __global__ __launch_bounds__(512, 1) void attn_prefill_kernel(AttnArgs a)
     int id_st_next = load_i32_async(id_addr(1, row_st()));
     wait_vm(id_dma, id_st_next);
     __syncthreads();
-    produce(0, id_st, nullptr);
+    produce(0, id_st, nullptr, true);
     id_st = id_st_next;
     __syncthreads();
 
@@ -417,9 +434,18 @@ __global__ __launch_bounds__(512, 1) void attn_prefill_kernel(AttnArgs a)
             int nd = load_i32_async(id_addr(i + 3, row_dma()));
             int nv = load_i32_async(id_addr(i + 2, row_st()));
             TSTAMP(1);
-            consume(i, &gc);
-            TSTAMP(2);
-            produce(i + 1, id_st, &gc);
+            // the two waves of a SIMD take the two halves in opposite order, so that one's MFMAs run under
+            // the other's softmax arithmetic
+            if (w < 4) {
+                consume(i, &gc);
+                TSTAMP(2);
+                produce(i + 1, id_st, &gc, true);
+            } else {
+                produce(i + 1, id_st, &gc, false);
+                TSTAMP(2);
+                consume(i, &gc);
+                vfetch(i + 1);
+            }
             TSTAMP(3);
             wait_vm(nd, nv);
             TSTAMP(4);
@@ -455,7 +481,7 @@ __global__ __launch_bounds__(512, 1) void attn_prefill_kernel(AttnArgs a)
         reset_acc();
         wait_vm(nd, nv);
         __syncthreads();
-        produce(0, id_st, nullptr);
+        produce(0, id_st, nullptr, true);
         id_dma = nd;
         id_st = nv;
         __syncthreads();

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libindexcache.so")
-SOURCES = ["ic_api.hip", "ic_indexer_score.hip", "ic_topk_select.hip", "ic_sparse_attn.hip", "ic_attn_prefill.hip",
+SOURCES = ["ic_api.hip", "ic_indexer_score.hip", "ic_topk_select.hip", "ic_sparse_attn.hip",
            "ic_overlap.hip", "ic_similarity.hip", "ic_distill.hip", "ic_calibrate.hip"]
 HEADERS = [os.path.join(CSRC, "ic_common.hpp"), os.path.join(ROOT, "include", "indexcache.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

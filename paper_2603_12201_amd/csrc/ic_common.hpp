@@ -121,8 +121,6 @@ hipError_t launch_select(const SelectArgs &a, int n_rows, int max_row_len, hipSt
 int select_cache_limit();
 hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st);
 hipError_t launch_attn_merge(const AttnArgs &a, int d_v, hipStream_t st);
-bool attn_prefill_supported(const AttnArgs &a, int d_qk, int d_v);
-hipError_t launch_attn_prefill(const AttnArgs &a, hipStream_t st);
 size_t overlap_ws_bytes(int n_layers);
 size_t overlap_lds_bytes(int n_layers, int Lk);
 hipError_t launch_overlap(const int32_t *const *idx_layers, int n_layers, int64_t nq, int k_sel, int Lk, double *overlap,

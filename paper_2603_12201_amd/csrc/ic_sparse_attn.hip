@@ -25,7 +25,6 @@
 // row sum.
 #include "ic_common.hpp"
 #include <type_traits>
-#include <cstdlib>
 
 namespace ic {
 
@@ -961,9 +960,6 @@ bool attn_shape_supported(int d_qk, int d_v)
 hipError_t launch_attn(const AttnArgs &a, int d_qk, int d_v, hipStream_t st)
 {
     if ((int64_t)a.B * a.Tq <= 0) return hipSuccess;
-    // whole selections of three or more tiles out of a dense cache: the eight-wave prefill form
-    static const bool wide_form = getenv("IC_ATTN_EIGHT_WAVES") != nullptr;   // experimental form, off by default (slower so far)
-    if (wide_form && attn_prefill_supported(a, d_qk, d_v)) return launch_attn_prefill(a, st);
     if (d_qk == 576 && d_v == 512) {
         // the row-slab form: one workgroup per query, or per split of a query's selection when
         // there are too few queries to fill the chip (decode); rows with the values elsewhere than

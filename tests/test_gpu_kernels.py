@@ -340,7 +340,7 @@ ATTN_CASES = [
     (2, 300, 400, 20, 576, 512, 0, 576, 130, 150, True),  # ragged heads
     (1, 520, 520, 32, 576, 512, 0, 640, 64, 0, False),    # padded KV rows, one tile, short causal rows
     (1, 512, 300, 32, 576, 512, 0, 576, 2, 40, False),    # two slots only
-    # whole selections of three or more tiles out of a dense MLA cache: the eight-wave prefill form
+    # whole selections of three or more tiles out of a dense MLA cache (the chained row-slab form)
     (1, 300, 3000, 32, 576, 512, 0, 576, 2048, 2700, False),  # 32 tiles; 44 workgroups walk two queries
     (2, 200, 500, 32, 576, 512, 0, 576, 192, 300, True),      # exactly three tiles, two sequences, holes
     (1, 700, 900, 32, 576, 512, 0, 576, 129, 200, False),     # one slot in the third tile; chains of three queries
