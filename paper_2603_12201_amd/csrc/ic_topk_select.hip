@@ -84,12 +84,7 @@ __device__ __forceinline__ void find_digit(const uint32_t *cnt, uint32_t need, u
         }
         mine += c[j];
     }
-    uint32_t incl = mine;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = __shfl_up(incl, off);
-        if (lane >= off) incl += up;
-    }
+    uint32_t incl = wave_incl_scan(mine);
     if (lane == 63) wsum[wave] = incl;
     __syncthreads();
     uint32_t before = 0;
@@ -113,11 +108,11 @@ __device__ __forceinline__ void find_digit(const uint32_t *cnt, uint32_t need, u
     __syncthreads();
 }
 
+// The radix select of one row (workgroup-wide; smem: kBins1 + 2 NW + 4 + a.cache_elems words).
 template <int NT>
-__global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
+__device__ __forceinline__ void select_row_generic(const SelectArgs &a, uint32_t *smem)
 {
     constexpr int NW = NT / 64;
-    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     uint32_t *hist1 = smem;                    // [kBins1]
     uint32_t *wsum = hist1 + kBins1;           // [2][NW] (scan partials / emit totals, double buffered)
     uint32_t *bc = wsum + 2 * NW;              // [4] broadcast: digit, remaining need
@@ -353,6 +348,248 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
         }
         run_g += chunk_total & 0xFFFFu;
         run_e += chunk_total >> 16;
+    }
+}
+
+template <int NT>
+__global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    select_row_generic<NT>(a, smem);
+}
+
+// ---- candidate form (long rows) ------------------------------------------------------------------
+// For rows much longer than k almost every key is far below the k-th score, and pushing all of them through
+// the digit histograms (LDS atomics into the few dozen bins a row's exponents fall into) is what the generic
+// form spends its time on.  Here the row is read ONCE:
+//   sample    4096 keys in 32 contiguous blocks spread over the row -> 12-bit digit histogram -> a threshold T0
+//             (a bin's lower edge) that about 2k keys of the row should reach
+//   sweep     one pass over the row: keys >= T0 are appended to a candidate list in LDS (one LDS atomic per
+//             wave and sweep step), their maximum is tracked
+//   select    one histogram over the candidates with 4096 LINEAR bins between T0 and that maximum (candidates
+//             spread over all of them), a scan for the bin of the k-th largest, and an exact ranking
+//             (key descending, position ascending) of the few members of that bin
+//   emit      selected positions set bits in a bitmap of the row; a prefix count over the bitmap words gives
+//             every selected candidate its slot, so positions come out ascending with their scores
+// Exact for every input: whenever a step cannot proceed (fewer than k candidates, more than the list holds,
+// too many ties in the boundary bin) the workgroup falls back to the generic radix select on the same row.
+constexpr int kCandCap = 12288;          // candidate list entries (6 k for k = 2048)
+constexpr int kCandMinLen = 16384;       // shorter rows of a launch take the generic form at once
+constexpr int kCandFrom = 65536;         // launches whose longest row exceeds this use the candidate form: below it the
+                                         // generic forms (row cached in LDS or registers, read once as well) are faster
+constexpr int kCandMaxLen = 131072;      // bitmap capacity
+constexpr int kCandSample = 4096;
+constexpr int kBoundaryCap = 1024;       // boundary-bin members ranked exactly
+constexpr int kCandLdsWords = kBins1 + 2 * 16 + 4 + 16 + 2 * kCandCap + 2 * (kCandMaxLen / 32);
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x = max(x, (uint32_t)__shfl_xor((int)x, off));
+    return x;
+}
+
+template <int NT>
+__global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
+{
+    static_assert(NT == 1024 && kCandSample == 4 * NT, "one sample vector and four bitmap words per thread");
+    constexpr int NW = NT / 64;
+    extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
+    uint32_t *hist = smem;                     // [kBins1]  (the generic form's layout starts the same way)
+    uint32_t *wsum = hist + kBins1;            // [2 NW]
+    uint32_t *bc = wsum + 2 * NW;              // [4]
+    uint32_t *misc = bc + 4;                   // [16]: 0 candidate count, 1 largest candidate key, 2 boundary-list count
+    uint32_t *ckey = misc + 16;                // [kCandCap]
+    uint32_t *cpos = ckey + kCandCap;          // [kCandCap]
+    uint32_t *bitmap = cpos + kCandCap;        // [kCandMaxLen / 32]
+    uint32_t *wpre = bitmap + kCandMaxLen / 32;   // [kCandMaxLen / 32] selected entries ahead of each bitmap word;
+                                                  // before that: the boundary bin's members (key, position)
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x;
+    const int b = a.b0 + r / a.Ri;
+    const int i = a.i0 + r % a.Ri;
+    if (i >= a.Tq) return;
+    const int Lk_b = a.seq_lens ? max(0, min(a.seq_lens[b], a.Lk)) : a.Lk;
+    int64_t nv64 = (a.seq_lens ? (int64_t)Lk_b - a.Tq : a.q_pos0) + (int64_t)i + 1;
+    nv64 = nv64 < 0 ? 0 : (nv64 > Lk_b ? Lk_b : nv64);
+    const int nv = (int)nv64;
+    auto generic = [&]() {
+        SelectArgs ga = a;
+        ga.cache_elems = 32768;                // the candidate arrays' space serves as the row cache
+        select_row_generic<NT>(ga, smem);
+    };
+    if (nv < kCandMinLen || nv < 4 * a.k_sel) {  // workgroup-uniform
+        generic();
+        return;
+    }
+    const float *row = a.strip + (int64_t)r * a.ld;
+    int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
+    float *osel = a.sel ? a.sel + ((int64_t)b * a.Tq + i) * a.k_sel : nullptr;
+    const uint32_t k = (uint32_t)a.k_sel;
+
+    // The row arrives in groups of kGroup vectors per thread, two groups in flight: a single workgroup has to
+    // cover the whole memory latency by itself.  The first group is requested before the sample is looked at.
+    constexpr int kGroup = 4;
+    const int nsteps = (nv + 4 * NT - 1) / (4 * NT);
+    auto load_group = [&](int c0, f32x4 (&dst)[kGroup]) {
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            const int p = ((c0 + j) * NT + tid) * 4;
+            dst[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (p < nv) dst[j] = *(const f32x4 *)(row + p);   // may run past nv inside the row's padding; masked below
+        }
+    };
+    f32x4 ga[kGroup], gb[kGroup];
+    load_group(0, ga);
+
+    // ---- sample: 32 blocks of 128 keys ----
+    for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bitmap[4 * tid + q] = 0;
+    if (tid < 16) misc[tid] = 0;
+    __syncthreads();
+    {
+        const int blk = tid >> 5;
+        const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 512 apart
+        const f32x4 v = *(const f32x4 *)(row + p);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) atomicAdd(&hist[score_key(v[e]) >> 20], 1u);
+    }
+    __syncthreads();
+    uint32_t want = (uint32_t)(((int64_t)kCandSample * 2 * k) / nv) + 32u;
+    want = want > (uint32_t)kCandSample ? (uint32_t)kCandSample : want;
+    find_digit<NT, kBins1 / NT>(hist, want, wsum, bc, tid, lane, wave);
+    const uint32_t T0 = bc[0] << 20;
+    __syncthreads();
+
+    // ---- sweep: the row once, candidates to LDS ----
+    {
+        uint32_t tmax = 0;
+        auto sweep_group = [&](int c0, const f32x4 (&v)[kGroup]) {
+            uint32_t n_t = 0;
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j) {
+                const int p = ((c0 + j) * NT + tid) * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) n_t += (p + e < nv && score_key(v[j][e]) >= T0) ? 1u : 0u;
+            }
+            const uint32_t incl = wave_incl_scan(n_t);
+            const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+            if (total == 0u) return;               // wave-uniform
+            uint32_t base = 0;
+            if (lane == 63) base = atomicAdd(&misc[0], total);
+            base = (uint32_t)__builtin_amdgcn_readlane((int)base, 63);
+            uint32_t off = base + incl - n_t;
+            if (n_t == 0u) return;
+#pragma unroll
+            for (int j = 0; j < kGroup; ++j) {
+                const int p = ((c0 + j) * NT + tid) * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t key = score_key(v[j][e]);
+                    if (p + e < nv && key >= T0) {
+                        if (off < (uint32_t)kCandCap) {
+                            ckey[off] = key;
+                            cpos[off] = (uint32_t)(p + e);
+                        }
+                        ++off;
+                        tmax = max(tmax, key);
+                    }
+                }
+            }
+        };
+#pragma unroll 1
+        for (int c0 = 0; c0 < nsteps; c0 += 2 * kGroup) {
+            if (c0 + kGroup < nsteps) load_group(c0 + kGroup, gb);
+            sweep_group(c0, ga);
+            if (c0 + kGroup >= nsteps) break;
+            if (c0 + 2 * kGroup < nsteps) load_group(c0 + 2 * kGroup, ga);
+            sweep_group(c0 + kGroup, gb);
+        }
+        tmax = wave_max_u32(tmax);
+        if (lane == 0 && tmax != 0u) atomicMax(&misc[1], tmax);
+    }
+    __syncthreads();
+    const uint32_t n_cand = misc[0], kmax = misc[1];
+    if (n_cand < k || n_cand > (uint32_t)kCandCap) {   // workgroup-uniform
+        __syncthreads();
+        generic();
+        return;
+    }
+
+    // ---- one histogram over the candidates: 4096 linear bins over [T0, kmax] ----
+    for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
+    __syncthreads();
+    const uint32_t range = kmax - T0;
+    const int nbits = range ? 32 - __clz((int)range) : 0;
+    const int sh = nbits > 12 ? nbits - 12 : 0;
+    for (uint32_t j = tid; j < n_cand; j += NT) atomicAdd(&hist[(ckey[j] - T0) >> sh], 1u);
+    __syncthreads();
+    find_digit<NT, kBins1 / NT>(hist, k, wsum, bc, tid, lane, wave);
+    const uint32_t bstar = bc[0], need = bc[1], n_b = bc[2];
+    __syncthreads();
+    const bool ranked = need < n_b;            // the boundary bin is cut: rank its members exactly
+    if (ranked && n_b > (uint32_t)kBoundaryCap) {
+        generic();
+        return;
+    }
+
+    // ---- mark the selected positions ----
+    uint32_t *bl_key = wpre, *bl_pos = wpre + kBoundaryCap;
+    for (uint32_t j = tid; j < n_cand; j += NT) {
+        const uint32_t bin = (ckey[j] - T0) >> sh;
+        if (bin > bstar || (bin == bstar && !ranked)) {
+            atomicOr(&bitmap[cpos[j] >> 5], 1u << (cpos[j] & 31u));
+        } else if (bin == bstar) {
+            const uint32_t s = atomicAdd(&misc[2], 1u);
+            bl_key[s] = ckey[j];
+            bl_pos[s] = cpos[j];
+        }
+    }
+    __syncthreads();
+    if (ranked) {
+        for (uint32_t m = tid; m < n_b; m += NT) {
+            const uint32_t km = bl_key[m], pm = bl_pos[m];
+            uint32_t ahead = 0;                // members that beat this one: larger key, or equal key at a lower position
+            for (uint32_t x = 0; x < n_b; ++x) ahead += (bl_key[x] > km || (bl_key[x] == km && bl_pos[x] < pm)) ? 1u : 0u;
+            if (ahead < need) atomicOr(&bitmap[pm >> 5], 1u << (pm & 31u));
+        }
+        __syncthreads();
+    }
+
+    // ---- slots: selected entries ahead of every bitmap word ----
+    {
+        uint32_t wcnt[4], mine = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            wcnt[q] = (uint32_t)__popc(bitmap[4 * tid + q]);
+            mine += wcnt[q];
+        }
+        const uint32_t incl = wave_incl_scan(mine);
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();                       // also: every read of the boundary list is over, wpre may be overwritten
+        uint32_t before = 0;
+#pragma unroll
+        for (int wv = 0; wv < NW; ++wv)
+            if (wv < wave) before += wsum[wv];
+        uint32_t run = before + incl - mine;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            wpre[4 * tid + q] = run;
+            run += wcnt[q];
+        }
+    }
+    __syncthreads();
+    for (uint32_t j = tid; j < n_cand; j += NT) {
+        const uint32_t pos = cpos[j], word = bitmap[pos >> 5], bit = pos & 31u;
+        if ((word >> bit) & 1u) {
+            const uint32_t slot = wpre[pos >> 5] + (uint32_t)__popc(word & ((1u << bit) - 1u));
+            if (slot < k) {                    // always true for a consistent select
+                oidx[slot] = (int32_t)pos;
+                if (osel) osel[slot] = key_score(ckey[j]);
+            }
+        }
     }
 }
 
@@ -618,6 +855,15 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     if (attr256 != hipSuccess) return attr256;
     if (attr1024 != hipSuccess) return attr1024;
     if (attr_reg != hipSuccess) return attr_reg;
+    static hipError_t attr_cand = hipFuncSetAttribute((const void *)select_cand_kernel<1024>,
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, kCandLdsWords * (int)sizeof(uint32_t));
+    if (attr_cand != hipSuccess) return attr_cand;
+    if (max_row_len > kCandFrom && max_row_len <= kCandMaxLen && max_row_len >= 4 * a.k_sel) {
+        // rows too long for LDS or registers: one read of the row, a sampled threshold and a candidate list
+        // (falls back row by row), where the generic form would stream the row three or four times
+        hipLaunchKernelGGL((select_cand_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), kCandLdsWords * sizeof(uint32_t), st, a);
+        return hipGetLastError();
+    }
     if (max_row_len <= 8192)
         hipLaunchKernelGGL((select_kernel<256>), dim3((unsigned)n_rows), dim3(256), lds, st, a);
     else if (max_row_len <= select_cache_limit())

@@ -179,6 +179,7 @@ TOPK_CASES = [
     (1, 33, 9000, 32, 128, 8967, 2048),  # long rows: 1024-thread select, LDS-cached row
     (1, 40, 300, 64, 128, 260, 1),       # k = 1: argmax
     (2, 2, 40000, 32, 128, 39998, 512),  # rows past the LDS cache: read once, selected in registers
+    (1, 3, 100000, 32, 128, 99997, 2048),  # rows past 65536 keys: sampled threshold + candidate list, one read of the row
 ]
 
 
@@ -238,6 +239,32 @@ def test_topk_ties_cut_at_the_boundary_on_long_rows(ic, oracle, Lk):
         # by hand: all 7s come first in position order; there are more of them than k
         want = np.nonzero(vals[:nv] == 7)[0][:ks]
         assert want.size == ks and np.array_equal(idx[0, i], want)
+
+
+def test_topk_candidate_form_with_ties_at_the_boundary(ic, oracle):
+    # rows past 65536 keys (candidate form): two one-hot heads with weights 1 and 1/256 and integer key
+    # coordinates below 256 give 65536 exactly representable score levels for 100000 keys, so small tie
+    # classes sit everywhere, the boundary included: the exact ranking of the boundary bin decides
+    say("topk candidate form, ties at the boundary")
+    B, Tq, Lk, H, d, ks = 1, 4, 100000, 2, 64, 2048
+    g = torch.Generator().manual_seed(99)
+    q = torch.zeros((B, Tq, H, d)); q[:, :, 0, 3] = 1.0; q[:, :, 1, 5] = 1.0
+    k = torch.zeros((B, Lk, d))
+    k[0, :, 3] = torch.randint(0, 256, (Lk,), generator=g).float()
+    k[0, :, 5] = torch.randint(0, 256, (Lk,), generator=g).float()
+    w = torch.zeros((B, Tq, H)); w[..., 0] = 1.0; w[..., 1] = 1.0 / 256.0
+    p0 = Lk - Tq
+    idx, sel = ic.indexer_topk(q.bfloat16().cuda(), k.bfloat16().cuda(), w.cuda(), ks, p0, want_scores=True)
+    idx, sel = idx.cpu().numpy(), sel.cpu().numpy()
+    sc = oracle.indexer_scores(synth.bits(q.bfloat16()), synth.bits(k.bfloat16()), synth.bits(w), p0)
+    kinds = {}
+    for i in range(Tq):
+        kind = parity.check_idx_row(idx[0, i], sc[0, i], p0 + i + 1, ks, oracle)
+        kinds[kind] = kinds.get(kind, 0) + 1
+        assert np.array_equal(sel[0, i].astype(np.float64), sc[0, i][idx[0, i]])       # exact scores on both sides
+        r = oracle.topk_row(sc[0, i], p0 + i + 1, ks)
+        assert np.array_equal(idx[0, i], np.sort(r["idx"]))                            # the oracle's set, ties and all
+    say("row kinds: %s" % kinds)
 
 
 @pytest.mark.parametrize("Lk", [70000, 140000])
