@@ -362,8 +362,8 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
 // For rows much longer than k almost every key is far below the k-th score, and pushing all of them through
 // the digit histograms (LDS atomics into the few dozen bins a row's exponents fall into) is what the generic
 // form spends its time on.  Here the row is read ONCE:
-//   sample    4096 keys in 32 contiguous blocks spread over the row -> 12-bit digit histogram -> a threshold T0
-//             (a bin's lower edge) that about 2k keys of the row should reach
+//   sample    4096 keys in 32 contiguous blocks spread over the row -> 12-bit digit histogram (refined by the next
+//             twelve bits inside the boundary bin) -> a threshold T0 that about 2k keys of the row should reach
 //   sweep     one pass over the row: keys >= T0 are appended to a candidate list in LDS (one LDS atomic per
 //             wave and sweep step), their maximum is tracked
 //   select    one histogram over the candidates with 4096 LINEAR bins between T0 and that maximum (candidates
@@ -449,19 +449,38 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     for (int q = 0; q < 4; ++q) bitmap[4 * tid + q] = 0;
     if (tid < 16) misc[tid] = 0;
     __syncthreads();
+    uint32_t skey[4];                          // this thread's four sampled keys
     {
         const int blk = tid >> 5;
         const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 512 apart
         const f32x4 v = *(const f32x4 *)(row + p);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) atomicAdd(&hist[score_key(v[e]) >> 20], 1u);
+        for (int e = 0; e < 4; ++e) {
+            skey[e] = score_key(v[e]);
+            atomicAdd(&hist[skey[e] >> 20], 1u);
+        }
     }
     __syncthreads();
     uint32_t want = (uint32_t)(((int64_t)kCandSample * 2 * k) / nv) + 32u;
     want = want > (uint32_t)kCandSample ? (uint32_t)kCandSample : want;
     find_digit<NT, kBins1 / NT>(hist, want, wsum, bc, tid, lane, wave);
-    const uint32_t T0 = bc[0] << 20;
+    uint32_t T0 = bc[0] << 20;
+    const uint32_t want2 = bc[1], in_bin = bc[2];
     __syncthreads();
+    // The scores of a row share a few exponents, so one bin of the first digit can hold a tenth of the row:
+    // when the bin holds clearly more sampled keys than are wanted from it, the next twelve bits of the
+    // sampled keys inside that bin place the threshold
+    if (in_bin > want2 + 16u) {                // workgroup-uniform
+        for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((skey[e] >> 20) == (T0 >> 20)) atomicAdd(&hist[(skey[e] >> 8) & 4095u], 1u);
+        __syncthreads();
+        find_digit<NT, kBins1 / NT>(hist, want2, wsum, bc, tid, lane, wave);
+        T0 |= bc[0] << 8;
+        __syncthreads();
+    }
 
     // ---- sweep: the row once, candidates to LDS ----
     {
