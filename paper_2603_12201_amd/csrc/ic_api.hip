@@ -74,6 +74,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Default strip budget when the caller asks how much workspace to bring.
 constexpr size_t kStripBudget = (size_t)1 << 30;   // 1 GiB of score rows in flight
+constexpr size_t kSmallStrip = (size_t)64 << 20;    // problems whose whole score matrix is below this keep it in one strip
 constexpr int kMinStripRows = 16;
 
 ic_status check_indexer(const ic_indexer_desc *d)
@@ -300,7 +301,13 @@ size_t ic_indexer_topk_workspace(const ic_indexer_desc *d)
     if (check_indexer(d) != IC_OK) return 0;
     const size_t row_bytes = strip_ld(d) * sizeof(float);
     const size_t all = (size_t)d->B * d->Tq * row_bytes;
-    size_t want = all < kStripBudget ? all : kStripBudget;
+    // small problems keep every row in flight; larger ones at most a quarter of their rows and at most the budget,
+    // so that the scores of a long sequence are never all resident at once
+    size_t want = all;
+    if (all > kSmallStrip) {
+        want = all / 4 > kSmallStrip ? all / 4 : kSmallStrip;
+        if (want > kStripBudget) want = kStripBudget;
+    }
     const size_t min_b = indexer_min_ws(d);
     if (want < min_b) want = min_b;
     return align_up(want / row_bytes * row_bytes);
