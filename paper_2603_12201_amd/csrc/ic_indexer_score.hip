@@ -453,6 +453,228 @@ __global__ void fill_kernel(float *p, int64_t n, float v)
     for (; i < n; i += stride) p[i] = v;
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Few query rows, bf16, d_I = 128 (decode): the kernel is a stream over the index-key cache, so what matters is
+// how the keys travel and in which order the chip walks the cache.
+// Travel.  Every wave owns a ring of R slots in LDS (one slot = 32 rows of 256 B = 8 KB) that it fills with loads
+// that write LDS directly: 64 lanes x 16 bytes = 1 KB = four whole rows per instruction, no registers, no LDS
+// stores, and -- the ring being private to the wave -- no barrier: the wave waits for its own oldest slot with the
+// vector-memory counter (loads return in order) and multiplies it while R - 1 slots are in flight.  A lane
+// fetches the 16-byte piece (lane & 15) ^ (row & 15) of its row, so that the operand reads (one row per lane, the
+// same piece for all lanes) spread over all banks.  The q rows of a token (32 heads x 256 B = one slot per head
+// tile) travel through the same ring as items of their own, ahead of the token's keys.
+// Order.  Reading the cache as a few wide windows that slide is faster than many narrow streams (measured: 32
+// concurrent per-token windows 100 us, 8 windows 90 us, one window 87 us for 537 MB).  So the G = 8 tokens in
+// flight each belong to the workgroups of one residue mod 8 (one XCD: workgroup ids are dealt round-robin over
+// the eight XCDs); all waves of those workgroups interleave slot by slot over the token's keys, then move to the
+// token G further on together.
+// ---------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void dma_lanes(const void *lane_addr, unsigned lds_addr /*uniform*/)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(lane_addr), "s"(lds_addr) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vm_le()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Small read-only operands (head weights, lengths, page table) are read through the constant address space: with a
+// uniform address that is a scalar load, which does not enter the vector-memory queue the ring's waits count on.
+// (An ordinary load inside the loop would make the compiler wait for "all its loads", i.e. drain the ring.)
+template <typename T> __device__ __forceinline__ T load_uniform(const T *p)
+{
+    return *(const __attribute__((address_space(4))) T *)(uintptr_t)p;
+}
+
+template <int HT, int NW, int R, bool PG>
+__global__ __launch_bounds__(64 * NW, 1) void score_stream_kernel(ScoreArgs a, int T, int G)
+{
+    constexpr int RB = 256;                     // bytes per key row (and per q row)
+    constexpr int SUB = 32;                     // rows per slot
+    constexpr int SLOT = SUB * RB;              // 8 KB
+    constexpr int NI = SLOT / 1024;             // loads per slot
+    constexpr int KS = 8;                       // MFMA steps over d_I = 128
+    static_assert(R >= 2 && NI * (R - 1) < 64, "the vector-memory counter holds 63");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char ring[];   // [NW][R][SLOT]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r32 = lane & 31, half = lane >> 5;
+    const int wdw = (int)blockIdx.x % G;                    // this workgroup's tokens: wdw, wdw + G, ...
+    const int wstride = NW * ((int)gridDim.x / G);          // waves that share a token
+    const int wfirst = ((int)blockIdx.x / G) * NW + wave;   // this wave's slots of a token: wfirst, wfirst + wstride, ...
+    const bool ragged = PG && a.pv.seq_lens, paged = PG && a.pv.page_table;
+    const int i_end = min(a.i0 + a.Ri, a.Tq);
+
+    // A cursor walks the wave's items: per token HT q items (jj = -HT .. -1), then its key slots (jj = 0 .. n_w - 1).
+    // Two cursors run over the same sequence: the one that issues loads stays R - 1 items ahead of the one that
+    // computes.
+    struct Cur {
+        int tk, jj, n_w;
+        int bz, t, Lk_b, vis;                   // sequence within the launch, query row, visible keys
+    };
+    auto enter = [&](Cur &c) {                  // first item of token c.tk or of the next token that has work
+        for (; c.tk < T; c.tk += G) {
+            c.bz = c.tk / a.Ri;
+            c.t = a.i0 + c.tk % a.Ri;
+            if (c.t >= i_end) continue;
+            const int b = a.b0 + c.bz;
+            c.Lk_b = ragged ? max(0, min(load_uniform(a.pv.seq_lens + b), a.Lk)) : a.Lk;
+            const int64_t q_pos0 = ragged ? (int64_t)c.Lk_b - a.Tq : a.q_pos0;
+            int64_t vis64 = q_pos0 + (int64_t)c.t + 1;
+            vis64 = vis64 < 0 ? 0 : (vis64 > c.Lk_b ? c.Lk_b : vis64);
+            c.vis = (int)vis64;
+            const int nsub = (c.vis + SUB - 1) / SUB;
+            c.n_w = nsub > wfirst ? (nsub - wfirst + wstride - 1) / wstride : 0;
+            if (c.n_w > 0) {
+                c.jj = -HT;
+                return;
+            }
+        }
+    };
+    auto next = [&](Cur &c) {
+        if (++c.jj >= c.n_w) {
+            c.tk += G;
+            enter(c);
+        }
+    };
+
+    const unsigned ring_w = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)ring + (unsigned)wave * (R * SLOT);
+    // rows a lane fetches within a slot: 4 i + (lane >> 4), i = 0..7; its piece of the row (lane & 15) ^ (row & 15)
+    const int lrow = lane >> 4, lpiece = lane & 15;
+    auto issue = [&](const Cur &c, int slot_i) {
+        const int b = a.b0 + c.bz;
+        const unsigned char *base;
+        int last;                               // rows past this one re-read it (their results are masked or weigh 0)
+        if (c.jj < 0) {
+            const int h0 = (c.jj + HT) * 32;    // head tile
+            base = (const unsigned char *)a.q + (((int64_t)b * a.Tq + c.t) * a.H_I + min(h0, a.H_I - 1)) * RB;
+            last = max(a.H_I - 1 - h0, 0);
+        } else {
+            const int s0 = (wfirst + c.jj * wstride) * SUB;             // < vis <= Lk_b
+            int64_t krow = (int64_t)b * a.Lk + s0;
+            if (paged) {                        // a slot never straddles a page: pages hold a multiple of 64 positions
+                const int32_t page = load_uniform(a.pv.page_table + (int64_t)b * a.pv.max_pages + (s0 >> a.pv.page_shift));
+                krow = ((int64_t)page << a.pv.page_shift) + (s0 & ((1 << a.pv.page_shift) - 1));
+            }
+            base = (const unsigned char *)a.k + krow * RB;
+            last = c.Lk_b - 1 - s0;
+        }
+        const unsigned slot = ring_w + (unsigned)slot_i * SLOT;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int row = 4 * i + lrow;
+            const int off = min(row, last) * RB + ((lpiece ^ (row & 15)) << 4);
+            dma_lanes(base + off, slot + i * 1024);
+        }
+    };
+
+    Cur pc, cc;                                 // producer, consumer
+    pc.tk = wdw;
+    enter(pc);
+    if (pc.tk >= T) return;                     // nothing for this wave (no barrier in this kernel)
+    cc = pc;
+    int p_slot = 0, c_slot = 0;
+#pragma unroll
+    for (int d = 0; d < R - 1; ++d)
+        if (pc.tk < T) {
+            issue(pc, p_slot);
+            p_slot = p_slot + 1 == R ? 0 : p_slot + 1;
+            next(pc);
+        }
+
+    bf16x8 qa[HT][KS];
+    float wr[HT][16];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qa[ht][ks] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+#pragma unroll
+        for (int i = 0; i < 16; ++i) wr[ht][i] = 0.f;
+    }
+    const unsigned char *my = ring + wave * (R * SLOT) + r32 * RB;       // this lane's row within a slot
+
+    while (cc.tk < T) {
+        if (pc.tk < T) {
+            issue(pc, p_slot);                                           // the slot consumed in the previous iteration
+            p_slot = p_slot + 1 == R ? 0 : p_slot + 1;
+            next(pc);
+            wait_vm_le<NI * (R - 1)>();                                  // the consumer's slot has landed
+        } else {
+            wait_vm_le<0>();
+        }
+        const unsigned char *sp = my + c_slot * SLOT;
+        c_slot = c_slot + 1 == R ? 0 : c_slot + 1;
+        bf16x8 kb[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            kb[ks] = *(const bf16x8 *)(sp + (((ks * 2 + half) ^ (r32 & 15)) << 4));
+        if (cc.jj < 0) {
+            // a q item: the token's rows of one head tile become the stationary operand; its head weights follow
+            // (uniform addresses: scalar loads)
+            const int ht_in = cc.jj + HT;
+            const float *wrow = a.w + ((int64_t)(a.b0 + cc.bz) * a.Tq + cc.t) * a.H_I;
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) {
+                if (ht != ht_in) continue;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) qa[ht][ks] = kb[ks];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int h_lo = ht * 32 + 8 * (i / 4) + (i % 4), h_hi = h_lo + 4;
+                    const float w_lo = h_lo < a.H_I ? load_uniform(wrow + h_lo) : 0.f;
+                    const float w_hi = h_hi < a.H_I ? load_uniform(wrow + h_hi) : 0.f;
+                    wr[ht][i] = half ? w_hi : w_lo;
+                }
+            }
+            asm volatile("" ::: "memory");
+            next(cc);
+            continue;
+        }
+        float s_acc = 0.f;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) {
+            f32x16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[ht][ks], kb[ks], acc, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                s_acc = fmaf(relu(acc[i]), wr[ht][i], s_acc);
+        }
+        // the reads of this slot have returned (the MFMAs consumed them) before the next iteration's loads
+        // overwrite it; the statement below keeps the compiler from moving them
+        asm volatile("" ::: "memory");
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(s_acc), __float_as_uint(s_acc), false, false);
+        const float v = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+        const int s = (wfirst + cc.jj * wstride) * SUB + r32;
+        if (half == 0 && s < cc.vis) a.strip[((int64_t)cc.bz * a.Ri + (cc.t - a.i0)) * a.ld + s] = v;
+        next(cc);
+    }
+}
+
+template <int HT, int NW, int R>
+hipError_t launch_stream(const ScoreArgs &a, int Bc, hipStream_t st)
+{
+    const int T = Bc * a.Ri;                    // tokens of the launch
+    if (T <= 0) return hipSuccess;
+    const int G = T < 8 ? T : 8;                // tokens in flight
+    const int W = G * (256 / G);                // one workgroup per CU (the ring takes most of a CU's LDS)
+    constexpr int lds = NW * R * 32 * 256;
+    static hipError_t attr = hipFuncSetAttribute((const void *)score_stream_kernel<HT, NW, R, false>,
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    static hipError_t attr_pg = hipFuncSetAttribute((const void *)score_stream_kernel<HT, NW, R, true>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    if (attr_pg != hipSuccess) return attr_pg;
+    if (a.pv.seq_lens || a.pv.page_table)
+        hipLaunchKernelGGL((score_stream_kernel<HT, NW, R, true>), dim3(W), dim3(64 * NW), lds, st, a, T, G);
+    else
+        hipLaunchKernelGGL((score_stream_kernel<HT, NW, R, false>), dim3(W), dim3(64 * NW), lds, st, a, T, G);
+    return hipGetLastError();
+}
+
 template <int HT, int DI, int TPW, int NW, int PD, int MINB, bool STREAM, bool FP8>
 hipError_t launch_t(const ScoreArgs &a, int Bc, int64_t max_vis, hipStream_t st)
 {
@@ -479,8 +701,9 @@ bool score_shape_supported(int dtype, int H_I, int d_I)
 hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipStream_t st)
 {
     ScoreArgs a = a_in;
-    // Few query rows per sequence (decode, short chunks): one token per workgroup, three workgroups
-    // per CU and three key tiles in flight per workgroup, because the kernel then only streams keys.
+    // Few query rows per sequence (decode, short chunks): the kernel only streams keys.  bf16 keys of 128
+    // take the ring form (score_stream_kernel); the other formats one token per workgroup, three workgroups
+    // per CU and three key tiles in flight per workgroup.
     // Otherwise 3 tokens per wave (2 for 64 heads) and the matrix pipe is the limit.
     const bool few_rows = a.Ri <= 4;
     const int BT = few_rows ? 1 : (a.H_I <= 32 ? 12 : 8);   // 4 waves x tokens per wave of the chosen form
@@ -497,12 +720,14 @@ hipError_t launch_score(const ScoreArgs &a_in, int dtype, int d_I, int Bc, hipSt
     kc = kc < 512 ? 512 : (kc > 8192 ? 8192 : kc);
     a.KC = (int)kc;
     const bool fp8 = dtype == IC_FP8_E4M3;
+    if (few_rows && !fp8 && d_I == 128)
+        return a.H_I <= 32 ? launch_stream<1, 4, 4>(a, Bc, st) : launch_stream<2, 4, 4>(a, Bc, st);
     if (!fp8) {
         if (a.H_I <= 32) {
-            if (d_I == 128) return few_rows ? launch_t<1, 128, 1, 4, 3, 3, true, false>(a, Bc, max_vis, st) : launch_t<1, 128, 3, 4, 1, 2, false, false>(a, Bc, max_vis, st);
+            if (d_I == 128) return launch_t<1, 128, 3, 4, 1, 2, false, false>(a, Bc, max_vis, st);
             if (d_I == 64) return few_rows ? launch_t<1, 64, 1, 4, 3, 3, true, false>(a, Bc, max_vis, st) : launch_t<1, 64, 3, 4, 1, 2, false, false>(a, Bc, max_vis, st);
         } else {
-            if (d_I == 128) return few_rows ? launch_t<2, 128, 1, 4, 3, 2, true, false>(a, Bc, max_vis, st) : launch_t<2, 128, 2, 4, 1, 1, false, false>(a, Bc, max_vis, st);
+            if (d_I == 128) return launch_t<2, 128, 2, 4, 1, 1, false, false>(a, Bc, max_vis, st);
             if (d_I == 64) return few_rows ? launch_t<2, 64, 1, 4, 3, 2, true, false>(a, Bc, max_vis, st) : launch_t<2, 64, 2, 4, 1, 1, false, false>(a, Bc, max_vis, st);
         }
     } else {

@@ -67,6 +67,32 @@ def test_indexer_scores(ic, oracle, case):
     parity.check_scores(got.cpu().numpy(), want)
 
 
+# Few query rows per sequence (decode): the ring form of the score kernel -- several slots per wave, more tokens
+# than are in flight at once, two head tiles, a head count that leaves part of a head tile empty, rows that see
+# only part of the cache, caches shorter than one slot.
+FEW_ROW_CASES = [
+    # B, Tq, Lk, H, d, q_pos0, signed
+    (3, 1, 5000, 32, 128, 4999, True),
+    (2, 4, 3000, 64, 128, 2996, True),
+    (11, 2, 700, 17, 128, 698, False),
+    (1, 3, 100, 32, 128, 50, False),
+    (9, 1, 40000, 32, 128, 39999, True),
+    (20, 1, 31, 32, 128, 30, False),
+    (5, 2, 2049, 40, 128, 2047, True),
+]
+
+
+@pytest.mark.parametrize("case", FEW_ROW_CASES)
+def test_indexer_scores_few_rows(ic, oracle, case):
+    B, Tq, Lk, H, d, p0, signed = case
+    say("scores few rows B=%d Tq=%d Lk=%d H=%d d=%d q_pos0=%d signed=%s" % case)
+    q, k, w = _mk_indexer(300 + B + Lk, B, Tq, Lk, H, d, signed)
+    got = ic.debug_indexer_scores(q.cuda(), k.cuda(), w.cuda(), p0, 0, Tq)
+    torch.cuda.synchronize()
+    want = oracle.indexer_scores(synth.bits(q), synth.bits(k), synth.bits(w), p0)
+    parity.check_scores(got.cpu().numpy(), want)
+
+
 def _sweep_cases(n, seed):
     """Seeded random shapes around the tile (64 keys) and block (8 / 12 tokens) boundaries of the score kernel."""
     rng = np.random.default_rng(seed)
