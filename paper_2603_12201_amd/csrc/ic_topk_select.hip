@@ -414,15 +414,11 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     int64_t nv64 = (a.seq_lens ? (int64_t)Lk_b - a.Tq : a.q_pos0) + (int64_t)i + 1;
     nv64 = nv64 < 0 ? 0 : (nv64 > Lk_b ? Lk_b : nv64);
     const int nv = (int)nv64;
-    auto generic = [&]() {
-        SelectArgs ga = a;
-        ga.cache_elems = 32768;                // the candidate arrays' space serves as the row cache
-        select_row_generic<NT>(ga, smem);
-    };
-    if (nv < kCandMinLen || nv < 4 * a.k_sel) {  // workgroup-uniform
-        generic();
-        return;
-    }
+    // The candidate form proper; false = this row takes the generic form (one call site below: a fallback reached
+    // through several calls is not inlined, and a kernel argument captured by a real function is copied to scratch
+    // memory by every thread of every row).
+    auto candidate_form = [&]() -> bool {
+    if (nv < kCandMinLen || nv < 4 * a.k_sel) return false;   // workgroup-uniform
     const float *row = a.strip + (int64_t)r * a.ld;
     int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
     float *osel = a.sel ? a.sel + ((int64_t)b * a.Tq + i) * a.k_sel : nullptr;
@@ -533,8 +529,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     const uint32_t n_cand = misc[0], kmax = misc[1];
     if (n_cand < k || n_cand > (uint32_t)kCandCap) {   // workgroup-uniform
         __syncthreads();
-        generic();
-        return;
+        return false;
     }
 
     // ---- one histogram over the candidates: 4096 linear bins over [T0, kmax] ----
@@ -549,10 +544,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     const uint32_t bstar = bc[0], need = bc[1], n_b = bc[2];
     __syncthreads();
     const bool ranked = need < n_b;            // the boundary bin is cut: rank its members exactly
-    if (ranked && n_b > (uint32_t)kBoundaryCap) {
-        generic();
-        return;
-    }
+    if (ranked && n_b > (uint32_t)kBoundaryCap) return false;
 
     // ---- mark the selected positions ----
     uint32_t *bl_key = wpre, *bl_pos = wpre + kBoundaryCap;
@@ -609,6 +601,13 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
                 if (osel) osel[slot] = key_score(ckey[j]);
             }
         }
+    }
+    return true;
+    };
+    if (!candidate_form()) {
+        SelectArgs ga = a;
+        ga.cache_elems = 32768;                // the candidate arrays' space serves as the row cache
+        select_row_generic<NT>(ga, smem);
     }
 }
 
