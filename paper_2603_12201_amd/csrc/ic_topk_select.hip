@@ -375,8 +375,9 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
 // too many ties in the boundary bin) the workgroup falls back to the generic radix select on the same row.
 constexpr int kCandCap = 12288;          // candidate list entries (6 k for k = 2048)
 constexpr int kCandMinLen = 16384;       // shorter rows of a launch take the generic form at once
-constexpr int kCandFrom = 65536;         // launches whose longest row exceeds this use the candidate form: below it the
-                                         // generic forms (row cached in LDS or registers, read once as well) are faster
+constexpr int kCandFrom = 16384;         // launches whose longest row exceeds this use the candidate form (measured:
+                                         // from 8192 it is slower than the LDS-cached generic form, from 16384 faster
+                                         // than both the LDS-cached and the register-resident one)
 constexpr int kCandMaxLen = 131072;      // bitmap capacity
 constexpr int kCandSample = 4096;
 constexpr int kBoundaryCap = 1024;       // boundary-bin members ranked exactly
@@ -877,8 +878,7 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kCandLdsWords * (int)sizeof(uint32_t));
     if (attr_cand != hipSuccess) return attr_cand;
     if (max_row_len > kCandFrom && max_row_len <= kCandMaxLen && max_row_len >= 4 * a.k_sel) {
-        // rows too long for LDS or registers: one read of the row, a sampled threshold and a candidate list
-        // (falls back row by row), where the generic form would stream the row three or four times
+        // one read of the row, a sampled threshold and a candidate list (falls back row by row)
         hipLaunchKernelGGL((select_cand_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), kCandLdsWords * sizeof(uint32_t), st, a);
         return hipGetLastError();
     }
