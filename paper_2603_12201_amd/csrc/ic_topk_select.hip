@@ -17,9 +17,9 @@
 //            wave scan per word on the DPP path, one scan over the (sweep, wave) cells, two
 //            barriers in all.  When ties are cut at the boundary: per-sweep scans of packed
 //            greater / equal counts.
-// Three forms by row length: keys cached in LDS (<= 32768), keys in registers (<= 65536, the
-// decode shape, with the first-digit histogram spread over 8 counters per bin), and a streaming
-// form that re-reads the row on every sweep (longer rows).
+// Forms by row length: the radix select with the keys cached in LDS (rows up to 16384 keys; up to 32768 when k
+// exceeds a quarter of the row), the candidate form further down (16385 to 131072 keys), and the radix select
+// re-reading the row on every sweep (whatever is longer).
 #include "ic_common.hpp"
 
 namespace ic {
@@ -612,238 +612,6 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     }
 }
 
-// ---- register-resident form (rows of up to NT*4*NCH scores) ----------------------------------
-// Same radix select for rows that do not fit the LDS cache: the row is read from memory exactly
-// once and then lives in registers as keys (a thread owns 4 consecutive positions of every chunk
-// of 4*NT positions), so the three digit passes and the ordered emit never touch memory again.  Prefix counts inside a wave come
-// from ballots and mbcnt (no shuffles through the LDS crossbar); the waves are combined through
-// one packed LDS word per wave and chunk.
-template <int NT, int NCH>
-__global__ __launch_bounds__(NT) void select_reg_kernel(SelectArgs a)
-{
-    constexpr int NW = NT / 64;
-    // First digit: all 4*NT*NCH keys hit the histogram and most of them fall into a few dozen bins
-    // (scores of one row share a handful of exponents), so every bin has kSpread counters and a
-    // lane adds to counter lane % kSpread: an eighth of the same-address collisions.  The later
-    // digits count few keys and use the first kBins1 words as a plain histogram.
-    constexpr int kSpread = 8;
-    extern __shared__ __attribute__((aligned(16))) uint32_t hist[];   // [kBins1 * kSpread]
-    __shared__ uint32_t wsum[2 * NW];
-    __shared__ uint32_t bc[4];
-    __shared__ __attribute__((aligned(16))) uint32_t wtot[2][NW < 4 ? 4 : NW];   // emit: equal << 16 | greater per wave
-    static_assert(NCH % 2 == 0 && NCH * NW == 256, "the one-scan emit covers 256 (chunk, wave) cells with one wave");
-    __shared__ __attribute__((aligned(16))) uint32_t cellsum[NCH / 2][NW];    // selected entries of (chunk pair, wave), 16-bit fields
-    __shared__ __attribute__((aligned(16))) uint32_t cellbase[NCH * NW];      // selected entries ahead of cell (chunk, wave)
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = blockIdx.x;
-    const int b = a.b0 + r / a.Ri;
-    const int i = a.i0 + r % a.Ri;
-    if (i >= a.Tq) return;
-    // ragged cache: the sequence holds Lk_b keys and its Tq query rows are its last Tq positions
-    const int Lk_b = a.seq_lens ? max(0, min(a.seq_lens[b], a.Lk)) : a.Lk;
-    int64_t nv64 = (a.seq_lens ? (int64_t)Lk_b - a.Tq : a.q_pos0) + (int64_t)i + 1;
-    nv64 = nv64 < 0 ? 0 : (nv64 > Lk_b ? Lk_b : nv64);
-    const int nv = (int)nv64;
-    const float *row = a.strip + (int64_t)r * a.ld;
-    int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
-    float *osel = a.sel ? a.sel + ((int64_t)b * a.Tq + i) * a.k_sel : nullptr;
-
-    if (nv <= a.k_sel) {                       // every visible key is selected
-        for (int m = tid; m < a.k_sel; m += NT) {
-            oidx[m] = m < nv ? m : -1;
-            if (osel) osel[m] = m < nv ? row[m] : -INFINITY;
-        }
-        return;
-    }
-
-    // Keys of the row.  Rows start 256-byte aligned and are padded to a multiple of 64 floats, so
-    // the last vector may run past nv (never past the row).  Positions at or beyond nv get key 0:
-    // it is below the key of every finite score, lands in the lowest histogram bin and is never
-    // reached by a search for k <= nv real entries.
-    u32x4 key[NCH];
-    {
-        // unconditional loads (address clamped into the row, value masked); a group of kGroup
-        // vectors is in flight while the previous group is turned into keys
-        constexpr int kGroup = NCH < 8 ? NCH : 8;
-        f32x4 raw[2][kGroup];
-        auto load_group = [&](int c0, f32x4 (&dst)[kGroup]) {
-#pragma unroll
-            for (int j = 0; j < kGroup; ++j) dst[j] = *(const f32x4 *)(row + min(((c0 + j) * NT + tid) * 4, (int)a.ld - 4));
-        };
-        load_group(0, raw[0]);
-#pragma unroll
-        for (int c0 = 0; c0 < NCH; c0 += kGroup) {
-            if (c0 + kGroup < NCH) load_group(c0 + kGroup, raw[(c0 / kGroup + 1) & 1]);
-#pragma unroll
-            for (int j = 0; j < kGroup; ++j) {
-                const int p = ((c0 + j) * NT + tid) * 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) key[c0 + j][e] = (p + e < nv) ? score_key(raw[(c0 / kGroup) & 1][j][e]) : 0u;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-
-    // ---- three digit passes: 12 + 12 + 8 bits, most significant first ----
-    uint32_t prefix, prefix_mask, need;
-    bool all_sel;                              // workgroup-uniform
-    {
-        for (int e = tid; e < kBins1 * kSpread / 4; e += NT) ((u32x4 *)hist)[e] = u32x4{0u, 0u, 0u, 0u};
-        __syncthreads();
-        const uint32_t copy = (uint32_t)lane & (kSpread - 1);
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) atomicAdd(&hist[((key[c][e] >> 20) * kSpread) | copy], 1u);
-        __syncthreads();
-        find_digit<NT, kBins1 / NT, kSpread>(hist, (uint32_t)a.k_sel, wsum, bc, tid, lane, wave);
-        prefix = bc[0] << 20;
-        prefix_mask = 4095u << 20;
-        need = bc[1];
-        all_sel = bc[2] == need;
-        __syncthreads();
-    }
-    // (as in select_kernel: the sweeps stop once every entry left in the boundary bin is selected)
-#pragma unroll 1
-    for (int pass = 1; pass < 3 && !all_sel; ++pass) {
-        const int shift = pass == 1 ? 8 : 0;
-        const uint32_t dmask = pass == 2 ? 255u : 4095u;
-        for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
-        __syncthreads();
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if ((key[c][e] & prefix_mask) == prefix) atomicAdd(&hist[(key[c][e] >> shift) & dmask], 1u);
-        __syncthreads();
-        find_digit<NT, kBins1 / NT>(hist, need, wsum, bc, tid, lane, wave);
-        prefix |= bc[0] << shift;
-        prefix_mask |= dmask << shift;
-        need = bc[1];
-        all_sel = bc[2] == need;
-        __syncthreads();
-    }
-    const uint32_t tau = prefix;               // key of the k-th largest score (all_sel: a lower bound no unselected entry reaches)
-    const uint32_t need_eq = need;             // how many entries equal to tau are selected
-
-    int tid_e = tid;
-    asm volatile("" : "+v"(tid_e));                    // recompute positions here: the 4*NCH values computed
-                                                       // for the load masks would otherwise stay live all along
-    // ---- ordered emit, common case: every entry equal to tau is selected (the k-th score is
-    // unique, or all of its ties fit).  Then "selected" is the single test key >= tau, and the
-    // slot of an entry is the number of selected entries ahead of it in position order, i.e.
-    // (chunk, wave, lane, element).  One packed wave scan per chunk pair, one scan over the 256
-    // (chunk, wave) cells, two barriers in all. ----
-    if (all_sel) {
-        uint32_t cw[NCH / 2], inc[NCH / 2];
-#pragma unroll
-        for (int j = 0; j < NCH / 2; ++j) {
-            uint32_t n0 = 0, n1 = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                n0 += key[2 * j][e] >= tau ? 1u : 0u;
-                n1 += key[2 * j + 1][e] >= tau ? 1u : 0u;
-            }
-            cw[j] = n0 | (n1 << 16);
-            inc[j] = wave_incl_scan(cw[j]);
-        }
-        if (lane == 63) {
-#pragma unroll
-            for (int j = 0; j < NCH / 2; ++j) cellsum[j][wave] = inc[j];
-        }
-        __syncthreads();
-        if (wave == 0) {
-            // lane L owns cells 4L..4L+3 = chunk L/4, waves 4(L%4)..+3
-            const int c = lane >> 2;
-            const u32x4 t4 = *(const u32x4 *)&cellsum[c >> 1][4 * (lane & 3)];
-            uint32_t v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = (t4[j] >> (16 * (c & 1))) & 0xFFFFu;
-            const uint32_t own = v[0] + v[1] + v[2] + v[3];
-            const uint32_t ex = wave_incl_scan(own) - own;
-            u32x4 o4;
-            o4[0] = ex;
-            o4[1] = ex + v[0];
-            o4[2] = ex + v[0] + v[1];
-            o4[3] = ex + v[0] + v[1] + v[2];
-            *(u32x4 *)&cellbase[4 * lane] = o4;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            if (c * NT * 4 >= nv) continue;            // workgroup-uniform; nothing left in this chunk
-            const int p = (c * NT + tid_e) * 4;
-            uint32_t slot = cellbase[c * NW + wave] + (((inc[c >> 1] - cw[c >> 1]) >> (16 * (c & 1))) & 0xFFFFu);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (key[c][e] >= tau) {
-                    if (slot < (uint32_t)a.k_sel) {    // always true for a consistent select
-                        oidx[slot] = p + e;
-                        if (osel) osel[slot] = key_score(key[c][e]);
-                    }
-                    ++slot;
-                }
-            }
-        }
-        return;
-    }
-
-    // ---- ordered emit, ties cut at the boundary: slot = #greater before + min(#equal before, need_eq) ----
-    uint32_t run_g = 0, run_e = 0;
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        if (c * NT * 4 >= nv) continue;                // workgroup-uniform; nothing left in this chunk
-        const int p = (c * NT + tid_e) * 4;
-        uint32_t lower_g = 0, lower_e = 0, wave_g = 0, wave_e = 0;
-        bool g[4], q[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            g[e] = key[c][e] > tau;
-            q[e] = key[c][e] == tau;
-            const unsigned long long bg = __ballot(g[e]), bq = __ballot(q[e]);
-            lower_g += __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
-            lower_e += __builtin_amdgcn_mbcnt_hi((uint32_t)(bq >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bq, 0u));
-            wave_g += (uint32_t)__popcll(bg);
-            wave_e += (uint32_t)__popcll(bq);
-        }
-        // positions are thread-major: all four entries of every lower lane come first, then the
-        // lane's own in order
-        if (lane == 0) wtot[c & 1][wave] = (wave_e << 16) | wave_g;   // at most 256 each
-        __syncthreads();
-        uint32_t before_g = run_g + lower_g, before_e = run_e + lower_e, tot_g = 0, tot_e = 0;
-#pragma unroll
-        for (int w4 = 0; w4 < NW; w4 += 4) {
-            const u32x4 t4 = *(const u32x4 *)&wtot[c & 1][w4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (w4 + j >= NW) continue;
-                const uint32_t tg = t4[j] & 0xFFFFu, te = t4[j] >> 16;
-                if (w4 + j < wave) {
-                    before_g += tg;
-                    before_e += te;
-                }
-                tot_g += tg;
-                tot_e += te;
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (g[e] || (q[e] && before_e < need_eq)) {
-                const uint32_t slot = before_g + (before_e < need_eq ? before_e : need_eq);
-                if (slot < (uint32_t)a.k_sel) {        // always true for a consistent select
-                    oidx[slot] = p + e;
-                    if (osel) osel[slot] = key_score(key[c][e]);
-                }
-            }
-            before_g += g[e] ? 1u : 0u;
-            before_e += q[e] ? 1u : 0u;
-        }
-        run_g += tot_g;
-        run_e += tot_e;
-    }
-}
-
 size_t select_lds_bytes(int cache_elems)
 {
     return (size_t)(kBins1 + 2 * 16 + 4 + cache_elems) * sizeof(uint32_t);
@@ -868,12 +636,8 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     static hipError_t attr1024 = hipFuncSetAttribute((const void *)select_kernel<1024>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize,
                                                      (int)select_lds_bytes(select_cache_limit()));
-    constexpr int kRegHistBytes = kBins1 * 8 * (int)sizeof(uint32_t);   // spread first-digit histogram of the register form
-    static hipError_t attr_reg = hipFuncSetAttribute((const void *)select_reg_kernel<1024, 16>,
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kRegHistBytes);
     if (attr256 != hipSuccess) return attr256;
     if (attr1024 != hipSuccess) return attr1024;
-    if (attr_reg != hipSuccess) return attr_reg;
     static hipError_t attr_cand = hipFuncSetAttribute((const void *)select_cand_kernel<1024>,
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kCandLdsWords * (int)sizeof(uint32_t));
     if (attr_cand != hipSuccess) return attr_cand;
@@ -884,14 +648,10 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     }
     if (max_row_len <= 8192)
         hipLaunchKernelGGL((select_kernel<256>), dim3((unsigned)n_rows), dim3(256), lds, st, a);
-    else if (max_row_len <= select_cache_limit())
-        hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);
-    else if (max_row_len <= 65536)
-        // too long for the LDS cache, short enough for the registers of one workgroup (the decode
-        // shape: few rows of 64K scores): read once, select in registers
-        hipLaunchKernelGGL((select_reg_kernel<1024, 16>), dim3((unsigned)n_rows), dim3(1024), kRegHistBytes, st, a);
     else
-        hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);   // streams the row on every sweep
+        // rows up to the cache limit stay in LDS after one read; longer ones (beyond the candidate form's range, or
+        // with k above a quarter of the row) are streamed on every sweep
+        hipLaunchKernelGGL((select_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), lds, st, a);
     return hipGetLastError();
 }
 

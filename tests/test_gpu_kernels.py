@@ -204,8 +204,11 @@ TOPK_CASES = [
     (2, 1, 1000, 32, 128, 999, 256),     # decode
     (1, 33, 9000, 32, 128, 8967, 2048),  # long rows: 1024-thread select, LDS-cached row
     (1, 40, 300, 64, 128, 260, 1),       # k = 1: argmax
-    (2, 2, 40000, 32, 128, 39998, 512),  # rows past the LDS cache: read once, selected in registers
+    (2, 2, 40000, 32, 128, 39998, 512),  # rows of 16385 keys and more: sampled threshold + candidate list
     (1, 3, 100000, 32, 128, 99997, 2048),  # rows past 65536 keys: sampled threshold + candidate list, one read of the row
+    (1, 3, 16400, 32, 128, 16397, 2048),   # just past the candidate form's lower limit
+    (1, 40, 16420, 32, 128, 16380, 512),   # a candidate-form launch whose first rows are too short for it (generic form inside)
+    (1, 1, 140000, 32, 128, 139999, 2048), # beyond the candidate form's bitmap: the radix select streaming the row
 ]
 
 

@@ -92,7 +92,7 @@ INDEXER_CASES = [
     ([40, 33], 3, 4, 64, 16, 64, 64),                        # tiny-config head shape
     ([0, 130, 64], 1, 32, 128, 32, 64, 192),                 # an empty sequence (owns no page)
     ([9000, 5000, 8200], 1, 32, 128, 512, 256, 9000),        # rows longer than one select tile
-    ([40000, 33000, 2100], 1, 32, 128, 2048, 64, 40000),     # register-resident select range, k = 2048
+    ([40000, 33000, 2100], 1, 32, 128, 2048, 64, 40000),     # candidate-form select range, k = 2048
 ]
 
 
