@@ -362,10 +362,10 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
 // For rows much longer than k almost every key is far below the k-th score, and pushing all of them through
 // the digit histograms (LDS atomics into the few dozen bins a row's exponents fall into) is what the generic
 // form spends its time on.  Here the row is read ONCE:
-//   sample    4096 keys in 32 contiguous blocks spread over the row -> 12-bit digit histogram (refined by the next
-//             twelve bits inside the boundary bin) -> a threshold T0 that about 2k keys of the row should reach
-//   sweep     one pass over the row: keys >= T0 are appended to a candidate list in LDS (one LDS atomic per
-//             wave and sweep step), their maximum is tracked
+//   sample    4096 keys in 32 contiguous blocks spread over the row -> a histogram of 4096 linear bins between
+//             the smallest and the largest sampled key -> a threshold T0 that about 2k keys of the row should reach
+//   sweep     one pass over the row: every wave appends its keys >= T0 to a candidate list of its own in LDS (no
+//             atomics: a wave scan places the entries), their maximum is tracked
 //   select    one histogram over the candidates with 4096 LINEAR bins between T0 and that maximum (candidates
 //             spread over all of them), a scan for the bin of the k-th largest, and an exact ranking
 //             (key descending, position ascending) of the few members of that bin
@@ -399,7 +399,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     uint32_t *hist = smem;                     // [kBins1]  (the generic form's layout starts the same way)
     uint32_t *wsum = hist + kBins1;            // [2 NW]
     uint32_t *bc = wsum + 2 * NW;              // [4]
-    uint32_t *misc = bc + 4;                   // [16]: 0 candidate count, 1 largest candidate key, 2 boundary-list count
+    uint32_t *misc = bc + 4;                   // [16]: 0 candidate count, 1 largest candidate key, 2 boundary-list count, 3 a list overflowed
     uint32_t *ckey = misc + 16;                // [kCandCap]
     uint32_t *cpos = ckey + kCandCap;          // [kCandCap]
     uint32_t *bitmap = cpos + kCandCap;        // [kCandMaxLen / 32]
@@ -426,8 +426,9 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     const uint32_t k = (uint32_t)a.k_sel;
 
     // The row arrives in groups of kGroup vectors per thread, two groups in flight: a single workgroup has to
-    // cover the whole memory latency by itself.  The first group is requested before the sample is looked at.
+    // cover the whole memory latency by itself.  The sample and the first group are requested before anything else.
     constexpr int kGroup = 4;
+    constexpr int WCAP = kCandCap / NW;        // every wave keeps its candidates in a list of its own
     const int nsteps = (nv + 4 * NT - 1) / (4 * NT);
     auto load_group = [&](int c0, f32x4 (&dst)[kGroup]) {
 #pragma unroll
@@ -438,81 +439,92 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
         }
     };
     f32x4 ga[kGroup], gb[kGroup];
+    f32x4 sv;
+    {
+        const int blk = tid >> 5;
+        const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 512 apart
+        sv = *(const f32x4 *)(row + p);
+    }
     load_group(0, ga);
 
-    // ---- sample: 32 blocks of 128 keys ----
+    // ---- sample: 32 blocks of 128 keys, a histogram of 4096 linear bins between the smallest and the largest of
+    //      them (the scores of a row share a few exponents: bins of a key digit would be hit a hundred times each,
+    //      and LDS atomics on one address take turns) ----
     for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
 #pragma unroll
     for (int q = 0; q < 4; ++q) bitmap[4 * tid + q] = 0;
     if (tid < 16) misc[tid] = 0;
-    __syncthreads();
-    uint32_t skey[4];                          // this thread's four sampled keys
-    {
-        const int blk = tid >> 5;
-        const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 512 apart
-        const f32x4 v = *(const f32x4 *)(row + p);
+    uint32_t skey[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            skey[e] = score_key(v[e]);
-            atomicAdd(&hist[skey[e] >> 20], 1u);
+    for (int e = 0; e < 4; ++e) skey[e] = score_key(sv[e]);
+    {
+        const uint32_t mx = wave_max_u32(max(max(skey[0], skey[1]), max(skey[2], skey[3])));
+        const uint32_t mn = ~wave_max_u32(~min(min(skey[0], skey[1]), min(skey[2], skey[3])));
+        if (lane == 0) {                       // (wpre is free until the boundary list is built)
+            wpre[wave] = mn;
+            wpre[NW + wave] = mx;
         }
     }
+    __syncthreads();
+    const uint32_t smin = ~wave_max_u32(~(lane < NW ? wpre[lane] : 0xFFFFFFFFu));
+    const uint32_t smax = wave_max_u32(lane < NW ? wpre[NW + lane] : 0u);
+    const uint32_t srange = smax - smin;
+    const int sbits = srange ? 32 - __clz((int)srange) : 0;
+    const int ssh = sbits > 12 ? sbits - 12 : 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) atomicAdd(&hist[(skey[e] - smin) >> ssh], 1u);
     __syncthreads();
     uint32_t want = (uint32_t)(((int64_t)kCandSample * 2 * k) / nv) + 32u;
     want = want > (uint32_t)kCandSample ? (uint32_t)kCandSample : want;
     find_digit<NT, kBins1 / NT>(hist, want, wsum, bc, tid, lane, wave);
-    uint32_t T0 = bc[0] << 20;
-    const uint32_t want2 = bc[1], in_bin = bc[2];
+    const uint32_t T0 = smin + (bc[0] << ssh); // a bin's lower edge: at least `want` sampled keys reach it
     __syncthreads();
-    // The scores of a row share a few exponents, so one bin of the first digit can hold a tenth of the row:
-    // when the bin holds clearly more sampled keys than are wanted from it, the next twelve bits of the
-    // sampled keys inside that bin place the threshold
-    if (in_bin > want2 + 16u) {                // workgroup-uniform
-        for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
-        __syncthreads();
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if ((skey[e] >> 20) == (T0 >> 20)) atomicAdd(&hist[(skey[e] >> 8) & 4095u], 1u);
-        __syncthreads();
-        find_digit<NT, kBins1 / NT>(hist, want2, wsum, bc, tid, lane, wave);
-        T0 |= bc[0] << 8;
-        __syncthreads();
-    }
 
-    // ---- sweep: the row once, candidates to LDS ----
+    // ---- sweep: the row once, the positions of the candidates to the wave's list ----
+    // The sweep is bound by vector-ALU instructions (sixteen keys per thread and group), so it does the least per
+    // key: one float comparison against the threshold (the key order is the float order) into a bit mask; only the
+    // set bits are visited afterwards, and only positions are stored -- the few candidates' keys are read back
+    // from the row (still in L2) once the sweep is over.
+    uint32_t my_cnt = 0;                       // entries in this wave's list (uniform)
+    uint32_t *wkey = ckey + wave * WCAP, *wpos = cpos + wave * WCAP;
+    // (rows of up to 65536 keys: a workgroup's row is still in L2 when its candidates are read back; longer rows of
+    // a full grid push one another out, there the keys are stored during the sweep)
+    const bool reread = nv <= 65536;           // workgroup-uniform
     {
-        uint32_t tmax = 0;
+        const float T0f = key_score(T0);
         auto sweep_group = [&](int c0, const f32x4 (&v)[kGroup]) {
-            uint32_t n_t = 0;
+            uint32_t m = 0;
 #pragma unroll
             for (int j = 0; j < kGroup; ++j) {
                 const int p = ((c0 + j) * NT + tid) * 4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) n_t += (p + e < nv && score_key(v[j][e]) >= T0) ? 1u : 0u;
+                for (int e = 0; e < 4; ++e) m |= (uint32_t)((int)(p + e < nv) & (int)(v[j][e] >= T0f)) << (4 * j + e);
             }
+            const uint32_t n_t = (uint32_t)__popc(m);
             const uint32_t incl = wave_incl_scan(n_t);
             const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
             if (total == 0u) return;               // wave-uniform
-            uint32_t base = 0;
-            if (lane == 63) base = atomicAdd(&misc[0], total);
-            base = (uint32_t)__builtin_amdgcn_readlane((int)base, 63);
-            uint32_t off = base + incl - n_t;
-            if (n_t == 0u) return;
-#pragma unroll
-            for (int j = 0; j < kGroup; ++j) {
-                const int p = ((c0 + j) * NT + tid) * 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t key = score_key(v[j][e]);
-                    if (p + e < nv && key >= T0) {
-                        if (off < (uint32_t)kCandCap) {
-                            ckey[off] = key;
-                            cpos[off] = (uint32_t)(p + e);
-                        }
-                        ++off;
-                        tmax = max(tmax, key);
-                    }
+            uint32_t off = my_cnt + incl - n_t;
+            my_cnt += total;
+            if (reread) {
+                while (m) {
+                    const int bit = __builtin_ctz(m);
+                    m &= m - 1u;
+                    if (off < (uint32_t)WCAP) wpos[off] = (uint32_t)(((c0 + (bit >> 2)) * NT + tid) * 4 + (bit & 3));
+                    ++off;
                 }
+            } else {
+#pragma unroll
+                for (int j = 0; j < kGroup; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if ((m >> (4 * j + e)) & 1u) {
+                            if (off < (uint32_t)WCAP) {
+                                wpos[off] = (uint32_t)(((c0 + j) * NT + tid) * 4 + e);
+                                wkey[off] = max(score_key(v[j][e]), T0);
+                            }
+                            ++off;
+                        }
             }
         };
 #pragma unroll 1
@@ -523,23 +535,42 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
             if (c0 + 2 * kGroup < nsteps) load_group(c0 + 2 * kGroup, ga);
             sweep_group(c0 + kGroup, gb);
         }
-        tmax = wave_max_u32(tmax);
-        if (lane == 0 && tmax != 0u) atomicMax(&misc[1], tmax);
+        if (lane == 0) {
+            atomicAdd(&misc[0], my_cnt);
+            if (my_cnt > (uint32_t)WCAP) misc[3] = 1u;     // this wave's list overflowed
+        }
     }
     __syncthreads();
-    const uint32_t n_cand = misc[0], kmax = misc[1];
-    if (n_cand < k || n_cand > (uint32_t)kCandCap) {   // workgroup-uniform
+    const uint32_t n_cand = misc[0];
+    if (n_cand < k || misc[3] != 0u) {             // workgroup-uniform
         __syncthreads();
         return false;
+    }
+    // the candidates' keys and their maximum
+    {
+        uint32_t tmax = 0;
+        for (uint32_t j = lane; j < my_cnt; j += 64) {
+            uint32_t key;
+            if (reread) {
+                key = max(score_key(row[wpos[j]]), T0);   // (>= T0 by construction; the bins below rely on it)
+                wkey[j] = key;
+            } else {
+                key = wkey[j];
+            }
+            tmax = max(tmax, key);
+        }
+        tmax = wave_max_u32(tmax);
+        if (lane == 0 && tmax != 0u) atomicMax(&misc[1], tmax);
     }
 
     // ---- one histogram over the candidates: 4096 linear bins over [T0, kmax] ----
     for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
     __syncthreads();
+    const uint32_t kmax = misc[1];
     const uint32_t range = kmax - T0;
     const int nbits = range ? 32 - __clz((int)range) : 0;
     const int sh = nbits > 12 ? nbits - 12 : 0;
-    for (uint32_t j = tid; j < n_cand; j += NT) atomicAdd(&hist[(ckey[j] - T0) >> sh], 1u);
+    for (uint32_t j = lane; j < my_cnt; j += 64) atomicAdd(&hist[(wkey[j] - T0) >> sh], 1u);
     __syncthreads();
     find_digit<NT, kBins1 / NT>(hist, k, wsum, bc, tid, lane, wave);
     const uint32_t bstar = bc[0], need = bc[1], n_b = bc[2];
@@ -549,14 +580,14 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
 
     // ---- mark the selected positions ----
     uint32_t *bl_key = wpre, *bl_pos = wpre + kBoundaryCap;
-    for (uint32_t j = tid; j < n_cand; j += NT) {
-        const uint32_t bin = (ckey[j] - T0) >> sh;
+    for (uint32_t j = lane; j < my_cnt; j += 64) {
+        const uint32_t bin = (wkey[j] - T0) >> sh;
         if (bin > bstar || (bin == bstar && !ranked)) {
-            atomicOr(&bitmap[cpos[j] >> 5], 1u << (cpos[j] & 31u));
+            atomicOr(&bitmap[wpos[j] >> 5], 1u << (wpos[j] & 31u));
         } else if (bin == bstar) {
             const uint32_t s = atomicAdd(&misc[2], 1u);
-            bl_key[s] = ckey[j];
-            bl_pos[s] = cpos[j];
+            bl_key[s] = wkey[j];
+            bl_pos[s] = wpos[j];
         }
     }
     __syncthreads();
@@ -593,13 +624,13 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
         }
     }
     __syncthreads();
-    for (uint32_t j = tid; j < n_cand; j += NT) {
-        const uint32_t pos = cpos[j], word = bitmap[pos >> 5], bit = pos & 31u;
+    for (uint32_t j = lane; j < my_cnt; j += 64) {
+        const uint32_t pos = wpos[j], word = bitmap[pos >> 5], bit = pos & 31u;
         if ((word >> bit) & 1u) {
             const uint32_t slot = wpre[pos >> 5] + (uint32_t)__popc(word & ((1u << bit) - 1u));
             if (slot < k) {                    // always true for a consistent select
                 oidx[slot] = (int32_t)pos;
-                if (osel) osel[slot] = key_score(ckey[j]);
+                if (osel) osel[slot] = key_score(wkey[j]);
             }
         }
     }
