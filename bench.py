@@ -265,6 +265,15 @@ def calibration(ic, synth, idx_prefill, kv_rows):
         out["prefill_row_gather"] = {"bytes": gb, "ms": ms, "GBs": gb / (ms * 1e-3) / 1e9, "workgroups": 512,
                                      "note": "served out of L2 / Infinity Cache; no compute attached; 512 workgroups of 4 waves "
                                              "(about 72 KB in flight per CU) is the fastest schedule found: 256 give 11, 8192 give 10.8 TB/s"}
+        # the attention kernel's tile loop without its arithmetic: the same rows through the same registers and LDS
+        tp = {}
+        for kind, name in ((ic.CALIB_TILE_GATHER, "gather_into_registers"), (ic.CALIB_TILE_STORE, "plus_lds_store"),
+                           (ic.CALIB_TILE_READ2, "plus_both_lds_reads")):
+            tp[name + "_ms"] = event_ms(lambda: ic.calibrate(kind, table, scratch, idx=flat, n=flat.numel(), table_rows=kv_rows,
+                                                             row_bytes=1152, wgs=256), reps=2, warmup=1)
+        tp["note"] = ("64-row tiles, 4 waves, one workgroup per CU, one tile of gathers ahead, one barrier per tile: what the data "
+                      "movement of the prefill attention kernel takes with no MFMA and no softmax (what is read is folded with XORs)")
+        out["prefill_attn_tile_path"] = tp
     del table, rows
     for kind, name, flop, peak in ((ic.CALIB_MFMA_BF16, "mfma_bf16", 2.0 * 32 * 32 * 16, MFMA_BF16_PEAK_TFLOPS),
                                    (ic.CALIB_MFMA_FP8, "mfma_fp8", 2.0 * 32 * 32 * 64, MFMA_FP8_PEAK_TFLOPS)):

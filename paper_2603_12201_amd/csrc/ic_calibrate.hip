@@ -100,6 +100,92 @@ __global__ __launch_bounds__(256) void calib_mfma_kernel(int iters, float *out)
     if (s == 12345.678f) out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The data movement of the prefill attention kernel's tile loop without its arithmetic: tiles of 64 table rows of
+// 1152 bytes, four waves, wave w rows 16 w .. 16 w + 15.  PARTS: 1 = gather into registers only (18 loads per lane
+// and tile, eight lanes per 128-byte line, one tile ahead); 2 = + store the tile to LDS (row-major, swizzled, double
+// buffered, one barrier per tile); 3 = + read it back as an A operand would be (16-byte reads, once per byte);
+// 4 = + read its first 1024 bytes per row through the transposing 8-byte read, once per byte.  Everything read is
+// folded into one word so that nothing is dropped.
+template <int PARTS>
+__global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned char *src, const int32_t *idx, int64_t n_rows,
+                                                                int64_t table_rows, uint32_t *out)
+{
+    constexpr int ROWB = 1152, KS = 18, TBUFB = 64 * ROWB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][64][ROWB]
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
+    const int gr = lane >> 3, gp = lane & 7;
+    auto swz = [](int row) { return ((row & 3) << 1) | ((row >> 2) & 1); };
+    const int st_off = (16 * wave + gr) * ROWB + ((gp ^ swz(gr)) << 4);
+    const int ka_row = (16 * wave + l16) * ROWB;
+    const int ka_e = ka_row + ((g ^ swz(l16)) << 4), ka_o = ka_row + (((4 + g) ^ swz(l16)) << 4);
+    const int tr_row = 8 * hh + (l16 >> 2);
+    const int tr_slot = 4 * (wave & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
+    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
+    const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int64_t n_tiles = n_rows / 64;
+    auto row_ptr = [&](int64_t tile, int half) {
+        const int64_t r = tile * 64 + 16 * wave + 8 * half + gr;
+        int64_t row = idx[r < n_rows ? r : 0];
+        row = row < 0 ? 0 : (row >= table_rows ? table_rows - 1 : row);
+        return (const u32x4 *)(src + row * ROWB) + gp;
+    };
+    u32x4 cur[KS];
+    uint32_t acc = 0;
+    int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    {
+        const u32x4 *pl = row_ptr(t, 0), *ph = row_ptr(t, 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) cur[ks] = ((ks & 1) ? ph : pl)[8 * (ks >> 1)];
+    }
+    int buf = 0;
+    for (; t < n_tiles; t += gridDim.x, buf ^= 1) {
+        unsigned char *tb = smem + buf * TBUFB;
+        const int64_t tn = t + gridDim.x < n_tiles ? t + gridDim.x : t;
+        const u32x4 *pl = row_ptr(tn, 0), *ph = row_ptr(tn, 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if constexpr (PARTS >= 2)
+                *(u32x4 *)(tb + st_off + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
+            else
+                acc ^= cur[ks][0] ^ cur[ks][1] ^ cur[ks][2] ^ cur[ks][3];
+            cur[ks] = ((ks & 1) ? ph : pl)[8 * (ks >> 1)];
+        }
+        if constexpr (PARTS >= 2) __syncthreads();
+        if constexpr (PARTS >= 3) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 v = *(const u32x4 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1));
+                acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+            }
+        }
+        if constexpr (PARTS >= 4) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
+                    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
+                    acc ^= (uint32_t)(uint16_t)(a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]);
+                }
+        }
+    }
+    if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
+}
+
+template <int PARTS>
+hipError_t launch_tilepath(const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows, int wgs, hipStream_t st)
+{
+    constexpr int lds = 2 * 64 * 1152;
+    static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath_kernel<PARTS>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((calib_tilepath_kernel<PARTS>), dim3((unsigned)wgs), dim3(256), lds, st, (const unsigned char *)src, idx, n, table_rows,
+                       (uint32_t *)dst);
+    return hipGetLastError();
+}
+
 } // namespace
 
 hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows, int row_bytes,
@@ -127,6 +213,14 @@ hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx
     case IC_CALIB_MFMA_FP8:
         hipLaunchKernelGGL((calib_mfma_kernel<true>), grid, block, 0, st, (int)n, (float *)dst);
         break;
+    case IC_CALIB_TILE_GATHER:
+        return launch_tilepath<1>(src, dst, idx, n, table_rows, wgs, st);
+    case IC_CALIB_TILE_STORE:
+        return launch_tilepath<2>(src, dst, idx, n, table_rows, wgs, st);
+    case IC_CALIB_TILE_READ:
+        return launch_tilepath<3>(src, dst, idx, n, table_rows, wgs, st);
+    case IC_CALIB_TILE_READ2:
+        return launch_tilepath<4>(src, dst, idx, n, table_rows, wgs, st);
     default:
         return hipErrorInvalidValue;
     }

@@ -351,6 +351,24 @@ def test_distill_argument_errors_need_no_gpu(ic):
     assert L.ic_distill_loss(bad, 2, one, 1000, 64, one, one, None, one, ws, None) == S.ERR_NULL
 
 
+def test_calibrate_argument_errors_need_no_gpu(ic):
+    L, S = ic.lib(), ic.Status
+    one = C.c_void_p(4096)
+    assert L.ic_calibrate(99, one, one, None, 16, 0, 0, 1, None) == S.ERR_SHAPE               # unknown kind
+    assert L.ic_calibrate(ic.CALIB_READ, one, None, None, 16, 0, 0, 1, None) == S.ERR_NULL       # no dst
+    assert L.ic_calibrate(ic.CALIB_READ, None, one, None, 16, 0, 0, 1, None) == S.ERR_NULL       # no src
+    assert L.ic_calibrate(ic.CALIB_READ, one, one, None, 24, 0, 0, 1, None) == S.ERR_SHAPE       # not a multiple of 16
+    assert L.ic_calibrate(ic.CALIB_READ, one, one, None, 16, 0, 0, 0, None) == S.ERR_SHAPE       # no workgroups
+    assert L.ic_calibrate(ic.CALIB_GATHER, one, one, None, 64, 10, 1152, 1, None) == S.ERR_NULL  # no idx
+    assert L.ic_calibrate(ic.CALIB_GATHER, one, one, one, 64, 10, 512, 1, None) == S.ERR_UNSUPPORTED
+    assert L.ic_calibrate(ic.CALIB_GATHER, one, one, one, 64, 0, 1152, 1, None) == S.ERR_SHAPE
+    for kind in (ic.CALIB_TILE_GATHER, ic.CALIB_TILE_STORE, ic.CALIB_TILE_READ, ic.CALIB_TILE_READ2):
+        assert L.ic_calibrate(kind, one, one, None, 64, 10, 1152, 1, None) == S.ERR_NULL
+        assert L.ic_calibrate(kind, one, one, one, 100, 10, 1152, 1, None) == S.ERR_SHAPE        # whole tiles of 64 rows
+        assert L.ic_calibrate(kind, one, one, one, 64, 10, 256, 1, None) == S.ERR_UNSUPPORTED
+    assert L.ic_calibrate(ic.CALIB_MFMA_BF16, None, one, None, 1 << 40, 0, 0, 1, None) == S.ERR_SHAPE
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The build is for one GPU: the bench says so and exits instead of pretending to scale."""
     import os

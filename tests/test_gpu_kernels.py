@@ -437,3 +437,25 @@ def test_sparse_attn_empty_rows_and_out_of_range(ic, oracle, Tq):
     assert np.all(O[0, 0].float().cpu().numpy() == 0)
     assert np.all(np.isneginf(lse[0, 0].cpu().numpy()))
     assert np.allclose(lse[0, 1:].cpu().numpy(), want_lse[0, 1:], atol=2e-2)
+
+
+def test_calibration_kernels_run_on_small_inputs(ic):
+    # measurement aids, no numerical result: every kind launches, stays inside its buffers (out-of-table and negative row
+    # numbers are clamped) and leaves the stream usable
+    say("calibration kernels")
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda").view(torch.uint8)
+    dst = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    ic.calibrate(ic.CALIB_READ, src, dst, n=src.numel(), wgs=64)
+    ic.calibrate(ic.CALIB_COPY, src, dst, n=dst.numel(), wgs=64)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src[:dst.numel()])
+    table = torch.zeros((300, 1152), dtype=torch.uint8, device="cuda")
+    rows = torch.randint(-5, 400, (64 * 9,), generator=torch.Generator().manual_seed(3)).to(torch.int32).cuda()
+    scratch = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    for kind in (ic.CALIB_GATHER, ic.CALIB_TILE_GATHER, ic.CALIB_TILE_STORE, ic.CALIB_TILE_READ, ic.CALIB_TILE_READ2):
+        ic.calibrate(kind, table, scratch, idx=rows, n=rows.numel(), table_rows=table.shape[0], row_bytes=1152, wgs=4)
+    for kind in (ic.CALIB_MFMA_BF16, ic.CALIB_MFMA_FP8):
+        ic.calibrate(kind, None, scratch, n=10, wgs=4)
+    torch.cuda.synchronize()
+    assert int(scratch.sum().item()) == 0          # the "rarely written" outputs were not written
+
