@@ -175,6 +175,75 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned c
     if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
 }
 
+// The same bytes per tile as calib_tilepath_kernel<4>, moved by eight waves (two per SIMD) instead of four: wave w
+// gathers and stores rows 8 w .. + 7, reads the score operand of rows 16 (w & 3) .. + 15 for the contraction steps
+// of parity w >> 2, and does the transpose reads of column block w & 3 for the row groups 2 (w >> 2), + 1.  No byte
+// is read twice.  (An attention kernel cannot be laid out this way as it stands: a wave that computes scores for
+// all heads holds all of Q, 144 registers, and at two waves per SIMD a wave has 256.)
+__global__ __launch_bounds__(512, 1) void calib_tilepath8_kernel(const unsigned char *src, const int32_t *idx, int64_t n_rows,
+                                                                 int64_t table_rows, uint32_t *out)
+{
+    constexpr int ROWB = 1152, LINES = 9, TBUFB = 64 * ROWB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][64][ROWB]
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
+    const int gr = lane >> 3, gp = lane & 7;
+    const int cb = wave & 3, par = wave >> 2;
+    auto swz = [](int row) { return ((row & 3) << 1) | ((row >> 2) & 1); };
+    const int st_off = (8 * wave + gr) * ROWB + ((gp ^ swz(gr)) << 4);
+    const int ka_row = (16 * cb + l16) * ROWB;
+    const int ka_e = ka_row + ((g ^ swz(l16)) << 4), ka_o = ka_row + (((4 + g) ^ swz(l16)) << 4);
+    const int tr_row = 8 * hh + (l16 >> 2);
+    const int tr_slot = 4 * (cb & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
+    const int tr0 = tr_row * ROWB + 128 * (cb >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
+    const int tr1 = (tr_row + 4) * ROWB + 128 * (cb >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int64_t n_tiles = n_rows / 64;
+    auto row_ptr = [&](int64_t tile) {
+        const int64_t r = tile * 64 + 8 * wave + gr;
+        int64_t row = idx[r < n_rows ? r : 0];
+        row = row < 0 ? 0 : (row >= table_rows ? table_rows - 1 : row);
+        return (const u32x4 *)(src + row * ROWB) + gp;
+    };
+    u32x4 cur[LINES];
+    uint32_t acc = 0;
+    int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    {
+        const u32x4 *pr = row_ptr(t);
+#pragma unroll
+        for (int c = 0; c < LINES; ++c) cur[c] = pr[8 * c];
+    }
+    int buf = 0;
+    for (; t < n_tiles; t += gridDim.x, buf ^= 1) {
+        unsigned char *tb = smem + buf * TBUFB;
+        const int64_t tn = t + gridDim.x < n_tiles ? t + gridDim.x : t;
+        const u32x4 *pr = row_ptr(tn);
+#pragma unroll
+        for (int c = 0; c < LINES; ++c) {
+            *(u32x4 *)(tb + st_off + 128 * c) = cur[c];
+            cur[c] = pr[8 * c];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < LINES; ++i) {
+            const int ks = 2 * i + par;
+            const u32x4 v = *(const u32x4 *)(tb + (par ? ka_o : ka_e) + 128 * (ks >> 1));
+            acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                const int j = 2 * par + jj;
+                const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
+                const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
+                acc ^= (uint32_t)(uint16_t)(a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]);
+            }
+    }
+    if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
+}
+
 template <int PARTS>
 hipError_t launch_tilepath(const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows, int wgs, hipStream_t st)
 {
@@ -221,6 +290,13 @@ hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx
         return launch_tilepath<3>(src, dst, idx, n, table_rows, wgs, st);
     case IC_CALIB_TILE_READ2:
         return launch_tilepath<4>(src, dst, idx, n, table_rows, wgs, st);
+    case IC_CALIB_TILE_8WAVES: {
+        constexpr int lds = 2 * 64 * 1152;
+        static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(calib_tilepath8_kernel, grid, dim3(512), lds, st, (const unsigned char *)src, idx, n, table_rows, (uint32_t *)dst);
+        break;
+    }
     default:
         return hipErrorInvalidValue;
     }
