@@ -40,7 +40,13 @@ def _random_layers(seed, n, shape, k, Lk, holes):
     (5, (2, 19), 24, 300, True),       # ragged query block (38 rows, blocks of 16), tiny Lk
     (3, (1, 64), 2048, 40000, False),  # full-size rows, bitmap of several KB
     (1, (1, 5), 7, 33, True),          # single layer: only the diagonal
-    (9, (1, 33), 100, 1 << 20, True),  # largest supported position range (128 KB bitmap)
+    (9, (1, 33), 100, 1 << 20, True),  # largest supported position range (128 KB bitmap): the membership form
+    # the bitmap form beyond one chunk, one tile or one pass
+    (48, (1, 20), 256, 40000, True),   # 12 x 12 tiles of layers, three chunks of the position range
+    (128, (1, 6), 64, 9000, True),     # the most layers: short chunks, 32 x 32 tiles
+    (7, (1, 9), 5000, 20000, False),   # rows longer than one pass of the workgroup; layers not a multiple of four
+    (6, (3, 5), 30, 5000, True),       # k_sel not a multiple of four: scalar reads
+    (2, (1, 300), 16, 64, False),      # more query rows than workgroups walk in one round; tiny bitmaps
 ])
 def test_overlap_matches_oracle(ic, oracle, case):
     n, shape, k, Lk, holes = case
