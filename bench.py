@@ -268,12 +268,14 @@ def calibration(ic, synth, idx_prefill, kv_rows):
         # the attention kernel's tile loop without its arithmetic: the same rows through the same registers and LDS
         tp = {}
         for kind, name in ((ic.CALIB_TILE_GATHER, "gather_into_registers"), (ic.CALIB_TILE_STORE, "plus_lds_store"),
-                           (ic.CALIB_TILE_READ2, "plus_both_lds_reads"), (ic.CALIB_TILE_8WAVES, "same_bytes_eight_waves")):
+                           (ic.CALIB_TILE_READ, "plus_score_operand_reads"), (ic.CALIB_TILE_READ2, "plus_both_lds_reads"),
+                           (ic.CALIB_TILE_INTERLEAVED, "same_bytes_phases_merged"), (ic.CALIB_TILE_8WAVES, "same_bytes_eight_waves")):
             tp[name + "_ms"] = event_ms(lambda: ic.calibrate(kind, table, scratch, idx=flat, n=flat.numel(), table_rows=kv_rows,
                                                              row_bytes=1152, wgs=256), reps=2, warmup=1)
         tp["note"] = ("64-row tiles, 4 waves, one workgroup per CU, one tile of gathers ahead, one barrier per tile: what the data "
                       "movement of the prefill attention kernel takes with no MFMA and no softmax (what is read is folded with XORs); "
-                      "same_bytes_eight_waves: the last of these with the work dealt to eight waves, no byte read twice")
+                      "same_bytes_phases_merged: stores and gathers spread between the reads; same_bytes_eight_waves: the work "
+                      "dealt to eight waves, no byte read twice")
         out["prefill_attn_tile_path"] = tp
     del table, rows
     for kind, name, flop, peak in ((ic.CALIB_MFMA_BF16, "mfma_bf16", 2.0 * 32 * 32 * 16, MFMA_BF16_PEAK_TFLOPS),

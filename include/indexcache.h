@@ -360,17 +360,19 @@ uint64_t ic_debug_indexer_launch_count(void);
  *   IC_CALIB_MFMA_FP8   workgroup), or of four 32x32x64 e4m3 instructions; dst: >= 1024 * wgs bytes
  *   IC_CALIB_TILE_*     the data movement of the prefill sparse-attention tile loop without its arithmetic, over
  *                       n rows (a multiple of 64; tiles of 64 rows) of 1152 bytes named by idx as for GATHER, one
- *                       workgroup per CU: _GATHER rows into registers, one tile ahead; _STORE also stores each
- *                       tile to LDS; _READ also reads it back once in 16-byte pieces; _READ2 also reads the
- *                       first 1024 bytes of every row a second time through the transposing LDS read;
+ *                       workgroup per CU, row numbers fetched a tile ahead of the rows: _GATHER rows into
+ *                       registers, one tile ahead; _STORE also stores each tile to LDS; _READ also reads it back
+ *                       once in 16-byte pieces; _READ2 also reads the first 1024 bytes of every row a second time
+ *                       through the transposing LDS read (the reads of a phase are all in flight together);
  *                       _8WAVES moves exactly the bytes of _READ2 with eight waves per workgroup instead of four
- *                       (wgs then counts workgroups of 512 threads)
+ *                       (wgs then counts workgroups of 512 threads); _INTERLEAVED moves them with four waves and
+ *                       the stores and gathers spread between the reads instead of in a phase of their own
  * wgs = workgroups of 256 threads to launch (1 .. 2^20).  All pointers are device pointers owned by the
  * caller; nothing is allocated.  Errors: IC_ERR_NULL, IC_ERR_SHAPE, IC_ERR_UNSUPPORTED (row_bytes), IC_ERR_HIP.
  */
 enum { IC_CALIB_READ = 0, IC_CALIB_COPY = 1, IC_CALIB_GATHER = 2, IC_CALIB_MFMA_BF16 = 3, IC_CALIB_MFMA_FP8 = 4,
        IC_CALIB_TILE_GATHER = 5, IC_CALIB_TILE_STORE = 6, IC_CALIB_TILE_READ = 7, IC_CALIB_TILE_READ2 = 8,
-       IC_CALIB_TILE_8WAVES = 9 };
+       IC_CALIB_TILE_8WAVES = 9, IC_CALIB_TILE_INTERLEAVED = 10 };
 ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows,
                        int32_t row_bytes, int32_t wgs, void *stream);
 

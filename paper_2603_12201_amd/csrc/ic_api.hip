@@ -945,7 +945,7 @@ uint64_t ic_debug_indexer_launch_count(void) { return g_indexer_launches.load();
 ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows,
                        int32_t row_bytes, int32_t wgs, void *stream)
 {
-    if (kind < IC_CALIB_READ || kind > IC_CALIB_TILE_8WAVES) return fail(IC_ERR_SHAPE, "unknown calibration kind %d", kind);
+    if (kind < IC_CALIB_READ || kind > IC_CALIB_TILE_INTERLEAVED) return fail(IC_ERR_SHAPE, "unknown calibration kind %d", kind);
     if (!dst) return fail(IC_ERR_NULL, "dst must not be NULL");
     if (wgs < 1 || wgs > (1 << 20)) return fail(IC_ERR_SHAPE, "wgs=%d outside [1, 2^20]", wgs);
     if (n < 0) return fail(IC_ERR_SHAPE, "n must not be negative");

@@ -125,10 +125,14 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned c
     const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
     const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
     const int64_t n_tiles = n_rows / 64;
-    auto row_ptr = [&](int64_t tile, int half) {
-        const int64_t r = tile * 64 + 16 * wave + 8 * half + gr;
-        int64_t row = idx[r < n_rows ? r : 0];
-        row = row < 0 ? 0 : (row >= table_rows ? table_rows - 1 : row);
+    // the row numbers of a tile are requested a tile before its rows are (as the attention kernel does), so that
+    // no gather waits for them
+    auto row_id = [&](int64_t tile, int half) {
+        const int64_t r = (tile < n_tiles ? tile : n_tiles - 1) * 64 + 16 * wave + 8 * half + gr;
+        return idx[r];
+    };
+    auto row_ptr = [&](int32_t id) {
+        const int64_t row = id < 0 ? 0 : (id >= table_rows ? table_rows - 1 : (int64_t)id);
         return (const u32x4 *)(src + row * ROWB) + gp;
     };
     u32x4 cur[KS];
@@ -136,15 +140,17 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned c
     int64_t t = blockIdx.x;
     if (t >= n_tiles) return;
     {
-        const u32x4 *pl = row_ptr(t, 0), *ph = row_ptr(t, 1);
+        const u32x4 *pl = row_ptr(row_id(t, 0)), *ph = row_ptr(row_id(t, 1));
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) cur[ks] = ((ks & 1) ? ph : pl)[8 * (ks >> 1)];
     }
+    int32_t id_lo = row_id(t + gridDim.x, 0), id_hi = row_id(t + gridDim.x, 1);
     int buf = 0;
     for (; t < n_tiles; t += gridDim.x, buf ^= 1) {
         unsigned char *tb = smem + buf * TBUFB;
-        const int64_t tn = t + gridDim.x < n_tiles ? t + gridDim.x : t;
-        const u32x4 *pl = row_ptr(tn, 0), *ph = row_ptr(tn, 1);
+        const u32x4 *pl = row_ptr(id_lo), *ph = row_ptr(id_hi);
+        id_lo = row_id(t + 2 * (int64_t)gridDim.x, 0);
+        id_hi = row_id(t + 2 * (int64_t)gridDim.x, 1);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if constexpr (PARTS >= 2)
@@ -154,22 +160,37 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned c
             cur[ks] = ((ks & 1) ? ph : pl)[8 * (ks >> 1)];
         }
         if constexpr (PARTS >= 2) __syncthreads();
+        // (the reads of a phase are all issued before the first of them is looked at, as a kernel that feeds them
+        // to the matrix pipes through a ring of registers would have them in flight)
         if constexpr (PARTS >= 3) {
+            u32x4 v[KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 v = *(const u32x4 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1));
-                acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
-            }
+            for (int ks = 0; ks < KS; ++ks) v[ks] = *(const u32x4 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc ^= v[ks][0] ^ v[ks][1] ^ v[ks][2] ^ v[ks][3];
         }
         if constexpr (PARTS >= 4) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int jh = 0; jh < 2; ++jh) {
+                s16x4 va[2][4], vb[2][4];
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
-                    const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
-                    acc ^= (uint32_t)(uint16_t)(a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]);
-                }
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        const int j = 2 * jh + jj;
+                        va[jj][nb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
+                        vb[jj][nb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        const s16x4 a = va[jj][nb], b = vb[jj][nb];
+                        acc ^= (uint32_t)(uint16_t)(a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]);
+                    }
+            }
         }
     }
     if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
@@ -199,10 +220,12 @@ __global__ __launch_bounds__(512, 1) void calib_tilepath8_kernel(const unsigned 
     const int tr0 = tr_row * ROWB + 128 * (cb >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
     const int tr1 = (tr_row + 4) * ROWB + 128 * (cb >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
     const int64_t n_tiles = n_rows / 64;
-    auto row_ptr = [&](int64_t tile) {
-        const int64_t r = tile * 64 + 8 * wave + gr;
-        int64_t row = idx[r < n_rows ? r : 0];
-        row = row < 0 ? 0 : (row >= table_rows ? table_rows - 1 : row);
+    auto row_id = [&](int64_t tile) {
+        const int64_t r = (tile < n_tiles ? tile : n_tiles - 1) * 64 + 8 * wave + gr;
+        return idx[r];
+    };
+    auto row_ptr = [&](int32_t id) {
+        const int64_t row = id < 0 ? 0 : (id >= table_rows ? table_rows - 1 : (int64_t)id);
         return (const u32x4 *)(src + row * ROWB) + gp;
     };
     u32x4 cur[LINES];
@@ -210,36 +233,143 @@ __global__ __launch_bounds__(512, 1) void calib_tilepath8_kernel(const unsigned 
     int64_t t = blockIdx.x;
     if (t >= n_tiles) return;
     {
-        const u32x4 *pr = row_ptr(t);
+        const u32x4 *pr = row_ptr(row_id(t));
 #pragma unroll
         for (int c = 0; c < LINES; ++c) cur[c] = pr[8 * c];
     }
+    int32_t id_n = row_id(t + gridDim.x);
     int buf = 0;
     for (; t < n_tiles; t += gridDim.x, buf ^= 1) {
         unsigned char *tb = smem + buf * TBUFB;
-        const int64_t tn = t + gridDim.x < n_tiles ? t + gridDim.x : t;
-        const u32x4 *pr = row_ptr(tn);
+        const u32x4 *pr = row_ptr(id_n);
+        id_n = row_id(t + 2 * (int64_t)gridDim.x);
 #pragma unroll
         for (int c = 0; c < LINES; ++c) {
             *(u32x4 *)(tb + st_off + 128 * c) = cur[c];
             cur[c] = pr[8 * c];
         }
         __syncthreads();
+        {
+            u32x4 v[LINES];
 #pragma unroll
-        for (int i = 0; i < LINES; ++i) {
-            const int ks = 2 * i + par;
-            const u32x4 v = *(const u32x4 *)(tb + (par ? ka_o : ka_e) + 128 * (ks >> 1));
-            acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+            for (int i = 0; i < LINES; ++i) {
+                const int ks = 2 * i + par;
+                v[i] = *(const u32x4 *)(tb + (par ? ka_o : ka_e) + 128 * (ks >> 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < LINES; ++i) acc ^= v[i][0] ^ v[i][1] ^ v[i][2] ^ v[i][3];
+        }
+        {
+            s16x4 va[2][4], vb[2][4];
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    const int j = 2 * par + jj;
+                    va[jj][nb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
+                    vb[jj][nb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
+                }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    const s16x4 a = va[jj][nb], b = vb[jj][nb];
+                    acc ^= (uint32_t)(uint16_t)(a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]);
+                }
+        }
+    }
+    if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
+}
+
+// The four-wave movement of calib_tilepath_kernel<4> with its phases merged: the 18 store + gather pairs that stage
+// tile t + 1 and fetch tile t + 2 are spread evenly between the 50 reads of tile t (two buffers, one barrier per
+// tile, row numbers three tiles ahead), so that the vector memory queue and the LDS pipe work at the same time.
+__global__ __launch_bounds__(256, 1) void calib_tilepath_il_kernel(const unsigned char *src, const int32_t *idx, int64_t n_rows,
+                                                                   int64_t table_rows, uint32_t *out)
+{
+    constexpr int ROWB = 1152, KS = 18, TBUFB = 64 * ROWB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][64][ROWB]
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
+    const int gr = lane >> 3, gp = lane & 7;
+    auto swz = [](int row) { return ((row & 3) << 1) | ((row >> 2) & 1); };
+    const int st_off = (16 * wave + gr) * ROWB + ((gp ^ swz(gr)) << 4);
+    const int ka_row = (16 * wave + l16) * ROWB;
+    const int ka_e = ka_row + ((g ^ swz(l16)) << 4), ka_o = ka_row + (((4 + g) ^ swz(l16)) << 4);
+    const int tr_row = 8 * hh + (l16 >> 2);
+    const int tr_slot = 4 * (wave & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
+    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
+    const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int64_t n_tiles = n_rows / 64;
+    auto row_id = [&](int64_t tile, int half) {
+        const int64_t r = (tile < n_tiles ? tile : n_tiles - 1) * 64 + 16 * wave + 8 * half + gr;
+        return idx[r];
+    };
+    auto row_ptr = [&](int32_t id) {
+        const int64_t row = id < 0 ? 0 : (id >= table_rows ? table_rows - 1 : (int64_t)id);
+        return (const u32x4 *)(src + row * ROWB) + gp;
+    };
+    u32x4 cur[KS];
+    uint32_t acc = 0;
+    int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+    const int64_t G = gridDim.x;
+    {
+        const u32x4 *pl = row_ptr(row_id(t, 0)), *ph = row_ptr(row_id(t, 1));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) cur[ks] = ((ks & 1) ? ph : pl)[8 * (ks >> 1)];
+        const u32x4 *ql = row_ptr(row_id(t + G, 0)), *qh = row_ptr(row_id(t + G, 1));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            *(u32x4 *)(smem + st_off + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
+            cur[ks] = ((ks & 1) ? qh : ql)[8 * (ks >> 1)];
+        }
+    }
+    int32_t id_lo = row_id(t + 2 * G, 0), id_hi = row_id(t + 2 * G, 1);
+    __syncthreads();
+    int buf = 0;
+    for (; t < n_tiles; t += G, buf ^= 1) {
+        const unsigned char *tb = smem + buf * TBUFB;      // tile t
+        unsigned char *tn = smem + (buf ^ 1) * TBUFB;      // tile t + G goes here
+        const u32x4 *pl = row_ptr(id_lo), *ph = row_ptr(id_hi);
+        id_lo = row_id(t + 3 * G, 0);
+        id_hi = row_id(t + 3 * G, 1);
+        // 50 reads (18 of the score operand, 32 transposing ones) with the 18 store + gather pairs spread evenly
+        // between them
+        u32x4 v[KS];
+        s16x4 va[4][4], vb[4][4];
+        auto pair = [&](int ks) {
+            *(u32x4 *)(tn + st_off + (ks & 1) * 8 * ROWB + 128 * (ks >> 1)) = cur[ks];
+            cur[ks] = ((ks & 1) ? ph : pl)[8 * (ks >> 1)];
+        };
+#pragma unroll
+        for (int r = 0; r < 50; ++r) {
+            if (r < KS) {
+                v[r] = *(const u32x4 *)(tb + ((r & 1) ? ka_o : ka_e) + 128 * (r >> 1));
+            } else {
+                const int e = r - KS, j = e >> 3, nb = (e >> 1) & 3;
+                if (e & 1)
+                    vb[j][nb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
+                else
+                    va[j][nb] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
+            }
+            // pair k goes after read number floor((k + 1) * 50 / 18) - 1
+            if ((r + 1) * KS / 50 != r * KS / 50) pair(r * KS / 50);
+            __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
+        for (int ks = 0; ks < KS; ++ks) acc ^= v[ks][0] ^ v[ks][1] ^ v[ks][2] ^ v[ks][3];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) {
-                const int j = 2 * par + jj;
-                const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr0 + 16 * j * ROWB + 256 * nb));
-                const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tb + tr1 + 16 * j * ROWB + 256 * nb));
-                acc ^= (uint32_t)(uint16_t)(a[0] ^ a[1] ^ a[2] ^ a[3] ^ b[0] ^ b[1] ^ b[2] ^ b[3]);
+                const s16x4 x = va[j][nb], y = vb[j][nb];
+                acc ^= (uint32_t)(uint16_t)(x[0] ^ x[1] ^ x[2] ^ x[3] ^ y[0] ^ y[1] ^ y[2] ^ y[3]);
             }
+        __syncthreads();
     }
     if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
 }
@@ -290,6 +420,13 @@ hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx
         return launch_tilepath<3>(src, dst, idx, n, table_rows, wgs, st);
     case IC_CALIB_TILE_READ2:
         return launch_tilepath<4>(src, dst, idx, n, table_rows, wgs, st);
+    case IC_CALIB_TILE_INTERLEAVED: {
+        constexpr int lds = 2 * 64 * 1152;
+        static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath_il_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(calib_tilepath_il_kernel, grid, dim3(256), lds, st, (const unsigned char *)src, idx, n, table_rows, (uint32_t *)dst);
+        break;
+    }
     case IC_CALIB_TILE_8WAVES: {
         constexpr int lds = 2 * 64 * 1152;
         static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);

@@ -362,7 +362,8 @@ def test_calibrate_argument_errors_need_no_gpu(ic):
     assert L.ic_calibrate(ic.CALIB_GATHER, one, one, None, 64, 10, 1152, 1, None) == S.ERR_NULL  # no idx
     assert L.ic_calibrate(ic.CALIB_GATHER, one, one, one, 64, 10, 512, 1, None) == S.ERR_UNSUPPORTED
     assert L.ic_calibrate(ic.CALIB_GATHER, one, one, one, 64, 0, 1152, 1, None) == S.ERR_SHAPE
-    for kind in (ic.CALIB_TILE_GATHER, ic.CALIB_TILE_STORE, ic.CALIB_TILE_READ, ic.CALIB_TILE_READ2, ic.CALIB_TILE_8WAVES):
+    for kind in (ic.CALIB_TILE_GATHER, ic.CALIB_TILE_STORE, ic.CALIB_TILE_READ, ic.CALIB_TILE_READ2, ic.CALIB_TILE_8WAVES,
+                 ic.CALIB_TILE_INTERLEAVED):
         assert L.ic_calibrate(kind, one, one, None, 64, 10, 1152, 1, None) == S.ERR_NULL
         assert L.ic_calibrate(kind, one, one, one, 100, 10, 1152, 1, None) == S.ERR_SHAPE        # whole tiles of 64 rows
         assert L.ic_calibrate(kind, one, one, one, 64, 10, 256, 1, None) == S.ERR_UNSUPPORTED

@@ -453,7 +453,7 @@ def test_calibration_kernels_run_on_small_inputs(ic):
     rows = torch.randint(-5, 400, (64 * 9,), generator=torch.Generator().manual_seed(3)).to(torch.int32).cuda()
     scratch = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
     for kind in (ic.CALIB_GATHER, ic.CALIB_TILE_GATHER, ic.CALIB_TILE_STORE, ic.CALIB_TILE_READ, ic.CALIB_TILE_READ2,
-                 ic.CALIB_TILE_8WAVES):
+                 ic.CALIB_TILE_8WAVES, ic.CALIB_TILE_INTERLEAVED):
         ic.calibrate(kind, table, scratch, idx=rows, n=rows.numel(), table_rows=table.shape[0], row_bytes=1152, wgs=4)
     for kind in (ic.CALIB_MFMA_BF16, ic.CALIB_MFMA_FP8):
         ic.calibrate(kind, None, scratch, n=10, wgs=4)
