@@ -399,7 +399,14 @@ def main():
         torch.cuda.synchronize()
         arms["calibration"] = calibration(ic, synth, stack.idx_cache if cfg["Tq"] == 32768 else None, cfg["Lk"])
         cal = arms["calibration"]
-        if "prefill_row_gather" in cal:
+        if "prefill_attn_tile_path" in cal:
+            # the kernel's own ceilings: its rows fetched in its own order with nothing done to them, and all of its
+            # data movement (gather, LDS stores, both operand reads) with no arithmetic, in its best four-wave order
+            tp = cal["prefill_attn_tile_path"]
+            kernels["sparse_attn"]["gather_only_ms"] = min(tp["gather_into_registers_ms"], tp["plus_lds_store_ms"])
+            kernels["sparse_attn"]["data_movement_only_ms"] = tp["same_bytes_phases_merged_ms"]
+            kernels["sparse_attn"]["frac_of_data_movement_only"] = tp["same_bytes_phases_merged_ms"] / kernels["sparse_attn"]["ms_per_layer"]
+        elif "prefill_row_gather" in cal:
             kernels["sparse_attn"]["gather_only_ms"] = cal["prefill_row_gather"]["ms"]
         kernels["sparse_attn"]["frac_of_measured_mfma"] = kernels["sparse_attn"]["achieved"] / cal["mfma_bf16"]["TFLOPs"]
         kernels["indexer_score"]["frac_of_measured_mfma"] = kernels["indexer_score"]["achieved"] / cal["mfma_bf16"]["TFLOPs"]
