@@ -17,9 +17,10 @@
 //            wave scan per word on the DPP path, one scan over the (sweep, wave) cells, two
 //            barriers in all.  When ties are cut at the boundary: per-sweep scans of packed
 //            greater / equal counts.
-// Forms by row length: the radix select with the keys cached in LDS (rows up to 16384 keys; up to 32768 when k
-// exceeds a quarter of the row), the candidate form further down (16385 to 131072 keys), and the radix select
-// re-reading the row on every sweep (whatever is longer).
+// Forms by row length: the radix select with the keys cached in LDS (launches whose rows have up to 8192 keys; up to
+// 32768 when k exceeds a quarter of the row), the candidate form further down (8193 to 131072 keys; two instances, the
+// one for rows of up to 32768 keys sized so that two rows are in flight per CU), and the radix select re-reading the
+// row on every sweep (whatever is longer).
 #include "ic_common.hpp"
 
 namespace ic {
@@ -374,14 +375,22 @@ __global__ __launch_bounds__(NT) void select_kernel(SelectArgs a)
 // Exact for every input: whenever a step cannot proceed (fewer than k candidates, more than the list holds,
 // too many ties in the boundary bin) the workgroup falls back to the generic radix select on the same row.
 constexpr int kCandCap = 12288;          // candidate list entries (6 k for k = 2048)
-constexpr int kCandMinLen = 16384;       // shorter rows of a launch take the generic form at once
-constexpr int kCandFrom = 16384;         // launches whose longest row exceeds this use the candidate form (measured:
-                                         // from 8192 it is slower than the LDS-cached generic form, from 16384 faster
-                                         // than both the LDS-cached and the register-resident one)
+constexpr int kCandMinLen = 8192;        // shorter rows of a launch take the generic form at once
+constexpr int kCandFrom = 8192;          // launches whose longest row exceeds this use the candidate form (measured: with
+                                         // two rows in flight per CU it beats the LDS-cached generic form from here on;
+                                         // with one it did so only from 16384)
 constexpr int kCandMaxLen = 131072;      // bitmap capacity
 constexpr int kCandSample = 4096;
 constexpr int kBoundaryCap = 1024;       // boundary-bin members ranked exactly
-constexpr int kCandLdsWords = kBins1 + 2 * 16 + 4 + 16 + 2 * kCandCap + 2 * (kCandMaxLen / 32);
+// A second instance for rows of up to kCandSmallLen keys: half the threads and half the LDS, so that two rows are in
+// flight per CU (a row's phases are chains of latencies; a second workgroup fills them)
+constexpr int kCandSmallLen = 32768;
+constexpr int kCandSmallCap = 6144;
+constexpr int cand_aux_words(int maxlen) { return maxlen / 32 > 2 * kBoundaryCap ? maxlen / 32 : 2 * kBoundaryCap; }
+constexpr int cand_lds_words(int nt, int maxlen, int cap)
+{
+    return kBins1 + 2 * (nt / 64) + 4 + 16 + 2 * cap + maxlen / 32 + cand_aux_words(maxlen);
+}
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
 {
@@ -390,21 +399,23 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
     return x;
 }
 
-template <int NT>
+template <int NT, int MAXLEN, int CAP>
 __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
 {
-    static_assert(NT == 1024 && kCandSample == 4 * NT, "one sample vector and four bitmap words per thread");
+    static_assert(kCandSample % (4 * NT) == 0 && (MAXLEN / 32) % NT == 0, "whole sample vectors and bitmap words per thread");
     constexpr int NW = NT / 64;
+    constexpr int SV = kCandSample / (4 * NT); // sample vectors per thread
+    constexpr int BW = MAXLEN / 32 / NT;       // bitmap words per thread
     extern __shared__ __attribute__((aligned(16))) uint32_t smem[];
     uint32_t *hist = smem;                     // [kBins1]  (the generic form's layout starts the same way)
     uint32_t *wsum = hist + kBins1;            // [2 NW]
     uint32_t *bc = wsum + 2 * NW;              // [4]
     uint32_t *misc = bc + 4;                   // [16]: 0 candidate count, 1 largest candidate key, 2 boundary-list count, 3 a list overflowed
-    uint32_t *ckey = misc + 16;                // [kCandCap]
-    uint32_t *cpos = ckey + kCandCap;          // [kCandCap]
-    uint32_t *bitmap = cpos + kCandCap;        // [kCandMaxLen / 32]
-    uint32_t *wpre = bitmap + kCandMaxLen / 32;   // [kCandMaxLen / 32] selected entries ahead of each bitmap word;
-                                                  // before that: the boundary bin's members (key, position)
+    uint32_t *ckey = misc + 16;                // [CAP]
+    uint32_t *cpos = ckey + CAP;               // [CAP]
+    uint32_t *bitmap = cpos + CAP;             // [MAXLEN / 32]
+    uint32_t *wpre = bitmap + MAXLEN / 32;     // [max(MAXLEN / 32, 2 kBoundaryCap)] selected entries ahead of each bitmap
+                                               // word; before that: the boundary bin's members (key, position)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = blockIdx.x;
@@ -419,7 +430,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     // through several calls is not inlined, and a kernel argument captured by a real function is copied to scratch
     // memory by every thread of every row).
     auto candidate_form = [&]() -> bool {
-    if (nv < kCandMinLen || nv < 4 * a.k_sel) return false;   // workgroup-uniform
+    if (nv < kCandMinLen || nv < 4 * a.k_sel || nv > MAXLEN) return false;   // workgroup-uniform
     const float *row = a.strip + (int64_t)r * a.ld;
     int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
     float *osel = a.sel ? a.sel + ((int64_t)b * a.Tq + i) * a.k_sel : nullptr;
@@ -428,7 +439,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     // The row arrives in groups of kGroup vectors per thread, two groups in flight: a single workgroup has to
     // cover the whole memory latency by itself.  The sample and the first group are requested before anything else.
     constexpr int kGroup = 4;
-    constexpr int WCAP = kCandCap / NW;        // every wave keeps its candidates in a list of its own
+    constexpr int WCAP = CAP / NW;             // every wave keeps its candidates in a list of its own
     const int nsteps = (nv + 4 * NT - 1) / (4 * NT);
     auto load_group = [&](int c0, f32x4 (&dst)[kGroup]) {
 #pragma unroll
@@ -439,11 +450,12 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
         }
     };
     f32x4 ga[kGroup], gb[kGroup];
-    f32x4 sv;
-    {
-        const int blk = tid >> 5;
-        const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 512 apart
-        sv = *(const f32x4 *)(row + p);
+    f32x4 sv[SV];
+#pragma unroll
+    for (int u = 0; u < SV; ++u) {
+        const int blk = (tid >> 5) + (NT / 32) * u;
+        const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 256 apart
+        sv[u] = *(const f32x4 *)(row + p);
     }
     load_group(0, ga);
 
@@ -452,14 +464,19 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     //      and LDS atomics on one address take turns) ----
     for (int e = tid; e < kBins1; e += NT) hist[e] = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) bitmap[4 * tid + q] = 0;
+    for (int q = 0; q < BW; ++q) bitmap[BW * tid + q] = 0;
     if (tid < 16) misc[tid] = 0;
-    uint32_t skey[4];
+    uint32_t skey[4 * SV];
+    uint32_t kmx = 0u, kmn = 0xFFFFFFFFu;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) skey[e] = score_key(sv[e]);
+    for (int e = 0; e < 4 * SV; ++e) {
+        skey[e] = score_key(sv[e >> 2][e & 3]);
+        kmx = max(kmx, skey[e]);
+        kmn = min(kmn, skey[e]);
+    }
     {
-        const uint32_t mx = wave_max_u32(max(max(skey[0], skey[1]), max(skey[2], skey[3])));
-        const uint32_t mn = ~wave_max_u32(~min(min(skey[0], skey[1]), min(skey[2], skey[3])));
+        const uint32_t mx = wave_max_u32(kmx);
+        const uint32_t mn = ~wave_max_u32(~kmn);
         if (lane == 0) {                       // (wpre is free until the boundary list is built)
             wpre[wave] = mn;
             wpre[NW + wave] = mx;
@@ -472,7 +489,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     const int sbits = srange ? 32 - __clz((int)srange) : 0;
     const int ssh = sbits > 12 ? sbits - 12 : 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) atomicAdd(&hist[(skey[e] - smin) >> ssh], 1u);
+    for (int e = 0; e < 4 * SV; ++e) atomicAdd(&hist[(skey[e] - smin) >> ssh], 1u);
     __syncthreads();
     uint32_t want = (uint32_t)(((int64_t)kCandSample * 2 * k) / nv) + 32u;
     want = want > (uint32_t)kCandSample ? (uint32_t)kCandSample : want;
@@ -603,10 +620,10 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
 
     // ---- slots: selected entries ahead of every bitmap word ----
     {
-        uint32_t wcnt[4], mine = 0;
+        uint32_t wcnt[BW], mine = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            wcnt[q] = (uint32_t)__popc(bitmap[4 * tid + q]);
+        for (int q = 0; q < BW; ++q) {
+            wcnt[q] = (uint32_t)__popc(bitmap[BW * tid + q]);
             mine += wcnt[q];
         }
         const uint32_t incl = wave_incl_scan(mine);
@@ -618,8 +635,8 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
             if (wv < wave) before += wsum[wv];
         uint32_t run = before + incl - mine;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            wpre[4 * tid + q] = run;
+        for (int q = 0; q < BW; ++q) {
+            wpre[BW * tid + q] = run;
             run += wcnt[q];
         }
     }
@@ -638,7 +655,9 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     };
     if (!candidate_form()) {
         SelectArgs ga = a;
-        ga.cache_elems = 32768;                // the candidate arrays' space serves as the row cache
+        // the candidate arrays' space serves as the row cache (rows that do not fit it are streamed)
+        constexpr int kSpace = 16 + 2 * CAP + MAXLEN / 32 + cand_aux_words(MAXLEN);
+        ga.cache_elems = kSpace >= 32768 ? 32768 : kSpace / 64 * 64;
         select_row_generic<NT>(ga, smem);
     }
 }
@@ -669,12 +688,20 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
                                                      (int)select_lds_bytes(select_cache_limit()));
     if (attr256 != hipSuccess) return attr256;
     if (attr1024 != hipSuccess) return attr1024;
-    static hipError_t attr_cand = hipFuncSetAttribute((const void *)select_cand_kernel<1024>,
-                                                      hipFuncAttributeMaxDynamicSharedMemorySize, kCandLdsWords * (int)sizeof(uint32_t));
+    constexpr int lds_big = cand_lds_words(1024, kCandMaxLen, kCandCap) * (int)sizeof(uint32_t);
+    constexpr int lds_small = cand_lds_words(512, kCandSmallLen, kCandSmallCap) * (int)sizeof(uint32_t);
+    static hipError_t attr_cand = hipFuncSetAttribute((const void *)select_cand_kernel<1024, kCandMaxLen, kCandCap>,
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_big);
+    static hipError_t attr_cand_s = hipFuncSetAttribute((const void *)select_cand_kernel<512, kCandSmallLen, kCandSmallCap>,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_small);
     if (attr_cand != hipSuccess) return attr_cand;
+    if (attr_cand_s != hipSuccess) return attr_cand_s;
     if (max_row_len > kCandFrom && max_row_len <= kCandMaxLen && max_row_len >= 4 * a.k_sel) {
         // one read of the row, a sampled threshold and a candidate list (falls back row by row)
-        hipLaunchKernelGGL((select_cand_kernel<1024>), dim3((unsigned)n_rows), dim3(1024), kCandLdsWords * sizeof(uint32_t), st, a);
+        if (max_row_len <= kCandSmallLen)
+            hipLaunchKernelGGL((select_cand_kernel<512, kCandSmallLen, kCandSmallCap>), dim3((unsigned)n_rows), dim3(512), lds_small, st, a);
+        else
+            hipLaunchKernelGGL((select_cand_kernel<1024, kCandMaxLen, kCandCap>), dim3((unsigned)n_rows), dim3(1024), lds_big, st, a);
         return hipGetLastError();
     }
     if (max_row_len <= 8192)

@@ -209,6 +209,9 @@ TOPK_CASES = [
     (1, 3, 16400, 32, 128, 16397, 2048),   # just past the candidate form's lower limit
     (1, 40, 16420, 32, 128, 16380, 512),   # a candidate-form launch whose first rows are too short for it (generic form inside)
     (1, 1, 140000, 32, 128, 139999, 2048), # beyond the candidate form's bitmap: the radix select streaming the row
+    (1, 4, 25000, 32, 128, 24996, 2048),   # the candidate form's half-size instance (rows of 16385 to 32768 keys)
+    (1, 3, 32769, 32, 128, 32766, 2048),   # its last two rows, and the first one past it in a launch of the full-size instance
+    (1, 2, 32768, 32, 128, 32766, 1024),   # a launch that ends exactly at its limit
 ]
 
 
@@ -247,7 +250,7 @@ def test_topk_tie_break_on_equal_scores(ic, oracle):
         assert np.all(idx[0, i, n:] == -1)
 
 
-@pytest.mark.parametrize("Lk", [3000, 9000, 40000, 70000])
+@pytest.mark.parametrize("Lk", [3000, 9000, 25000, 40000, 70000])
 def test_topk_ties_cut_at_the_boundary_on_long_rows(ic, oracle, Lk):
     # one head, one-hot q, keys from a handful of small integers: scores are exact on both sides
     # and fall into a few large tie classes, so the k-th score has far more ties than fit and the
@@ -270,12 +273,13 @@ def test_topk_ties_cut_at_the_boundary_on_long_rows(ic, oracle, Lk):
         assert want.size == ks and np.array_equal(idx[0, i], want)
 
 
-def test_topk_candidate_form_with_ties_at_the_boundary(ic, oracle):
-    # rows past 65536 keys (candidate form): two one-hot heads with weights 1 and 1/256 and integer key
-    # coordinates below 256 give 65536 exactly representable score levels for 100000 keys, so small tie
-    # classes sit everywhere, the boundary included: the exact ranking of the boundary bin decides
-    say("topk candidate form, ties at the boundary")
-    B, Tq, Lk, H, d, ks = 1, 4, 100000, 2, 64, 2048
+@pytest.mark.parametrize("Lk", [100000, 30000])
+def test_topk_candidate_form_with_ties_at_the_boundary(ic, oracle, Lk):
+    # candidate form (both of its instances, by row length): two one-hot heads with weights 1 and 1/256 and integer
+    # key coordinates below 256 give 65536 exactly representable score levels, so small tie classes sit everywhere,
+    # the boundary included: the exact ranking of the boundary bin decides
+    say("topk candidate form, ties at the boundary, Lk=%d" % Lk)
+    B, Tq, H, d, ks = 1, 4, 2, 64, 2048
     g = torch.Generator().manual_seed(99)
     q = torch.zeros((B, Tq, H, d)); q[:, :, 0, 3] = 1.0; q[:, :, 1, 5] = 1.0
     k = torch.zeros((B, Lk, d))
@@ -327,7 +331,7 @@ def test_topk_tie_class_beyond_65535_entries(ic, oracle, Lk):
         assert np.array_equal(idx[0, i], want)
 
 
-@pytest.mark.parametrize("Lk", [3000, 9000, 40000, 70000])
+@pytest.mark.parametrize("Lk", [3000, 9000, 25000, 40000, 70000])
 def test_topk_boundary_bin_fully_selected(ic, oracle, Lk):
     # exactly k winners, all inside one bin of the first radix digit ([64, 72): sixteen bf16 values),
     # everything else far below: the digit sweeps may stop after the first one, and "selected" becomes
