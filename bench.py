@@ -175,13 +175,17 @@ def algorithmic(cfg):
     B, Tq, Lk, p0 = cfg["B"], cfg["Tq"], cfg["Lk"], cfg["q_pos0"]
     pairs = sum(max(0, min(Lk, p0 + i + 1)) for i in range(Tq)) * B if Tq <= 4096 else \
         B * (Tq * (Tq + 1) // 2 if p0 == 0 and Tq == Lk else Tq * Lk)
+    # selected entries over all query rows: a row near the start of a sequence sees fewer keys than k_sel
+    ks = min(cfg["k_sel"], Lk)
+    n_short = max(0, min(Tq, ks - 1 - p0))                                  # rows i with p0 + i + 1 < ks
+    entries = B * ((Tq - n_short) * ks + sum(max(0, p0 + i + 1) for i in range(n_short)))
     return {
         "indexer_flop": 2.0 * cfg["H_I"] * cfg["d_I"] * pairs,                 # 2*H_I*d_I per causal pair
         "indexer_key_bytes": float(B) * Lk * cfg["d_I"] * 2,                   # decode: the key cache once
         "select_bytes": 4.0 * pairs + 4.0 * B * Tq * cfg["k_sel"],             # one read of the scores + idx
-        "attn_bytes": float(B) * Tq * (min(cfg["k_sel"], Lk) * cfg["row_elems"] * 2
-                                       + cfg["H_q"] * cfg["d_qk"] * 2 + cfg["H_q"] * cfg["d_v"] * 2),
-        "attn_flop": 2.0 * B * Tq * cfg["H_q"] * min(cfg["k_sel"], Lk) * (cfg["d_qk"] + cfg["d_v"]),
+        "attn_bytes": float(entries) * cfg["row_elems"] * 2
+                      + float(B) * Tq * (cfg["H_q"] * cfg["d_qk"] * 2 + cfg["H_q"] * cfg["d_v"] * 2),
+        "attn_flop": 2.0 * entries * cfg["H_q"] * (cfg["d_qk"] + cfg["d_v"]),
         # what a layer must move at least: its KV once, Q, O and the index tensor
         "attn_unique_bytes": float(B) * (Lk * cfg["row_elems"] * 2 + Tq * (cfg["H_q"] * (cfg["d_qk"] + cfg["d_v"]) * 2
                                                                          + cfg["k_sel"] * 4)),
@@ -383,7 +387,7 @@ def main():
     if dom == "sparse_attn":
         roofline["gathered_GBs"] = kd["gathered_GBs"]
         roofline["compulsory_bytes"] = kd["compulsory_bytes"]
-        roofline["note"] = ("algorithmic flops per launch (2 * H_q * k * (d_qk + d_v) per query token) against the bf16 MFMA peak; "
+        roofline["note"] = ("algorithmic flops per launch (2 * H_q * (d_qk + d_v) per selected entry: k per query token, fewer on the first k - 1 rows of a sequence) against the bf16 MFMA peak; "
                             "the gathered rows (gathered_GBs, algorithmic) come out of L2 / Infinity Cache, the HBM side "
                             "moves only `traffic`")
 

@@ -252,8 +252,10 @@ size_t indexer_min_ws(const ic_indexer_desc *d)
     return align_up((size_t)rows * strip_ld(d) * sizeof(float));
 }
 
+// causal_pos0 >= 0: idx is this library's causal top-k for query rows at positions causal_pos0 + t (rows that can hold
+// fewer than k_sel entries end in -1s, and the kernel leaves their empty tiles out); -1: idx is the caller's own
 ic_status run_attn(const ic_attn_desc *d, const void *Q, const void *KV, const int32_t *idx, void *O, float *lse,
-                   void *ws, hipStream_t st, const ic_paged_cache *pc = nullptr)
+                   void *ws, hipStream_t st, const ic_paged_cache *pc = nullptr, int64_t causal_pos0 = -1)
 {
     ic::AttnArgs a;
     memset(&a, 0, sizeof a);
@@ -272,6 +274,7 @@ ic_status run_attn(const ic_attn_desc *d, const void *Q, const void *KV, const i
     attn_splits(d, &a.n_splits, &a.split_len);
     a.scale_log2e = d->sm_scale * 1.4426950408889634f;
     a.pv = paged_view(pc);
+    a.causal_pos0 = causal_pos0;
     if (a.n_splits > 1) {
         const size_t nq = (size_t)d->B * d->Tq;
         a.part_o = (__bf16 *)ws;
@@ -455,13 +458,15 @@ static ic_status forward_stack_impl(const ic_layer *layers, int32_t n_layers, co
     s = check_ws(workspace, workspace_bytes, need);
     if (s != IC_OK) return s;
     hipStream_t st = (hipStream_t)stream;
+    int64_t idx_pos0 = -1;                     // position of query row 0 when the cached indices were selected
     for (int l = 0; l < n_layers; ++l) {
         const ic_layer *L = &layers[l];
         if (full_mask[l]) {   // Full: fresh indices overwrite the cache; Shared: cache left as it is
             s = run_indexer(&L->ix, L->q, L->k, L->w, idx_cache, nullptr, workspace, workspace_bytes, st, pc);
             if (s != IC_OK) return s;
+            idx_pos0 = (pc && pc->seq_lens) ? -1 : (L->ix.q_pos0 >= 0 ? (int64_t)L->ix.q_pos0 : -1);
         }
-        s = run_attn(&L->at, L->Q, L->KV, idx_cache, L->O, nullptr, workspace, st, pc);
+        s = run_attn(&L->at, L->Q, L->KV, idx_cache, L->O, nullptr, workspace, st, pc, idx_pos0);
         if (s != IC_OK) return s;
     }
     return IC_OK;

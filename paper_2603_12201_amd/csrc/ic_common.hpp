@@ -78,6 +78,10 @@ struct AttnArgs {
     int32_t n_splits, split_len; // key slots per split (multiple of 64)
     float scale_log2e;    // sm_scale * log2(e)
     PagedView pv;         // ragged / paged KV cache (KV is then the page pool [n_pages << page_shift, row_elems])
+    // >= 0: idx comes from the causal top-k of this library with query row t at position causal_pos0 + t, so row t
+    // holds min(k_sel, causal_pos0 + t + 1) entries followed by -1 only, and the tiles behind them need no work;
+    // < 0: nothing is known about idx
+    int64_t causal_pos0;
 };
 
 // Head-aggregated attention probabilities over the selected rows (the indexer's training target).

@@ -349,12 +349,21 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     int64_t qnext = chain ? qrow + gridDim.x : nq;        // >= nq: this is the workgroup's last query
 
     // what the gather needs to know about a query: its index row, its cache and its length
-    struct Src { const int32_t *idx_row; const unsigned short *kv; int b, len; bool live; };
+    // nt: tiles of the query in the chained stream.  When the selection is known to be a causal top-k, a row near the
+    // start of a sequence holds fewer than k_sel entries and ends in -1s: its tiles behind the last entry are left
+    // out (never fewer than three per query: the stream looks three tiles ahead and knows two queries at a time).
+    struct Src { const int32_t *idx_row; const unsigned short *kv; int b, len, nt; bool live; };
     auto src_of = [&](int64_t q) {
         Src r;
         r.live = q < nq;
         const int64_t qq = r.live ? q : (int64_t)blockIdx.x;          // a dead source still reads valid memory
         r.b = (int)(qq / a.Tq);
+        r.nt = ntiles;
+        if (!SPLIT && a.causal_pos0 >= 0) {
+            const int64_t held = a.causal_pos0 + qq % a.Tq + 1;       // entries the row can hold
+            if (held < a.k_sel) r.nt = max(3, (int)((held + kSlabTile - 1) / kSlabTile));
+            r.nt = min(r.nt, ntiles);
+        }
         r.idx_row = a.idx + qq * a.k_sel;
         r.kv = (const unsigned short *)a.KV + (PG && a.pv.page_table ? 0 : (int64_t)r.b * a.Lk * a.row_elems);
         r.len = PG && a.pv.seq_lens ? min(a.pv.seq_lens[r.b], a.Lk) : a.Lk;   // ragged cache: rows of this sequence
@@ -368,9 +377,9 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     struct Ids { int32_t lo, hi; };                       // validated ids of tile rows 16w+gr and 16w+gr+8
     // tile `it` of the stream: tiles at or beyond ntiles are the first tiles of the next query
     auto fetch_ids = [&](int it) -> Ids {
-        const bool nx = !SPLIT && it >= ntiles;
+        const bool nx = !SPLIT && it >= cs.nt;
         const Src &q = nx ? ns : cs;
-        const int s_lo = slot0 + (nx ? it - ntiles : it) * kSlabTile + 16 * wave + gr, s_hi = s_lo + 8;
+        const int s_lo = slot0 + (nx ? it - cs.nt : it) * kSlabTile + 16 * wave + gr, s_hi = s_lo + 8;
         const int32_t v_lo = q.idx_row[min(s_lo, a.k_sel - 1)], v_hi = q.idx_row[min(s_hi, a.k_sel - 1)];
         Ids r;
         // no short-circuit: one basic block, so the loaded ids are not waited for before their use
@@ -379,7 +388,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         return r;
     };
     auto row_ptr = [&](int32_t v, int it) {
-        const Src &q = (!SPLIT && it >= ntiles) ? ns : cs;
+        const Src &q = (!SPLIT && it >= cs.nt) ? ns : cs;
         // empty slots read row 0 of the cache (never a page-table entry: the sequence may own no page)
         const int64_t prow = v < 0 ? 0 : (PG && a.pv.page_table ? paged_row(a.pv, q.b, v) : (int64_t)v);
         return q.kv + prow * a.row_elems + 8 * gp;
@@ -840,17 +849,17 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
         for (;;) {
             step(0, F, T, T, T);
 #pragma unroll 1
-            for (int it = 1; it < ntiles; ++it) step(it, T, T, T, T);
-            step(ntiles, T, F, F, F);
+            for (int it = 1; it < cs.nt; ++it) step(it, T, T, T, T);
+            step(cs.nt, T, F, F, F);
             const bool more = qnext < nq;
             if (more) load_q_direct(qnext);               // lands while the outputs are stored
             finish();
             if (!more) break;
             qrow = qnext;
             qnext += gridDim.x;
+            g0 = (g0 + cs.nt) & 1;
             cs = ns;
             ns = src_of(qnext);
-            g0 = (g0 + ntiles) & 1;
 #pragma unroll
             for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll

@@ -235,3 +235,26 @@ def test_fp8_long_context_layer_sampled(ic, oracle, half):
     want, _ = oracle.sparse_attn(Qb, KVb, idx_rows, cfg["d_v"], cfg["v_off"], synth.sm_scale(cfg))
     err = parity.check_attn(outs[0][:, rows].float().cpu().numpy(), want)
     say("attention err %.4g" % err)
+
+
+def test_prefill_stack_rows_with_fewer_than_k_entries(ic, oracle):
+    """A prefill from position 0 through the stack: the first k_sel - 1 rows hold fewer than k_sel entries, and the
+    chained attention kernel leaves the tiles behind their last entry out.  Every row of the first layer and of a
+    Shared layer against the oracle, and against the stand-alone launch that knows nothing of the rows' lengths."""
+    cfg = synth.config("c3", Tq=1024, Lk=1024, k_sel=512, n_layers=2)
+    say("prefill stack L=1024 k=512: short rows")
+    layers = synth.stack_layers(cfg, device="cuda")
+    mask = ic.pattern_from_string("FS")
+    outs, idx_cache, n_idx = _run_stack(ic, cfg, layers, mask)
+    assert n_idx == 1
+    g = idx_cache.cpu().numpy()
+    assert np.all(g[0, 10, 11:] == -1) and np.all(g[0, 10, :11] == np.arange(11))
+    for l in range(2):
+        want, _ = oracle.sparse_attn(synth.bits(layers[l]["Q"]), synth.bits(layers[l]["KV"]), g, cfg["d_v"], cfg["v_off"],
+                                     synth.sm_scale(cfg))
+        err = parity.check_attn(outs[l].float().cpu().numpy(), want)
+        alone = ic.sparse_attn(layers[l]["Q"], layers[l]["KV"], idx_cache, cfg["d_v"], cfg["v_off"], synth.sm_scale(cfg))
+        torch.cuda.synchronize()
+        diff = (alone.float() - outs[l].float()).abs().max().item()
+        say("layer %d: err vs oracle %.4g, vs the stand-alone launch %.4g" % (l, err, diff))
+        assert diff <= 2e-2
