@@ -887,18 +887,36 @@ __global__ __launch_bounds__(D_V / 4) void attn_merge_kernel(AttnArgs a)
     const int v = threadIdx.x * 4;
     const float *ml = a.part_ml + ((qrow * a.n_splits) * a.H_q + h) * 2;
     const int64_t ml_stride = (int64_t)a.H_q * 2;
+    // The partial outputs do not depend on the weights: the first batch of them is requested together with the
+    // (maximum, sum) pairs, so that the launch waits for memory once, not twice.
+    constexpr int kBatch = 8;
+    const __bf16 *po = a.part_o + ((qrow * a.n_splits) * a.H_q + h) * D_V + v;
+    const int64_t po_stride = (int64_t)a.H_q * D_V;
+    s16x4 x[kBatch];
+    auto load_x = [&](int s0) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            x[j] = s16x4{0, 0, 0, 0};
+            if (s0 + j < a.n_splits) x[j] = *(const s16x4 *)(po + (s0 + j) * po_stride);
+        }
+    };
+    load_x(0);
     float m = -INFINITY;
     for (int s = 0; s < a.n_splits; ++s) m = fmaxf(m, ml[s * ml_stride]);
     float l = 0.f;
     f32x4 o = {0.f, 0.f, 0.f, 0.f};
-    const __bf16 *po = a.part_o + ((qrow * a.n_splits) * a.H_q + h) * D_V + v;
-    for (int s = 0; s < a.n_splits; ++s) {
-        const float ms = ml[s * ml_stride], ls = ml[s * ml_stride + 1];
-        const float sc = (ms == -INFINITY) ? 0.f : ls * fast_exp2(ms - m);   // the split's share of the row sum
-        l += sc;
-        const s16x4 x = *(const s16x4 *)(po + (int64_t)s * a.H_q * D_V);
+    for (int s0 = 0; s0 < a.n_splits; s0 += kBatch) {
+        if (s0 > 0) load_x(s0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] += __uint_as_float((uint32_t)(uint16_t)x[j] << 16) * sc;   // bf16 -> fp32 is a shift
+        for (int j = 0; j < kBatch; ++j) {
+            if (s0 + j < a.n_splits) {
+                const float ms = ml[(s0 + j) * ml_stride], ls = ml[(s0 + j) * ml_stride + 1];
+                const float sc = (ms == -INFINITY) ? 0.f : ls * fast_exp2(ms - m);   // the split's share of the row sum
+                l += sc;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] += __uint_as_float((uint32_t)(uint16_t)x[j][e] << 16) * sc;   // bf16 -> fp32 is a shift
+            }
+        }
     }
     const float inv = (l > 0.f) ? 1.f / l : 0.f;
     __bf16 *out = (__bf16 *)a.O + (qrow * a.H_q + h) * D_V + v;
