@@ -259,17 +259,23 @@ def calibration(ic, synth, idx_prefill, kv_rows):
         ic.calibrate(ic.CALIB_GATHER, table, scratch, idx=rows, n=rows.numel(), table_rows=table.shape[0], row_bytes=1152, wgs=2048)
     decode_gather()
     torch.cuda.synchronize()
-    cgraph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(cgraph):
-        for _ in range(20):
-            decode_gather()
-    torch.cuda.synchronize()
-    ms = event_ms(cgraph.replay, reps=5, warmup=2) / 20
+    note = "no compute attached, every row in flight at once; 20 launches per graph replay"
+    try:
+        cgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cgraph):
+            for _ in range(20):
+                decode_gather()
+        torch.cuda.synchronize()
+        ms = event_ms(cgraph.replay, reps=5, warmup=2) / 20
+        del cgraph
+    except Exception as e:                                   # no graph: plain launches, the host's time per call included
+        log("decode gather probe: graph capture failed (%s), timing plain launches" % e)
+        torch.cuda.synchronize()
+        ms = event_ms(decode_gather, reps=20, warmup=3)
+        note = "no compute attached, every row in flight at once; plain launches, host time per call included"
     gb = rows.numel() * 1152
     out["decode_row_gather"] = {"bytes": gb, "us": ms * 1e3, "GBs": gb / (ms * 1e-3) / 1e9,
-                                "frac_of_hbm_peak": gb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                                "note": "no compute attached, every row in flight at once; 20 launches per graph replay"}
-    del cgraph
+                                "frac_of_hbm_peak": gb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "note": note}
     # prefill attention: the rows one L=32768 layer really selects, out of its 37.7 MB cache
     if idx_prefill is not None:
         flat = idx_prefill.reshape(-1)
@@ -434,17 +440,23 @@ def main():
         ms_d14 = time_steps(lambda: dstack.step(m_fsss), args.decode_steps, 3)
         ms_dall = time_steps(lambda: dstack.step(m_ffff), args.decode_steps, 3)
         # the same FSSS step recorded in a HIP graph (the library allocates, clears and synchronises nothing)
-        dgraph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(dgraph):
-            dstack.step(m_fsss)
-        ms_d14_graph = time_steps(dgraph.replay, args.decode_steps, 3)
+        try:
+            dgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(dgraph):
+                dstack.step(m_fsss)
+            ms_d14_graph = time_steps(dgraph.replay, args.decode_steps, 3)
+        except Exception as e:                               # an arm of its own: the headline does not depend on it
+            log("decode graph arm failed: %s" % e)
+            torch.cuda.synchronize()
+            ms_d14_graph = None
         # per layer-step, from the two step times (launch gaps included; event pairs around 20 us
         # kernels would add their own few us each): FFFF - FSSS = three indexer + top-k runs
         d_idx = (ms_dall - ms_d14) / 3.0
         d_att = (ms_d14 - d_idx) / 4.0
         arms.update({
             "decode_1in4": {"ms_per_step": ms_d14, "tokens_per_s": dcfg["B"] / (ms_d14 * 1e-3), "pattern": "FSSS"},
-            "decode_1in4_graph_replay": {"ms_per_step": ms_d14_graph, "tokens_per_s": dcfg["B"] / (ms_d14_graph * 1e-3),
+            "decode_1in4_graph_replay": {"ms_per_step": ms_d14_graph,
+                                         "tokens_per_s": dcfg["B"] / (ms_d14_graph * 1e-3) if ms_d14_graph else None,
                                          "pattern": "FSSS"},
             "decode_all_full": {"ms_per_step": ms_dall, "tokens_per_s": dcfg["B"] / (ms_dall * 1e-3), "pattern": "FFFF"},
             "decode_speedup_1in4_vs_all_full": ms_dall / ms_d14,
