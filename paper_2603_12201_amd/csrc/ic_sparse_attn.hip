@@ -600,7 +600,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
             for (int hb = 0; hb < 2; ++hb)
 #pragma unroll
                 for (int par = 0; par < 2; ++par) s4[hb][par] = f32x4{0.f, 0.f, 0.f, 0.f};
-            constexpr int KRING = 6;                      // A-operand reads in flight ahead of the MFMAs
+            constexpr int KRING = 4;                      // A-operand reads in flight ahead of the MFMAs
             bf16x8 ka[KRING];
             auto ka_read = [&](int ks) { return *(const bf16x8 *)(tb + ((ks & 1) ? ka_o : ka_e) + 128 * (ks >> 1)); };
 #pragma unroll

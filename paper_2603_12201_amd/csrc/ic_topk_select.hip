@@ -399,7 +399,11 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x)
     return x;
 }
 
-template <int NT, int MAXLEN, int CAP>
+// RES: every row of the launch has at most 16 vectors per thread, and all of them are requested before anything is
+// waited for (the row sits in registers while the sample is worked on).  Used by the half-size instance, where it
+// is worth 4 % of a strip; for the 64K-key rows of a decode step it changed nothing (their sweep is bound by the
+// vector ALU of the one CU a row has, not by the loads).
+template <int NT, int MAXLEN, int CAP, bool RES>
 __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
 {
     static_assert(kCandSample % (4 * NT) == 0 && (MAXLEN / 32) % NT == 0, "whole sample vectors and bitmap words per thread");
@@ -431,6 +435,7 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
     // memory by every thread of every row).
     auto candidate_form = [&]() -> bool {
     if (nv < kCandMinLen || nv < 4 * a.k_sel || nv > MAXLEN) return false;   // workgroup-uniform
+    if (RES && nv > 16 * 4 * NT) return false;
     const float *row = a.strip + (int64_t)r * a.ld;
     int32_t *oidx = a.idx + ((int64_t)b * a.Tq + i) * a.k_sel;
     float *osel = a.sel ? a.sel + ((int64_t)b * a.Tq + i) * a.k_sel : nullptr;
@@ -449,7 +454,9 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
             if (p < nv) dst[j] = *(const f32x4 *)(row + p);   // may run past nv inside the row's padding; masked below
         }
     };
-    f32x4 ga[kGroup], gb[kGroup];
+    constexpr int NG = RES ? 4 : 2;
+    f32x4 rv[NG][kGroup];
+    f32x4 (&ga)[kGroup] = rv[0], (&gb)[kGroup] = rv[1];
     f32x4 sv[SV];
 #pragma unroll
     for (int u = 0; u < SV; ++u) {
@@ -457,7 +464,12 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
         const int p = (int)(((int64_t)blk * nv / 32) & ~(int64_t)3) + (tid & 31) * 4;   // p + 3 < nv: blocks are nv / 32 >= 256 apart
         sv[u] = *(const f32x4 *)(row + p);
     }
-    load_group(0, ga);
+    if constexpr (RES) {
+#pragma unroll
+        for (int gi = 0; gi < NG; ++gi) load_group(gi * kGroup, rv[gi]);
+    } else {
+        load_group(0, ga);
+    }
 
     // ---- sample: 32 blocks of 128 keys, a histogram of 4096 linear bins between the smallest and the largest of
     //      them (the scores of a row share a few exponents: bins of a key digit would be hit a hundred times each,
@@ -544,13 +556,19 @@ __global__ __launch_bounds__(NT) void select_cand_kernel(SelectArgs a)
                         }
             }
         };
+        if constexpr (RES) {
+#pragma unroll
+            for (int gi = 0; gi < NG; ++gi)
+                if (gi * kGroup < nsteps) sweep_group(gi * kGroup, rv[gi]);
+        } else {
 #pragma unroll 1
-        for (int c0 = 0; c0 < nsteps; c0 += 2 * kGroup) {
-            if (c0 + kGroup < nsteps) load_group(c0 + kGroup, gb);
-            sweep_group(c0, ga);
-            if (c0 + kGroup >= nsteps) break;
-            if (c0 + 2 * kGroup < nsteps) load_group(c0 + 2 * kGroup, ga);
-            sweep_group(c0 + kGroup, gb);
+            for (int c0 = 0; c0 < nsteps; c0 += 2 * kGroup) {
+                if (c0 + kGroup < nsteps) load_group(c0 + kGroup, gb);
+                sweep_group(c0, ga);
+                if (c0 + kGroup >= nsteps) break;
+                if (c0 + 2 * kGroup < nsteps) load_group(c0 + 2 * kGroup, ga);
+                sweep_group(c0 + kGroup, gb);
+            }
         }
         if (lane == 0) {
             atomicAdd(&misc[0], my_cnt);
@@ -690,18 +708,18 @@ hipError_t launch_select(const SelectArgs &a_in, int n_rows, int max_row_len, hi
     if (attr1024 != hipSuccess) return attr1024;
     constexpr int lds_big = cand_lds_words(1024, kCandMaxLen, kCandCap) * (int)sizeof(uint32_t);
     constexpr int lds_small = cand_lds_words(512, kCandSmallLen, kCandSmallCap) * (int)sizeof(uint32_t);
-    static hipError_t attr_cand = hipFuncSetAttribute((const void *)select_cand_kernel<1024, kCandMaxLen, kCandCap>,
+    static hipError_t attr_cand = hipFuncSetAttribute((const void *)select_cand_kernel<1024, kCandMaxLen, kCandCap, false>,
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_big);
-    static hipError_t attr_cand_s = hipFuncSetAttribute((const void *)select_cand_kernel<512, kCandSmallLen, kCandSmallCap>,
+    static hipError_t attr_cand_s = hipFuncSetAttribute((const void *)select_cand_kernel<512, kCandSmallLen, kCandSmallCap, true>,
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_small);
     if (attr_cand != hipSuccess) return attr_cand;
     if (attr_cand_s != hipSuccess) return attr_cand_s;
     if (max_row_len > kCandFrom && max_row_len <= kCandMaxLen && max_row_len >= 4 * a.k_sel) {
         // one read of the row, a sampled threshold and a candidate list (falls back row by row)
         if (max_row_len <= kCandSmallLen)
-            hipLaunchKernelGGL((select_cand_kernel<512, kCandSmallLen, kCandSmallCap>), dim3((unsigned)n_rows), dim3(512), lds_small, st, a);
+            hipLaunchKernelGGL((select_cand_kernel<512, kCandSmallLen, kCandSmallCap, true>), dim3((unsigned)n_rows), dim3(512), lds_small, st, a);
         else
-            hipLaunchKernelGGL((select_cand_kernel<1024, kCandMaxLen, kCandCap>), dim3((unsigned)n_rows), dim3(1024), lds_big, st, a);
+            hipLaunchKernelGGL((select_cand_kernel<1024, kCandMaxLen, kCandCap, false>), dim3((unsigned)n_rows), dim3(1024), lds_big, st, a);
         return hipGetLastError();
     }
     if (max_row_len <= 8192)
