@@ -1,10 +1,10 @@
 // Output similarity between a layer's attention under its own indices and under reused ones
 // (paper App. C: the matrix S the similarity-based pattern search is built on).
 //
-// cosine_kernel: one workgroup per row (one query token's output over all heads, bf16); products
-// and squares are exact in fp32, a thread sums its few dozen of them in fp32 and everything across
-// threads and rows is combined in fp64.  The mean over the rows goes through one fp64 atomic per
-// row.  HBM-bound: both tensors are read once.
+// cosine_kernel: one wave per row (one query token's output over all heads, bf16); products
+// and squares are exact in fp32, a lane sums a few dozen of them in fp32 and everything across
+// lanes and rows is combined in fp64.  The mean over the rows goes through one fp64 atomic per
+// workgroup.  HBM-bound: both tensors are read once.
 #include "ic_common.hpp"
 
 namespace ic {
@@ -20,80 +20,79 @@ __device__ __forceinline__ double wave_sum(double x)
     return x;
 }
 
+// One wave per row, rows dealt round-robin to the waves of a grid that fills the chip once: no barrier and no LDS
+// inside a row, eight 16-byte vectors per tensor and lane in flight, and one fp64 atomic per workgroup at the end
+// (one per row would queue tens of thousands of them on a single address).
 template <bool VEC>
-__global__ __launch_bounds__(256) void cosine_kernel(const unsigned short *A, const unsigned short *B, int64_t row_len,
-                                                     float *per_row, double *acc)
+__global__ __launch_bounds__(256) void cosine_kernel(const unsigned short *A, const unsigned short *B, int64_t n_rows,
+                                                     int64_t row_len, float *per_row, double *acc)
 {
-    __shared__ double part[3][4];
+    __shared__ double part[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t r = blockIdx.x;
-    const unsigned short *a = A + r * row_len, *b = B + r * row_len;
-    double ab = 0.0, aa = 0.0, bb = 0.0;
-    if (VEC) {
-        for (int64_t c0 = 0; c0 < row_len; c0 += 256 * 8 * 4) {        // up to four 16-byte vectors per tensor in flight
-            u32x4 va[4], vb[4];
+    const int64_t n_waves = (int64_t)gridDim.x * 4;
+    double mine = 0.0;                                         // sum of this wave's rows (lane 0)
+    for (int64_t r = (int64_t)blockIdx.x * 4 + wave; r < n_rows; r += n_waves) {
+        const unsigned short *a = A + r * row_len, *b = B + r * row_len;
+        double ab = 0.0, aa = 0.0, bb = 0.0;
+        if (VEC) {
+            constexpr int U = 8;
+            for (int64_t c0 = 0; c0 < row_len; c0 += 64 * 8 * U) {
+                u32x4 va[U], vb[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int64_t c = c0 + ((int64_t)u * 256 + tid) * 8;
-                va[u] = u32x4{0u, 0u, 0u, 0u};
-                vb[u] = u32x4{0u, 0u, 0u, 0u};
-                if (c < row_len) {
-                    va[u] = *(const u32x4 *)(a + c);
-                    vb[u] = *(const u32x4 *)(b + c);
+                for (int u = 0; u < U; ++u) {
+                    const int64_t c = c0 + ((int64_t)u * 64 + lane) * 8;
+                    va[u] = u32x4{0u, 0u, 0u, 0u};
+                    vb[u] = u32x4{0u, 0u, 0u, 0u};
+                    if (c < row_len) {
+                        va[u] = *(const u32x4 *)(a + c);
+                        vb[u] = *(const u32x4 *)(b + c);
+                    }
                 }
+                float sab = 0.f, saa = 0.f, sbb = 0.f;
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float x0 = __uint_as_float(va[u][e] << 16), x1 = __uint_as_float(va[u][e] & 0xFFFF0000u);
+                        const float y0 = __uint_as_float(vb[u][e] << 16), y1 = __uint_as_float(vb[u][e] & 0xFFFF0000u);
+                        sab += x0 * y0 + x1 * y1;
+                        saa += x0 * x0 + x1 * x1;
+                        sbb += y0 * y0 + y1 * y1;
+                    }
+                ab += (double)sab;
+                aa += (double)saa;
+                bb += (double)sbb;
             }
-            float sab = 0.f, saa = 0.f, sbb = 0.f;
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float x0 = __uint_as_float(va[u][e] << 16), x1 = __uint_as_float(va[u][e] & 0xFFFF0000u);
-                    const float y0 = __uint_as_float(vb[u][e] << 16), y1 = __uint_as_float(vb[u][e] & 0xFFFF0000u);
-                    sab += x0 * y0 + x1 * y1;
-                    saa += x0 * x0 + x1 * x1;
-                    sbb += y0 * y0 + y1 * y1;
+        } else {
+            for (int64_t c0 = 0; c0 < row_len; c0 += 64 * 16) {
+                float sab = 0.f, saa = 0.f, sbb = 0.f;
+                for (int u = 0; u < 16; ++u) {
+                    const int64_t c = c0 + (int64_t)u * 64 + lane;
+                    if (c < row_len) {
+                        const float x = bf16_to_f32(a[c]), y = bf16_to_f32(b[c]);
+                        sab += x * y;
+                        saa += x * x;
+                        sbb += y * y;
+                    }
                 }
-            ab += (double)sab;
-            aa += (double)saa;
-            bb += (double)sbb;
-        }
-    } else {
-        for (int64_t c0 = 0; c0 < row_len; c0 += 256 * 16) {
-            float sab = 0.f, saa = 0.f, sbb = 0.f;
-            for (int u = 0; u < 16; ++u) {
-                const int64_t c = c0 + (int64_t)u * 256 + tid;
-                if (c < row_len) {
-                    const float x = bf16_to_f32(a[c]), y = bf16_to_f32(b[c]);
-                    sab += x * y;
-                    saa += x * x;
-                    sbb += y * y;
-                }
+                ab += (double)sab;
+                aa += (double)saa;
+                bb += (double)sbb;
             }
-            ab += (double)sab;
-            aa += (double)saa;
-            bb += (double)sbb;
         }
-    }
-    ab = wave_sum(ab);
-    aa = wave_sum(aa);
-    bb = wave_sum(bb);
-    if (lane == 0) {
-        part[0][wave] = ab;
-        part[1][wave] = aa;
-        part[2][wave] = bb;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        ab = part[0][0] + part[0][1] + part[0][2] + part[0][3];
-        aa = part[1][0] + part[1][1] + part[1][2] + part[1][3];
-        bb = part[2][0] + part[2][1] + part[2][2] + part[2][3];
+        ab = wave_sum(ab);
+        aa = wave_sum(aa);
+        bb = wave_sum(bb);
         double cs;
-        if (aa == 0.0 && bb == 0.0) cs = 1.0;              // two all-zero rows agree
+        if (aa == 0.0 && bb == 0.0) cs = 1.0;                  // two all-zero rows agree
         else if (aa == 0.0 || bb == 0.0) cs = 0.0;
         else cs = ab / (sqrt(aa) * sqrt(bb));
-        if (per_row) per_row[r] = (float)cs;
-        atomicAdd(acc, cs);
+        if (lane == 0 && per_row) per_row[r] = (float)cs;
+        mine += cs;
     }
+    if (lane == 0) part[wave] = mine;
+    __syncthreads();
+    if (tid == 0) atomicAdd(acc, part[0] + part[1] + part[2] + part[3]);
 }
 
 __global__ void cosine_zero_kernel(double *acc) { *acc = 0.0; }
@@ -122,12 +121,14 @@ hipError_t launch_cosine(const void *A, const void *B, int64_t n_rows, int64_t r
 {
     hipLaunchKernelGGL(cosine_zero_kernel, dim3(1), dim3(1), 0, st, acc);
     const bool vec = row_len % 8 == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)B % 16 == 0;
+    const int64_t want = (n_rows + 3) / 4;                    // workgroups if every wave took one row
+    const unsigned grid = (unsigned)(want < 2048 ? (want < 1 ? 1 : want) : 2048);   // 8 workgroups per CU at most
     if (vec)
-        hipLaunchKernelGGL(cosine_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, st, (const unsigned short *)A,
-                           (const unsigned short *)B, row_len, per_row, acc);
+        hipLaunchKernelGGL(cosine_kernel<true>, dim3(grid), dim3(256), 0, st, (const unsigned short *)A,
+                           (const unsigned short *)B, n_rows, row_len, per_row, acc);
     else
-        hipLaunchKernelGGL(cosine_kernel<false>, dim3((unsigned)n_rows), dim3(256), 0, st, (const unsigned short *)A,
-                           (const unsigned short *)B, row_len, per_row, acc);
+        hipLaunchKernelGGL(cosine_kernel<false>, dim3(grid), dim3(256), 0, st, (const unsigned short *)A,
+                           (const unsigned short *)B, n_rows, row_len, per_row, acc);
     hipLaunchKernelGGL(cosine_finish_kernel, dim3(1), dim3(1), 0, st, (const double *)acc, n_rows, mean);
     return hipGetLastError();
 }
