@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void calib_mfma_kernel(int iters, float *out)
 
 // The data movement of the prefill attention kernel's tile loop without its arithmetic: tiles of 64 table rows of
 // 1152 bytes, four waves, wave w rows 16 w .. 16 w + 15.  PARTS: 1 = gather into registers only (18 loads per lane
-// and tile, eight lanes per 128-byte line, one tile ahead); 2 = + store the tile to LDS (row-major, swizzled, double
+// and tile, eight lanes per 128-byte line, one tile ahead); 2 = + store the tile to LDS (row-major, rows padded by 32 bytes, double
 // buffered, one barrier per tile); 3 = + read it back as an A operand would be (16-byte reads, once per byte);
 // 4 = + read its first 1024 bytes per row through the transposing 8-byte read, once per byte.  Everything read is
 // folded into one word so that nothing is dropped.
@@ -110,20 +110,19 @@ template <int PARTS>
 __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned char *src, const int32_t *idx, int64_t n_rows,
                                                                 int64_t table_rows, uint32_t *out)
 {
-    constexpr int ROWB = 1152, KS = 18, TBUFB = 64 * ROWB;
+    constexpr int ROWG = 1152, ROWB = ROWG + 32, KS = 18, TBUFB = 64 * ROWB;   // row in memory, row stride in LDS
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][64][ROWB]
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
     const int gr = lane >> 3, gp = lane & 7;
-    auto swz = [](int row) { return ((row & 3) << 1) | ((row >> 2) & 1); };
-    const int st_off = (16 * wave + gr) * ROWB + ((gp ^ swz(gr)) << 4);
+    const int st_off = (16 * wave + gr) * ROWB + (gp << 4);
     const int ka_row = (16 * wave + l16) * ROWB;
-    const int ka_e = ka_row + ((g ^ swz(l16)) << 4), ka_o = ka_row + (((4 + g) ^ swz(l16)) << 4);
-    const int tr_row = 8 * hh + (l16 >> 2);
+    const int ka_e = ka_row + (g << 4), ka_o = ka_row + ((4 + g) << 4);
+    const int tr_row = 8 * hh + 2 * (l16 >> 2);           // the four rows of a transpose read are two apart
     const int tr_slot = 4 * (wave & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
-    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
-    const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + (tr_slot << 4) + 8 * (l16 & 1);
+    const int tr1 = tr0 + ROWB;
     const int64_t n_tiles = n_rows / 64;
     // the row numbers of a tile are requested a tile before its rows are (as the attention kernel does), so that
     // no gather waits for them
@@ -133,7 +132,7 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned c
     };
     auto row_ptr = [&](int32_t id) {
         const int64_t row = id < 0 ? 0 : (id >= table_rows ? table_rows - 1 : (int64_t)id);
-        return (const u32x4 *)(src + row * ROWB) + gp;
+        return (const u32x4 *)(src + row * ROWG) + gp;
     };
     u32x4 cur[KS];
     uint32_t acc = 0;
@@ -204,21 +203,20 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_kernel(const unsigned c
 __global__ __launch_bounds__(512, 1) void calib_tilepath8_kernel(const unsigned char *src, const int32_t *idx, int64_t n_rows,
                                                                  int64_t table_rows, uint32_t *out)
 {
-    constexpr int ROWB = 1152, LINES = 9, TBUFB = 64 * ROWB;
+    constexpr int ROWG = 1152, ROWB = ROWG + 32, LINES = 9, TBUFB = 64 * ROWB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][64][ROWB]
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
     const int gr = lane >> 3, gp = lane & 7;
     const int cb = wave & 3, par = wave >> 2;
-    auto swz = [](int row) { return ((row & 3) << 1) | ((row >> 2) & 1); };
-    const int st_off = (8 * wave + gr) * ROWB + ((gp ^ swz(gr)) << 4);
+    const int st_off = (8 * wave + gr) * ROWB + (gp << 4);
     const int ka_row = (16 * cb + l16) * ROWB;
-    const int ka_e = ka_row + ((g ^ swz(l16)) << 4), ka_o = ka_row + (((4 + g) ^ swz(l16)) << 4);
-    const int tr_row = 8 * hh + (l16 >> 2);
+    const int ka_e = ka_row + (g << 4), ka_o = ka_row + ((4 + g) << 4);
+    const int tr_row = 8 * hh + 2 * (l16 >> 2);           // the four rows of a transpose read are two apart
     const int tr_slot = 4 * (cb & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
-    const int tr0 = tr_row * ROWB + 128 * (cb >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
-    const int tr1 = (tr_row + 4) * ROWB + 128 * (cb >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int tr0 = tr_row * ROWB + 128 * (cb >> 1) + (tr_slot << 4) + 8 * (l16 & 1);
+    const int tr1 = tr0 + ROWB;
     const int64_t n_tiles = n_rows / 64;
     auto row_id = [&](int64_t tile) {
         const int64_t r = (tile < n_tiles ? tile : n_tiles - 1) * 64 + 8 * wave + gr;
@@ -226,7 +224,7 @@ __global__ __launch_bounds__(512, 1) void calib_tilepath8_kernel(const unsigned 
     };
     auto row_ptr = [&](int32_t id) {
         const int64_t row = id < 0 ? 0 : (id >= table_rows ? table_rows - 1 : (int64_t)id);
-        return (const u32x4 *)(src + row * ROWB) + gp;
+        return (const u32x4 *)(src + row * ROWG) + gp;
     };
     u32x4 cur[LINES];
     uint32_t acc = 0;
@@ -289,20 +287,19 @@ __global__ __launch_bounds__(512, 1) void calib_tilepath8_kernel(const unsigned 
 __global__ __launch_bounds__(256, 1) void calib_tilepath_il_kernel(const unsigned char *src, const int32_t *idx, int64_t n_rows,
                                                                    int64_t table_rows, uint32_t *out)
 {
-    constexpr int ROWB = 1152, KS = 18, TBUFB = 64 * ROWB;
+    constexpr int ROWG = 1152, ROWB = ROWG + 32, KS = 18, TBUFB = 64 * ROWB;   // row in memory, row stride in LDS
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][64][ROWB]
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
     const int gr = lane >> 3, gp = lane & 7;
-    auto swz = [](int row) { return ((row & 3) << 1) | ((row >> 2) & 1); };
-    const int st_off = (16 * wave + gr) * ROWB + ((gp ^ swz(gr)) << 4);
+    const int st_off = (16 * wave + gr) * ROWB + (gp << 4);
     const int ka_row = (16 * wave + l16) * ROWB;
-    const int ka_e = ka_row + ((g ^ swz(l16)) << 4), ka_o = ka_row + (((4 + g) ^ swz(l16)) << 4);
-    const int tr_row = 8 * hh + (l16 >> 2);
+    const int ka_e = ka_row + (g << 4), ka_o = ka_row + ((4 + g) << 4);
+    const int tr_row = 8 * hh + 2 * (l16 >> 2);           // the four rows of a transpose read are two apart
     const int tr_slot = 4 * (wave & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
-    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row)) << 4) + 8 * (l16 & 1);
-    const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + (tr_slot << 4) + 8 * (l16 & 1);
+    const int tr1 = tr0 + ROWB;
     const int64_t n_tiles = n_rows / 64;
     auto row_id = [&](int64_t tile, int half) {
         const int64_t r = (tile < n_tiles ? tile : n_tiles - 1) * 64 + 16 * wave + 8 * half + gr;
@@ -310,7 +307,7 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_il_kernel(const unsigne
     };
     auto row_ptr = [&](int32_t id) {
         const int64_t row = id < 0 ? 0 : (id >= table_rows ? table_rows - 1 : (int64_t)id);
-        return (const u32x4 *)(src + row * ROWB) + gp;
+        return (const u32x4 *)(src + row * ROWG) + gp;
     };
     u32x4 cur[KS];
     uint32_t acc = 0;
@@ -377,7 +374,7 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_il_kernel(const unsigne
 template <int PARTS>
 hipError_t launch_tilepath(const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows, int wgs, hipStream_t st)
 {
-    constexpr int lds = 2 * 64 * 1152;
+    constexpr int lds = 2 * 64 * (1152 + 32);
     static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath_kernel<PARTS>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (attr != hipSuccess) return attr;
     hipLaunchKernelGGL((calib_tilepath_kernel<PARTS>), dim3((unsigned)wgs), dim3(256), lds, st, (const unsigned char *)src, idx, n, table_rows,
@@ -421,14 +418,14 @@ hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx
     case IC_CALIB_TILE_READ2:
         return launch_tilepath<4>(src, dst, idx, n, table_rows, wgs, st);
     case IC_CALIB_TILE_INTERLEAVED: {
-        constexpr int lds = 2 * 64 * 1152;
+        constexpr int lds = 2 * 64 * (1152 + 32);
         static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath_il_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(calib_tilepath_il_kernel, grid, dim3(256), lds, st, (const unsigned char *)src, idx, n, table_rows, (uint32_t *)dst);
         break;
     }
     case IC_CALIB_TILE_8WAVES: {
-        constexpr int lds = 2 * 64 * 1152;
+        constexpr int lds = 2 * 64 * (1152 + 32);
         static hipError_t attr = hipFuncSetAttribute((const void *)calib_tilepath8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(calib_tilepath8_kernel, grid, dim3(512), lds, st, (const unsigned char *)src, idx, n, table_rows, (uint32_t *)dst);

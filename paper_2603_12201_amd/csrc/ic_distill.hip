@@ -22,9 +22,10 @@ namespace {
 
 constexpr int kProbRows = 16;                 // selected rows per wave and step
 
-// XOR swizzle of the 16-byte slot inside a 128-byte window of an LDS row (rows are unpadded, so
-// without it the 16 rows of an A-operand read would start in the same bank)
-__device__ __forceinline__ int slot_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// LDS rows are padded by 32 bytes and not swizzled: with rows 1152 + 32 bytes apart the 16-byte A-operand read of 16
+// rows (lane = row, same piece in every lane) runs at the rate of a contiguous read (measured; with rows 1152 apart
+// and an XOR swizzle it took 1.65 times as long).
+constexpr int kProbPad = 32;
 
 // Validity of a wave's 16 rows from the two ballots over the gather lanes (lane 8r' + piece holds
 // row r' of the first / second eight rows): bit r of the result is row r.
@@ -46,8 +47,8 @@ template <int D_QK>
 __global__ __launch_bounds__(256, 2) void attn_probs_kernel(ProbsArgs a)
 {
     constexpr int KS = D_QK / 32;             // contraction steps = 16-byte chunks per gather lane
-    constexpr int ROWB = D_QK * 2;            // bytes per LDS row
-    static_assert(ROWB % 128 == 0 && KS % 2 == 0, "a row is a whole number of 128-byte windows");
+    constexpr int ROWB = D_QK * 2 + kProbPad; // bytes per LDS row
+    static_assert((D_QK * 2) % 128 == 0 && KS % 2 == 0, "a row is a whole number of 128-byte windows");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [4 waves][16 rows][ROWB]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
@@ -79,10 +80,10 @@ __global__ __launch_bounds__(256, 2) void attn_probs_kernel(ProbsArgs a)
     const float inv_h = 1.f / (float)a.H_q;
 
     // LDS offsets of the lane in its two roles
-    const int st_off = gr * ROWB + ((gp ^ slot_swz(gr)) << 4);            // + 8 rows for odd chunks
+    const int st_off = gr * ROWB + (gp << 4);                             // + 8 rows for odd chunks
     const int ka_row = l16 * ROWB;
-    const int ka_e = ka_row + ((g ^ slot_swz(l16)) << 4);                 // even contraction steps
-    const int ka_o = ka_row + (((4 + g) ^ slot_swz(l16)) << 4);           // odd ones
+    const int ka_e = ka_row + (g << 4);                                   // even contraction steps
+    const int ka_o = ka_row + ((4 + g) << 4);                             // odd ones
 
     struct Ids { int32_t lo, hi; };           // validated ids of rows gr and gr + 8 of a group, -1: empty slot
     auto fetch_ids = [&](int grp) -> Ids {
@@ -334,13 +335,13 @@ hipError_t launch_attn_probs(const ProbsArgs &a, int d_qk, hipStream_t st)
     const int64_t nq = (int64_t)a.B * a.Tq;
     if (nq <= 0) return hipSuccess;
     if (d_qk == 576) {
-        constexpr int lds = 4 * kProbRows * 576 * 2;      // above the default limit of dynamic LDS: opt in once
+        constexpr int lds = 4 * kProbRows * (576 * 2 + kProbPad);      // above the default limit of dynamic LDS: opt in once
         static hipError_t attr = hipFuncSetAttribute((const void *)attn_probs_kernel<576>,
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (attr != hipSuccess) return attr;
         hipLaunchKernelGGL(attn_probs_kernel<576>, dim3((unsigned)nq), dim3(256), lds, st, a);
     } else if (d_qk == 64) {
-        hipLaunchKernelGGL(attn_probs_kernel<64>, dim3((unsigned)nq), dim3(256), 4 * kProbRows * 64 * 2, st, a);
+        hipLaunchKernelGGL(attn_probs_kernel<64>, dim3((unsigned)nq), dim3(256), 4 * kProbRows * (64 * 2 + kProbPad), st, a);
     } else {
         return hipErrorInvalidValue;
     }

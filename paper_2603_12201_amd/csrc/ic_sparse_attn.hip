@@ -269,11 +269,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs a)
 constexpr int kSlabTile = 64;
 constexpr float kLazyLog2 = 8.f;
 
-// Swizzle of the 16-byte slot inside each 128-byte window of a tile row (row stride 1152 bytes,
-// a multiple of 128, no padding): eight consecutive rows land in eight different slots (the
-// A-operand reads and the stores), four consecutive rows in four different 32-byte pairs (the
-// transpose reads).
-__device__ __forceinline__ int slot_swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+// Tile rows in LDS are padded by 32 bytes (row stride 1184 for rows of 1152) and not swizzled.  Measured on this part
+// with every wave of a CU reading: the 16-byte A-operand read of 16 rows (lane = row, same piece in every lane) takes
+// 2.3 ticks per instruction with rows 1152 + an odd multiple of 32 bytes apart, as a contiguous read does, and 3.8
+// with rows 1152 apart under either of two XOR swizzles; an 8-byte transpose read serves 32 lanes per pass out of 64
+// banks of 4 bytes, i.e. 64 contiguous bytes of four rows, and rows 2 x 1184 apart start 64 bytes apart modulo 256:
+// conflict-free when the four rows of a pass are two apart (even rows, then odd rows).
+constexpr int kSlabPad = 32;
 
 // Reductions over the four 16-lane groups of a wave with the row-swap instructions (plain VALU
 // latency, no trip through the LDS crossbar).  permlane16_swap(x, x) yields {[r0,r0,r2,r2],
@@ -312,8 +314,8 @@ template <int D_QK, int D_V, bool PG, bool SPLIT>         // value columns = the
 __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
 {
     constexpr int KS = D_QK / 32;                         // contraction steps of S^T = 16-byte chunks per gather lane
-    constexpr int ROWB = D_QK * 2;                        // LDS row stride
-    static_assert(ROWB % 128 == 0 && D_V % 128 == 0 && KS % 2 == 0, "row = whole 128-byte windows");
+    constexpr int ROWB = D_QK * 2 + kSlabPad;             // LDS row stride
+    static_assert((D_QK * 2) % 128 == 0 && D_V % 128 == 0 && KS % 2 == 0, "row = whole 128-byte windows");
     constexpr int TBUFB = kSlabTile * ROWB;
     constexpr int PSTR = kSlabTile * 2 + 16;              // bytes per head row of the P tile
     constexpr int PBUFB = 32 * PSTR;
@@ -424,14 +426,16 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
     float l_own[2] = {0.f, 0.f};                          // this lane's share of the wave's row sums (ref m_ref)
 
     // LDS addresses of the lane in its three roles (byte offsets inside one tile buffer)
-    const int st_off = (16 * wave + gr) * ROWB + ((gp ^ slot_swz(gr)) << 4);          // + 8 rows for odd chunks
+    const int st_off = (16 * wave + gr) * ROWB + (gp << 4);                           // + 8 rows for odd chunks
     const int ka_row = (16 * wave + l16) * ROWB;
-    const int ka_e = ka_row + ((g ^ slot_swz(l16)) << 4);                             // even contraction steps
-    const int ka_o = ka_row + (((4 + g) ^ slot_swz(l16)) << 4);                       // odd ones
-    const int tr_row = 8 * hh + (l16 >> 2);
+    const int ka_e = ka_row + (g << 4);                                               // even contraction steps
+    const int ka_o = ka_row + ((4 + g) << 4);                                         // odd ones
+    // transpose reads: the four rows of a read are two apart; within a group of eight rows the first read takes the
+    // even rows (contraction positions 0-3), the second the odd ones (positions 4-7), and P is written in that order
+    const int tr_row = 8 * hh + 2 * (l16 >> 2);
     const int tr_slot = 4 * (wave & 1) + 2 * (g & 1) + ((l16 & 3) >> 1);
-    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + ((tr_slot ^ slot_swz(tr_row)) << 4) + 8 * (l16 & 1);
-    const int tr1 = (tr_row + 4) * ROWB + 128 * (wave >> 1) + ((tr_slot ^ slot_swz(tr_row + 4)) << 4) + 8 * (l16 & 1);
+    const int tr0 = tr_row * ROWB + 128 * (wave >> 1) + (tr_slot << 4) + 8 * (l16 & 1);
+    const int tr1 = tr0 + ROWB;
 
     // The gather registers are refilled chunk by chunk: as soon as chunk ks of tile t+1 has been
     // stored to LDS, the same registers receive chunk ks of tile t+2.
@@ -665,7 +669,7 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
                 const float m_new = (mx > m_all[hb] + kLazyLog2) ? mx : m_all[hb];   // m_all >= m_ref always
                 const float resc = (m_new == -INFINITY) ? 1.f : fast_exp2(m_ref[hb] - m_new);
                 float psum = 0.f;
-                s16x4 pk;
+                short pk[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const float p = (z[i] == -INFINITY) ? 0.f : fast_exp2(z[i] - m_new);
@@ -675,7 +679,12 @@ __global__ __launch_bounds__(256, 1) void attn_slab_kernel(AttnArgs a)
                 l_own[hb] = l_own[hb] * resc + psum;
                 m_ref[hb] = m_new;
                 unsigned char *prow = pb + (16 * hb + l16) * PSTR;
-                *(s16x4 *)(prow + (16 * wave + 4 * g) * 2) = pk;
+                // row e of a group of eight sits at contraction position e / 2 + 4 (e % 2) (see the transpose reads):
+                // the lane's rows 4 (g & 1) + {0, 2} are neighbours there, and so are its rows 4 (g & 1) + {1, 3}
+                typedef __attribute__((ext_vector_type(2))) short s16x2;
+                unsigned char *pg = prow + (16 * wave + 8 * (g >> 1) + 2 * (g & 1)) * 2;
+                *(s16x2 *)pg = s16x2{pk[0], pk[2]};
+                *(s16x2 *)(pg + 8) = s16x2{pk[1], pk[3]};
                 if (g == 0) *(float *)(prow + kSlabTile * 2 + 4 * wave) = m_new;
             }
         }
@@ -971,7 +980,7 @@ hipError_t launch_slab_t(const AttnArgs &a, size_t lds, hipStream_t st)
 template <int D_QK, int D_V>
 hipError_t launch_slab(const AttnArgs &a, hipStream_t st)
 {
-    const size_t lds = (size_t)2 * kSlabTile * D_QK * 2 + 2 * 32 * (kSlabTile * 2 + 16) + (4 * 32 + 4 * 32) * sizeof(float);
+    const size_t lds = (size_t)2 * kSlabTile * (D_QK * 2 + kSlabPad) + 2 * 32 * (kSlabTile * 2 + 16) + (4 * 32 + 4 * 32) * sizeof(float);
     const bool pg = a.pv.seq_lens || a.pv.page_table;
     if (a.n_splits > 1) return pg ? launch_slab_t<D_QK, D_V, true, true>(a, lds, st) : launch_slab_t<D_QK, D_V, false, true>(a, lds, st);
     return pg ? launch_slab_t<D_QK, D_V, true, false>(a, lds, st) : launch_slab_t<D_QK, D_V, false, false>(a, lds, st);
