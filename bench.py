@@ -167,6 +167,10 @@ def kernel_table(alg, prof, n_full, n_layers, traffic, workload, fp8):
         t = traffic.get((name, workload))
         if t is not None:
             v["traffic"] = t
+            # what the HBM side of L2 moved per second for this kernel (profiler counters of a tracked run over this
+            # kernel's time in THIS run): near the chip's stream rate means the kernel waits for memory beyond L2
+            v["traffic_GBs"] = t / (v["ms_per_layer"] * 1e-3) / 1e9
+            v["traffic_frac_of_hbm_peak"] = v["traffic_GBs"] / HBM_PEAK_GBS
     return k
 
 
