@@ -639,6 +639,15 @@ def main():
         ms4_all = time_steps(lambda: s4.step(m4_all), 1, 0)
         prof4 = profile_pass(ic, s4, m4_14)
         k4 = kernel_table(alg4, prof4, sum(m4_14), n4, traffic, "prefill131k_fp8", fp8=True)
+        # the rows the last Full layer really selects out of its 151 MB cache, fetched with no compute attached (the
+        # index tensor left by the profiled step is that layer's)
+        l_last = max(l for l in range(n4) if m4_14[l])
+        flat4 = s4.idx_cache.reshape(-1)
+        scratch4 = torch.empty((1 << 16,), dtype=torch.int32, device="cuda")
+        ms_g4 = event_ms(lambda: ic.calibrate(ic.CALIB_GATHER, s4.layers[l_last]["KV"], scratch4, idx=flat4, n=flat4.numel(),
+                                              table_rows=c4["Lk"], row_bytes=1152, wgs=512), reps=2, warmup=1)
+        k4["sparse_attn"]["gather_only_ms"] = ms_g4
+        k4["sparse_attn"]["frac_of_gather_only"] = ms_g4 / k4["sparse_attn"]["ms_per_layer"]
         arms["prefill_fp8_131k"] = {
             "workload": "configs[4]: 1 sequence, L=131072, %d layers, H_I=64 d_I=128 e4m3 q/k with per-token scales, k=2048, "
                         "MQA 32 heads, KV row 576 bf16; every layer has its own KV and indexer inputs, Q cycles over %d tensors "
