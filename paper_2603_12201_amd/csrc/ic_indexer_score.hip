@@ -464,10 +464,10 @@ __global__ void fill_kernel(float *p, int64_t n, float v)
 // same piece for all lanes) spread over all banks.  The q rows of a token (32 heads x 256 B = one slot per head
 // tile) travel through the same ring as items of their own, ahead of the token's keys.
 // Order.  Reading the cache as a few wide windows that slide is faster than many narrow streams (measured: 32
-// concurrent per-token windows 100 us, 8 windows 90 us, one window 87 us for 537 MB).  So the G = 8 tokens in
-// flight each belong to the workgroups of one residue mod 8 (one XCD: workgroup ids are dealt round-robin over
-// the eight XCDs); all waves of those workgroups interleave slot by slot over the token's keys, then move to the
-// token G further on together.
+// concurrent per-token windows 100 us, 8 windows 90 us, one window 87 us for 537 MB).  So only G tokens are in
+// flight, each with the workgroups of one residue mod G (for G = 8 that is one XCD: workgroup ids are dealt
+// round-robin over the eight XCDs; the kernel itself is a little faster with G = 16, two tokens per XCD); all waves
+// of those workgroups interleave slot by slot over the token's keys, then move to the token G further on together.
 // ---------------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void dma_lanes(const void *lane_addr, unsigned lds_addr /*uniform*/)
 {
@@ -659,7 +659,7 @@ hipError_t launch_stream(const ScoreArgs &a, int Bc, hipStream_t st)
 {
     const int T = Bc * a.Ri;                    // tokens of the launch
     if (T <= 0) return hipSuccess;
-    const int G = T < 8 ? T : 8;                // tokens in flight
+    const int G = T < 16 ? T : 16;              // tokens in flight (measured at 32 tokens: 2 -> 99.2, 4 -> 97.7, 8 -> 98.4, 16 -> 97.1, 32 -> 102.1 us)
     const int W = G * (256 / G);                // one workgroup per CU (the ring takes most of a CU's LDS)
     constexpr int lds = NW * R * 32 * 256;
     static hipError_t attr = hipFuncSetAttribute((const void *)score_stream_kernel<HT, NW, R, false>,
