@@ -309,6 +309,20 @@ def calibration(ic, synth, idx_prefill, kv_rows):
         tf = flop * 4 * rounds * 4 * wgs / (ms * 1e-3) / 1e12
         out[name] = {"TFLOPs": tf, "frac_of_published_peak": tf / peak, "waves_per_simd": 2,
                      "note": "constant operands; under random operands the shader clock settles lower"}
+    # LDS access patterns of the attention tile, nothing else running: time per 64-lane instruction and CU
+    lds = {}
+    for kind, name, nbytes in ((ic.CALIB_LDS_READ16_PADDED, "read16_rows_1184_apart", 1024),
+                               (ic.CALIB_LDS_READ16_SWIZZLED, "read16_rows_1152_apart_xor_swizzled", 1024),
+                               (ic.CALIB_LDS_TR8_ROWS2, "transpose_read8_rows_two_apart", 512),
+                               (ic.CALIB_LDS_TR8_ROWS1, "transpose_read8_consecutive_rows", 512)):
+        rounds, wgs = 4000, 256
+        ms = event_ms(lambda: ic.calibrate(kind, None, scratch, n=rounds, wgs=wgs), reps=3, warmup=1)
+        ns = ms * 1e6 / (rounds * 16 * 16)                  # 16 reads per round and wave, 16 waves per CU
+        lds[name] = {"ns_per_instruction_per_cu": ns, "bytes_per_ns_per_cu": nbytes / ns}
+    lds["note"] = ("16 waves per CU issue nothing but one kind of LDS read (the LDS fill at kernel start and the launch are in the "
+                   "figure: a few per cent); the first and the third are the patterns of the attention tile as it is laid out, "
+                   "the second is the layout it had before, the fourth what its transpose reads would cost over consecutive rows")
+    out["lds_access_patterns"] = lds
     return out
 
 

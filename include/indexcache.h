@@ -367,12 +367,18 @@ uint64_t ic_debug_indexer_launch_count(void);
  *                       _8WAVES moves exactly the bytes of _READ2 with eight waves per workgroup instead of four
  *                       (wgs then counts workgroups of 512 threads); _INTERLEAVED moves them with four waves and
  *                       the stores and gathers spread between the reads instead of in a phase of their own
+ *   IC_CALIB_LDS_*      n rounds of 16 LDS reads per wave in one access pattern of the attention tile, no global memory
+ *                       (src, idx unused; wgs counts workgroups of 1024 threads; dst as for READ): _READ16_PADDED the
+ *                       16-byte score-operand read of 16 rows 1184 bytes apart, _READ16_SWIZZLED the same with rows 1152
+ *                       bytes apart and XOR-swizzled slots, _TR8_ROWS2 / _TR8_ROWS1 the 8-byte transposing read over
+ *                       four rows two apart / four consecutive rows (rows 1184 apart)
  * wgs = workgroups of 256 threads to launch (1 .. 2^20).  All pointers are device pointers owned by the
  * caller; nothing is allocated.  Errors: IC_ERR_NULL, IC_ERR_SHAPE, IC_ERR_UNSUPPORTED (row_bytes), IC_ERR_HIP.
  */
 enum { IC_CALIB_READ = 0, IC_CALIB_COPY = 1, IC_CALIB_GATHER = 2, IC_CALIB_MFMA_BF16 = 3, IC_CALIB_MFMA_FP8 = 4,
        IC_CALIB_TILE_GATHER = 5, IC_CALIB_TILE_STORE = 6, IC_CALIB_TILE_READ = 7, IC_CALIB_TILE_READ2 = 8,
-       IC_CALIB_TILE_8WAVES = 9, IC_CALIB_TILE_INTERLEAVED = 10 };
+       IC_CALIB_TILE_8WAVES = 9, IC_CALIB_TILE_INTERLEAVED = 10,
+       IC_CALIB_LDS_READ16_PADDED = 11, IC_CALIB_LDS_READ16_SWIZZLED = 12, IC_CALIB_LDS_TR8_ROWS2 = 13, IC_CALIB_LDS_TR8_ROWS1 = 14 };
 ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows,
                        int32_t row_bytes, int32_t wgs, void *stream);
 

@@ -18,5 +18,6 @@ from .binding import (  # noqa: F401
     prof_enable, prof_collect, prof_get, prof_reset,
     calibrate, CALIB_READ, CALIB_COPY, CALIB_GATHER, CALIB_MFMA_BF16, CALIB_MFMA_FP8,
     CALIB_TILE_GATHER, CALIB_TILE_STORE, CALIB_TILE_READ, CALIB_TILE_READ2, CALIB_TILE_8WAVES, CALIB_TILE_INTERLEAVED,
+    CALIB_LDS_READ16_PADDED, CALIB_LDS_READ16_SWIZZLED, CALIB_LDS_TR8_ROWS2, CALIB_LDS_TR8_ROWS1,
     IndexerDesc, AttnDesc, Layer, PagedCache,
 )

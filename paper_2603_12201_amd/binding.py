@@ -239,6 +239,7 @@ def sparse_attn(Q, KV, idx, d_v, v_off, sm_scale, want_lse=False, workspace=None
 
 CALIB_READ, CALIB_COPY, CALIB_GATHER, CALIB_MFMA_BF16, CALIB_MFMA_FP8 = range(5)
 CALIB_TILE_GATHER, CALIB_TILE_STORE, CALIB_TILE_READ, CALIB_TILE_READ2, CALIB_TILE_8WAVES, CALIB_TILE_INTERLEAVED = range(5, 11)
+CALIB_LDS_READ16_PADDED, CALIB_LDS_READ16_SWIZZLED, CALIB_LDS_TR8_ROWS2, CALIB_LDS_TR8_ROWS1 = range(11, 15)
 
 
 def calibrate(kind, src, dst, idx=None, n=0, table_rows=0, row_bytes=0, wgs=2048, stream=None):

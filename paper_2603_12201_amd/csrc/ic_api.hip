@@ -950,7 +950,7 @@ uint64_t ic_debug_indexer_launch_count(void) { return g_indexer_launches.load();
 ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows,
                        int32_t row_bytes, int32_t wgs, void *stream)
 {
-    if (kind < IC_CALIB_READ || kind > IC_CALIB_TILE_INTERLEAVED) return fail(IC_ERR_SHAPE, "unknown calibration kind %d", kind);
+    if (kind < IC_CALIB_READ || kind > IC_CALIB_LDS_TR8_ROWS1) return fail(IC_ERR_SHAPE, "unknown calibration kind %d", kind);
     if (!dst) return fail(IC_ERR_NULL, "dst must not be NULL");
     if (wgs < 1 || wgs > (1 << 20)) return fail(IC_ERR_SHAPE, "wgs=%d outside [1, 2^20]", wgs);
     if (n < 0) return fail(IC_ERR_SHAPE, "n must not be negative");
@@ -961,6 +961,8 @@ ic_status ic_calibrate(int32_t kind, const void *src, void *dst, const int32_t *
         if (!src || !idx) return fail(IC_ERR_NULL, "src and idx must not be NULL");
         if (table_rows < 1) return fail(IC_ERR_SHAPE, "table_rows must be positive");
         if (row_bytes != 1152 && row_bytes != 256) return fail(IC_ERR_UNSUPPORTED, "row_bytes=%d (1152 or 256)", row_bytes);
+    } else if (kind >= IC_CALIB_LDS_READ16_PADDED) {
+        if (n > INT32_MAX) return fail(IC_ERR_SHAPE, "too many rounds");
     } else if (kind >= IC_CALIB_TILE_GATHER) {
         if (!src || !idx) return fail(IC_ERR_NULL, "src and idx must not be NULL");
         if (table_rows < 1) return fail(IC_ERR_SHAPE, "table_rows must be positive");

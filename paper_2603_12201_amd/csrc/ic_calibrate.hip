@@ -371,6 +371,60 @@ __global__ __launch_bounds__(256, 1) void calib_tilepath_il_kernel(const unsigne
     if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
 }
 
+// LDS access patterns of the attention tile by themselves: 16 waves per workgroup (one workgroup per CU keeps the
+// LDS unit busy from every SIMD) issue `rounds` x 16 reads of one kind and fold what they read.  PATTERN 0: the
+// 16-byte score-operand read (lane = row within 16, 16-byte piece lane / 16) with rows 1184 bytes apart, no
+// swizzle; 1: the same read with rows 1152 bytes apart and the 16-byte slot XOR-swizzled by the row number; 2: the
+// 8-byte transposing read over four rows TWO apart, rows 1184 apart; 3: the same over four consecutive rows.
+template <int PATTERN>
+__global__ __launch_bounds__(1024, 1) void calib_lds_kernel(int rounds, uint32_t *out)
+{
+    constexpr int kBytes = 96 * 1024;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int i = tid; i < kBytes / 4; i += 1024) ((uint32_t *)smem)[i] = (uint32_t)i * 2654435761u;
+    __syncthreads();
+    const int l16 = lane & 15, g = lane >> 4, hh = lane >> 5;
+    int off;
+    if (PATTERN == 0) {
+        off = l16 * 1184 + (g << 4);
+    } else if (PATTERN == 1) {
+        off = l16 * 1152 + ((g ^ (((l16 & 3) << 1) | ((l16 >> 2) & 1))) << 4);
+    } else {
+        const int row = 8 * hh + (PATTERN == 2 ? 2 : 1) * (l16 >> 2);
+        off = row * 1184 + ((2 * (g & 1) + ((l16 & 3) >> 1)) << 4) + 8 * (l16 & 1);
+    }
+    typedef __attribute__((address_space(3))) unsigned char lds_u8;
+    const lds_u8 *p = (const lds_u8 *)smem + off;         // + 15 * 4608 + 16 stays below kBytes for every pattern
+    uint32_t acc = 0;
+    for (int r = 0; r < rounds; ++r) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const lds_u8 *q = p + u * 4608;               // four rows of 1152 further: the same banks
+            if (PATTERN <= 1) {
+                const u32x4 v = *(const volatile __attribute__((address_space(3))) u32x4 *)q;
+                acc ^= v[0] ^ v[3];
+            } else {
+                const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)q);
+                acc ^= (uint32_t)(uint16_t)v[0] ^ (uint32_t)(uint16_t)v[3];
+                asm volatile("" ::"v"(v));
+            }
+        }
+    }
+    if (acc == 0x9e3779b9u) out[blockIdx.x] = acc;
+}
+
+template <int PATTERN>
+hipError_t launch_lds(void *dst, int64_t rounds, int wgs, hipStream_t st)
+{
+    constexpr int lds = 96 * 1024;
+    static hipError_t attr = hipFuncSetAttribute((const void *)calib_lds_kernel<PATTERN>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    hipLaunchKernelGGL((calib_lds_kernel<PATTERN>), dim3((unsigned)wgs), dim3(1024), lds, st, (int)rounds, (uint32_t *)dst);
+    return hipGetLastError();
+}
+
 template <int PARTS>
 hipError_t launch_tilepath(const void *src, void *dst, const int32_t *idx, int64_t n, int64_t table_rows, int wgs, hipStream_t st)
 {
@@ -431,6 +485,14 @@ hipError_t launch_calib(int kind, const void *src, void *dst, const int32_t *idx
         hipLaunchKernelGGL(calib_tilepath8_kernel, grid, dim3(512), lds, st, (const unsigned char *)src, idx, n, table_rows, (uint32_t *)dst);
         break;
     }
+    case IC_CALIB_LDS_READ16_PADDED:
+        return launch_lds<0>(dst, n, wgs, st);
+    case IC_CALIB_LDS_READ16_SWIZZLED:
+        return launch_lds<1>(dst, n, wgs, st);
+    case IC_CALIB_LDS_TR8_ROWS2:
+        return launch_lds<2>(dst, n, wgs, st);
+    case IC_CALIB_LDS_TR8_ROWS1:
+        return launch_lds<3>(dst, n, wgs, st);
     default:
         return hipErrorInvalidValue;
     }

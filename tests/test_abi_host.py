@@ -368,6 +368,8 @@ def test_calibrate_argument_errors_need_no_gpu(ic):
         assert L.ic_calibrate(kind, one, one, one, 100, 10, 1152, 1, None) == S.ERR_SHAPE        # whole tiles of 64 rows
         assert L.ic_calibrate(kind, one, one, one, 64, 10, 256, 1, None) == S.ERR_UNSUPPORTED
     assert L.ic_calibrate(ic.CALIB_MFMA_BF16, None, one, None, 1 << 40, 0, 0, 1, None) == S.ERR_SHAPE
+    assert L.ic_calibrate(ic.CALIB_LDS_TR8_ROWS1, None, one, None, 1 << 40, 0, 0, 1, None) == S.ERR_SHAPE
+    assert L.ic_calibrate(ic.CALIB_LDS_TR8_ROWS1 + 1, None, one, None, 1, 0, 0, 1, None) == S.ERR_SHAPE   # unknown kind
 
 
 def test_bench_refuses_more_than_one_gpu():

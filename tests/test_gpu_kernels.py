@@ -459,7 +459,8 @@ def test_calibration_kernels_run_on_small_inputs(ic):
     for kind in (ic.CALIB_GATHER, ic.CALIB_TILE_GATHER, ic.CALIB_TILE_STORE, ic.CALIB_TILE_READ, ic.CALIB_TILE_READ2,
                  ic.CALIB_TILE_8WAVES, ic.CALIB_TILE_INTERLEAVED):
         ic.calibrate(kind, table, scratch, idx=rows, n=rows.numel(), table_rows=table.shape[0], row_bytes=1152, wgs=4)
-    for kind in (ic.CALIB_MFMA_BF16, ic.CALIB_MFMA_FP8):
+    for kind in (ic.CALIB_MFMA_BF16, ic.CALIB_MFMA_FP8, ic.CALIB_LDS_READ16_PADDED, ic.CALIB_LDS_READ16_SWIZZLED,
+                 ic.CALIB_LDS_TR8_ROWS2, ic.CALIB_LDS_TR8_ROWS1):
         ic.calibrate(kind, None, scratch, n=10, wgs=4)
     torch.cuda.synchronize()
     assert int(scratch.sum().item()) == 0          # the "rarely written" outputs were not written
